@@ -1,0 +1,171 @@
+/*
+ * multi_lora.h -- C ABI of the fused multi-LoRA linear layer for AMD MI355X (gfx950).
+ *
+ * Many LoRA jobs share one frozen weight W.  All jobs' tokens sit in one flat
+ * activation buffer X[T,k]; adapter i owns the contiguous row segment
+ * [seg_offsets[i], seg_offsets[i+1]) and has its own rank r_i, scale s_i and
+ * matrices A_i[k,r_i], B_i[r_i,n]  (paper Sec. 2.1 for the LoRA branch Y = XW + XAB,
+ * Sec. 5.1 for the grouped forward/backward, App. A.1 for the flat token buffer with
+ * per-adapter offsets, the (adapter, block) schedule table and rank masking).
+ *
+ *   forward    S_i  = X_i A_i                       [T_i, r_i]   (cached for backward)
+ *              Y_i  = X_i W + s_i S_i B_i           [T_i, n]
+ *   backward   dS_i = s_i dY_i B_i^T                [T_i, r_i]
+ *              dX_i = dY_i W^T + dS_i A_i^T         [T_i, k]
+ *              dA_i = X_i^T dS_i                    [k, r_i]
+ *              dB_i = s_i S_i^T dY_i                [r_i, n]     (W is frozen: no dW)
+ *
+ * Layout: every matrix is dense row-major.  W is [k,n] (the paper's orientation, not
+ * torch's [out,in]).  S and dS are ragged: S_i starts at element sum_{j<i} T_j r_j and
+ * is [T_i, r_i] dense.  dtype is one of MLORA_F32 / MLORA_BF16 for all tensors;
+ * accumulation is always fp32 and each output is rounded once from the accumulator.
+ *
+ * Pointers: "device" = device memory the caller owns (for example torch tensors),
+ * "host" = ordinary host memory read during the call and free to reuse once the call
+ * returns.  `stream` is a hipStream_t passed as void* (NULL = the null stream).
+ * Every call only enqueues work on `stream`; none of them synchronises the device.
+ * A plan and its workspace may be in use on one stream at a time.
+ *
+ * Errors: every entry point returns MLORA_OK (0) or a negative mlora_status; argument
+ * checks happen before any GPU call, nothing is thrown or aborted, and
+ * multi_lora_last_error() returns a thread-local description of the last failure.
+ */
+#ifndef MULTI_LORA_H_
+#define MULTI_LORA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct mlora_plan mlora_plan; /* opaque, library-owned */
+
+typedef enum { MLORA_F32 = 0, MLORA_BF16 = 1 } mlora_dtype;
+
+typedef enum {
+    MLORA_OK = 0,
+    MLORA_ERR_NULL = -1,      /* a required pointer is NULL */
+    MLORA_ERR_SHAPE = -2,     /* T, k, n or N out of range */
+    MLORA_ERR_SEGMENTS = -3,  /* offsets do not start at 0, decrease, or do not end at T */
+    MLORA_ERR_RANK = -4,      /* a rank is outside [0, MLORA_MAX_RANK] */
+    MLORA_ERR_DTYPE = -5,
+    MLORA_ERR_ALIGN = -6,     /* a device pointer is not 16-byte aligned */
+    MLORA_ERR_WORKSPACE = -7, /* workspace NULL although multi_lora_workspace_bytes() > 0 */
+    MLORA_ERR_HIP = -8,       /* a HIP runtime call failed; see multi_lora_last_error() */
+    MLORA_ERR_FLAGS = -9,     /* unknown or contradictory flag bits */
+    MLORA_ERR_SCALE = -10     /* a scale is NaN or infinite */
+} mlora_status;
+
+#define MLORA_MAX_RANK 128      /* App. A.1: ranks are small, typically r <= 128 */
+#define MLORA_MAX_ADAPTERS 4096
+
+/* flags of multi_lora_fwd / multi_lora_bwd */
+#define MLORA_FLAG_BASE_ONLY 1u /* skip every LoRA term: Y = X W, dX = dY W^T; S, dA, dB untouched */
+#define MLORA_FLAG_LORA_ONLY 2u /* skip W: fwd Y += s S B in place (Y holds Y_base on entry, the
+                                   paper's decoupled "fused GEMM-add", Sec. 5.1 / App. A.1);
+                                   bwd dX += dS A^T in place; S, dA, dB as usual */
+
+/* which table multi_lora_plan_dump copies out */
+typedef enum {
+    MLORA_TABLE_ROW_BLOCKS = 0, /* LoRA block table, 4 x int32 per entry:
+                                   adapter, block index within the adapter, first global row, rows.
+                                   App. A.1 schedule table; order: adapter ascending, block ascending;
+                                   adapters with T_i = 0 or r_i = 0 have no entries. */
+    MLORA_TABLE_GEMM_ROW_TILES = 1, /* row tiles of the flat buffer used by the fused GEMMs,
+                                   4 x int32 per entry: first row, rows, first adapter touched,
+                                   last adapter touched + 1. */
+    MLORA_TABLE_WGRAD_CHUNKS = 2 /* token chunks reduced by the weight-gradient kernels, 4 x int32:
+                                   adapter, chunk index within the adapter, first global row, rows. */
+} mlora_table;
+
+/* geometry words returned by multi_lora_plan_geometry */
+enum {
+    MLORA_GEO_BLOCK_ROWS = 0,     /* rows per LoRA block (MLORA_TABLE_ROW_BLOCKS) */
+    MLORA_GEO_GEMM_TILE_ROWS = 1, /* rows per fused-GEMM row tile */
+    MLORA_GEO_GEMM_TILE_COLS = 2,
+    MLORA_GEO_WGRAD_CHUNK_ROWS = 3,
+    MLORA_GEO_R1_LO = 4,          /* sum_i T_i r_i, low and high 31 bits */
+    MLORA_GEO_R1_HI = 5,
+    MLORA_GEO_USES_MFMA = 6,      /* 1 if the bf16 MFMA kernels serve this plan, 0 for the fp32-FMA kernels */
+    MLORA_GEO_COUNT = 8
+};
+
+/*
+ * Build the per-segmentation plan (App. A.1: the schedule table is built once per step
+ * from the per-adapter offsets and shared by every layer).  Validates the arguments,
+ * allocates the small device tables and builds them with a device kernel on `stream`.
+ *   out          host, receives the plan
+ *   T, k, n      token count (>= 0), input width (>= 1), output width (>= 1)
+ *   N            number of adapters, 0..MLORA_MAX_ADAPTERS (0 = plain X W)
+ *   ranks        host [N], each in [0, MLORA_MAX_RANK]; rank 0 = rows pass through as X W
+ *   scales       host [N], finite
+ *   seg_offsets  host [N+1], seg_offsets[0] = 0, non-decreasing, seg_offsets[N] = T
+ * The only entry point that allocates device memory; freed by multi_lora_plan_destroy.
+ */
+int multi_lora_plan_create(mlora_plan** out, int dtype, int64_t T, int64_t k, int64_t n,
+                           int32_t N, const int32_t* ranks, const float* scales,
+                           const int64_t* seg_offsets, void* stream);
+
+/* Frees the plan's device tables (synchronises with nothing: destroy a plan only after
+ * the work that uses it has finished).  NULL is accepted. */
+int multi_lora_plan_destroy(mlora_plan* plan);
+
+/* Argument validation alone, with the same status codes as multi_lora_plan_create and
+ * without touching the GPU. */
+int multi_lora_validate(int dtype, int64_t T, int64_t k, int64_t n, int32_t N,
+                        const int32_t* ranks, const float* scales, const int64_t* seg_offsets);
+
+/* Bytes of caller-allocated device workspace multi_lora_fwd / multi_lora_bwd need
+ * (fp32 partial sums of the weight gradients and the dS buffer).  0 is possible. */
+size_t multi_lora_workspace_bytes(const mlora_plan* plan);
+
+/* Copies MLORA_GEO_COUNT int32 words describing the plan's tiling into `out` (host). */
+int multi_lora_plan_geometry(const mlora_plan* plan, int32_t* out);
+
+/* Copies a device-built table back to the host for bit-exact bookkeeping checks.
+ * `entries` (host) receives up to `cap` entries of 4 int32 each; `count` (host) the
+ * number of entries the table holds.  Synchronises the plan's build stream. */
+int multi_lora_plan_dump(const mlora_plan* plan, int which, int32_t* entries, int64_t cap,
+                         int64_t* count);
+
+/*
+ * Forward (Sec. 5.1: base GEMM, grouped shrink, fused expand-add; here the expand is
+ * folded into the base GEMM's accumulator so Y is written exactly once).
+ *   X  device [T,k]        W  device [k,n]
+ *   A  host array of N device pointers, A_i [k,r_i]   (entries with r_i = 0 are ignored)
+ *   B  host array of N device pointers, B_i [r_i,n]
+ *   Y  device [T,n] out (in/out with MLORA_FLAG_LORA_ONLY)
+ *   S  device ragged [sum T_i r_i] out, unscaled X_i A_i
+ *   workspace  device, multi_lora_workspace_bytes(plan) bytes
+ */
+int multi_lora_fwd(mlora_plan* plan, const void* X, const void* W, const void* const* A,
+                   const void* const* B, void* Y, void* S, void* workspace, uint32_t flags,
+                   void* stream);
+
+/*
+ * Backward (Sec. 5.1: grouped input gradients dS, dX; grouped weight gradients dA, dB
+ * reduced over each adapter's tokens; W frozen).  All outputs are overwritten.
+ *   dY device [T,n]   X device [T,k]   W device [k,n]   S device ragged, from forward
+ *   A, B   host arrays of N device pointers as in forward
+ *   dX device [T,k] out (in/out with MLORA_FLAG_LORA_ONLY)
+ *   dA host array of N device pointers, dA_i [k,r_i] out
+ *   dB host array of N device pointers, dB_i [r_i,n] out
+ * dS is kept in the workspace (first sum T_i r_i elements of the plan dtype).
+ */
+int multi_lora_bwd(mlora_plan* plan, const void* dY, const void* X, const void* W,
+                   const void* const* A, const void* const* B, const void* S, void* dX,
+                   void* const* dA, void* const* dB, void* workspace, uint32_t flags,
+                   void* stream);
+
+/* Thread-local text of the last error returned on this thread ("" if none). */
+const char* multi_lora_last_error(void);
+
+/* Library version, "major.minor". */
+const char* multi_lora_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MULTI_LORA_H_ */
