@@ -121,14 +121,17 @@ def owner_of_rows(offsets: Sequence[int], rows: np.ndarray) -> np.ndarray:
     return (np.searchsorted(off, rows, side="right") - 1).astype(np.int64)
 
 
-def shrink(X, A, offsets) -> List[np.ndarray]:
-    """S_i = X_i A_i for every adapter (paper Sec. 5.1)."""
+def shrink(X, A, offsets, adapters=None) -> List[Optional[np.ndarray]]:
+    """S_i = X_i A_i for every adapter, or only for those listed (others None) (paper Sec. 5.1)."""
     lib = _load()
     X = _f32(X)
     T, k = X.shape
     off = _check_segments(T, offsets)
     out = []
     for i, Ai in enumerate(A):
+        if adapters is not None and i not in adapters:
+            out.append(None)
+            continue
         Ai = _f32(Ai)
         r = Ai.shape[1] if Ai.ndim == 2 else 0
         Ti = int(off[i + 1] - off[i])
@@ -140,21 +143,24 @@ def shrink(X, A, offsets) -> List[np.ndarray]:
     return out
 
 
-def forward(X, W, A, B, scales, offsets, rows=None, cols=None, want_base=False) -> Forward:
-    """Y = X W + s_i (X_i A_i) B_i on the requested global rows / columns (default: all)."""
+def forward(X, W, A, B, scales, offsets, rows=None, cols=None, want_base=False, adapters=None) -> Forward:
+    """Y = X W + s_i (X_i A_i) B_i on the requested global rows / columns (default: all).
+    With ``adapters`` given, S_i is computed only for those adapters and for the owners of the
+    requested rows (the others are None)."""
     lib = _load()
     X, W = _f32(X), _f32(W)
     T, k = X.shape
     n = W.shape[1]
     assert W.shape[0] == k
     off = _check_segments(T, offsets)
-    S = shrink(X, A, off)
     rows_a = np.arange(T, dtype=np.int64) if rows is None else _idx(rows)
     cols_a = _idx(cols)
     nc = n if cols_a is None else cols_a.size
+    own = owner_of_rows(off, rows_a)
+    need = None if adapters is None else set(int(a) for a in adapters) | set(int(o) for o in own)
+    S = shrink(X, A, off, need)
     Y = np.zeros((rows_a.size, nc), dtype=np.float64)
     Yb = np.zeros_like(Y) if want_base else None
-    own = owner_of_rows(off, rows_a)
     for i in range(len(A)):
         sel = np.nonzero(own == i)[0]
         if sel.size == 0:
@@ -175,19 +181,26 @@ def forward(X, W, A, B, scales, offsets, rows=None, cols=None, want_base=False) 
 
 def backward(dY, X, W, A, B, scales, offsets, S=None, rows=None, cols=None,
              a_rows=None, b_cols=None, adapters=None) -> Backward:
-    """dX on the requested rows/cols, dS in full, dA_i / dB_i for the listed adapters
-    (default all), optionally only rows ``a_rows`` of dA_i and columns ``b_cols`` of dB_i.
+    """dX on the requested rows/cols; dA_i / dB_i for the listed adapters (default all),
+    optionally only rows ``a_rows`` of dA_i and columns ``b_cols`` of dB_i; dS_i for all
+    adapters, or with ``adapters`` given only for those and for the owners of the requested rows.
     ``S`` defaults to the oracle's own unrounded X_i A_i."""
     lib = _load()
     dY, X, W = _f32(dY), _f32(X), _f32(W)
     T, k = X.shape
     n = W.shape[1]
     off = _check_segments(T, offsets)
-    if S is None:
-        S = shrink(X, A, off)
     N = len(A)
+    rows_a = np.arange(T, dtype=np.int64) if rows is None else _idx(rows)
+    own = owner_of_rows(off, rows_a)
+    need = None if adapters is None else set(int(a) for a in adapters) | set(int(o) for o in own)
+    if S is None:
+        S = shrink(X, A, off, need)
     dS = []
     for i in range(N):
+        if need is not None and i not in need:
+            dS.append(None)
+            continue
         Bi = _f32(B[i])
         r = S[i].shape[1]
         Ti = int(off[i + 1] - off[i])
@@ -195,11 +208,9 @@ def backward(dY, X, W, A, B, scales, offsets, S=None, rows=None, cols=None,
         if Ti and r:
             lib.mlo_dshrink(Ti, n, r, float(scales[i]), _ptr(dY[off[i]:off[i + 1]]), n, _ptr(Bi), _ptr(d))
         dS.append(d)
-    rows_a = np.arange(T, dtype=np.int64) if rows is None else _idx(rows)
     cols_a = _idx(cols)
     nc = k if cols_a is None else cols_a.size
     dX = np.zeros((rows_a.size, nc), dtype=np.float64)
-    own = owner_of_rows(off, rows_a)
     for i in range(N):
         sel = np.nonzero(own == i)[0]
         if sel.size == 0:

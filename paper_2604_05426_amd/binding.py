@@ -1,0 +1,175 @@
+"""ctypes front end of libmultilora.so: the same entry points as ``include/multi_lora.h``.
+
+Argument marshalling only -- every step of the layer runs in the HIP kernels.  Tensors are
+passed as anything with ``data_ptr()`` (torch tensors) or as raw integer addresses; torch is
+used by callers for device memory and streams, never for compute.  Loading fails loudly if
+the shared library has not been built (``python -m paper_2604_05426_amd.build``).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence
+
+F32, BF16 = 0, 1
+FLAG_BASE_ONLY, FLAG_LORA_ONLY = 1, 2
+TABLE_ROW_BLOCKS, TABLE_GEMM_ROW_TILES, TABLE_WGRAD_CHUNKS = 0, 1, 2
+GEO_BLOCK_ROWS, GEO_GEMM_TILE_ROWS, GEO_GEMM_TILE_COLS, GEO_WGRAD_CHUNK_ROWS = 0, 1, 2, 3
+GEO_R1_LO, GEO_R1_HI, GEO_USES_MFMA, GEO_COUNT = 4, 5, 6, 8
+MAX_RANK, MAX_ADAPTERS = 128, 4096
+
+STATUS_NAMES = {0: "MLORA_OK", -1: "MLORA_ERR_NULL", -2: "MLORA_ERR_SHAPE", -3: "MLORA_ERR_SEGMENTS",
+                -4: "MLORA_ERR_RANK", -5: "MLORA_ERR_DTYPE", -6: "MLORA_ERR_ALIGN",
+                -7: "MLORA_ERR_WORKSPACE", -8: "MLORA_ERR_HIP", -9: "MLORA_ERR_FLAGS",
+                -10: "MLORA_ERR_SCALE"}
+
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmultilora.so")
+
+# every symbol include/multi_lora.h declares
+EXPORTS = ["multi_lora_plan_create", "multi_lora_plan_destroy", "multi_lora_validate",
+           "multi_lora_workspace_bytes", "multi_lora_plan_geometry", "multi_lora_plan_dump",
+           "multi_lora_fwd", "multi_lora_bwd", "multi_lora_last_error", "multi_lora_version"]
+
+
+class MultiLoraError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{STATUS_NAMES.get(status, status)}: {message}")
+        self.status = status
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded shared library (raises if it has not been built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2604_05426_amd.build`; "
+                              "there is no fallback path")
+        L = ctypes.CDLL(LIB_PATH)
+        i32, i64, vp, u32 = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p, ctypes.c_uint32
+        L.multi_lora_plan_create.argtypes = [ctypes.POINTER(vp), ctypes.c_int, i64, i64, i64, i32, vp, vp, vp, vp]
+        L.multi_lora_plan_create.restype = ctypes.c_int
+        L.multi_lora_plan_destroy.argtypes = [vp]
+        L.multi_lora_plan_destroy.restype = ctypes.c_int
+        L.multi_lora_validate.argtypes = [ctypes.c_int, i64, i64, i64, i32, vp, vp, vp]
+        L.multi_lora_validate.restype = ctypes.c_int
+        L.multi_lora_workspace_bytes.argtypes = [vp]
+        L.multi_lora_workspace_bytes.restype = ctypes.c_size_t
+        L.multi_lora_plan_geometry.argtypes = [vp, vp]
+        L.multi_lora_plan_geometry.restype = ctypes.c_int
+        L.multi_lora_plan_dump.argtypes = [vp, ctypes.c_int, vp, i64, ctypes.POINTER(i64)]
+        L.multi_lora_plan_dump.restype = ctypes.c_int
+        L.multi_lora_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, u32, vp]
+        L.multi_lora_fwd.restype = ctypes.c_int
+        L.multi_lora_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, u32, vp]
+        L.multi_lora_bwd.restype = ctypes.c_int
+        L.multi_lora_last_error.restype = ctypes.c_char_p
+        L.multi_lora_version.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def last_error() -> str:
+    return lib().multi_lora_last_error().decode()
+
+
+def version() -> str:
+    return lib().multi_lora_version().decode()
+
+
+def _check(status: int) -> None:
+    if status != 0:
+        raise MultiLoraError(status, last_error())
+
+
+def _addr(t) -> Optional[int]:
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return int(t.data_ptr())
+
+
+def _ptr_array(items: Optional[Sequence], n: int):
+    if items is None:
+        return None
+    arr = (ctypes.c_void_p * max(n, 1))()
+    for i in range(n):
+        arr[i] = _addr(items[i])
+    return arr
+
+
+def _meta(N, ranks, scales, offsets):
+    r = (ctypes.c_int32 * max(N, 1))(*[int(x) for x in ranks]) if ranks is not None else None
+    s = (ctypes.c_float * max(N, 1))(*[float(x) for x in scales]) if scales is not None else None
+    o = (ctypes.c_int64 * (len(offsets)))(*[int(x) for x in offsets]) if offsets is not None else None
+    return r, s, o
+
+
+def multi_lora_validate(dtype: int, T: int, k: int, n: int, N: int, ranks, scales, offsets) -> int:
+    """Status code of the argument check alone (touches no GPU)."""
+    r, s, o = _meta(N, ranks, scales, offsets)
+    return int(lib().multi_lora_validate(dtype, T, k, n, N, r, s, o))
+
+
+class Plan:
+    """Owns one mlora_plan (multi_lora_plan_create / multi_lora_plan_destroy)."""
+
+    def __init__(self, dtype: int, T: int, k: int, n: int, ranks, scales, offsets, stream: int = 0):
+        self.dtype, self.T, self.k, self.n = dtype, T, k, n
+        self.N = len(ranks)
+        self.ranks, self.scales, self.offsets = list(ranks), list(scales), list(offsets)
+        self._h = ctypes.c_void_p()
+        r, s, o = _meta(self.N, ranks, scales, offsets)
+        _check(lib().multi_lora_plan_create(ctypes.byref(self._h), dtype, T, k, n, self.N, r, s, o,
+                                            ctypes.c_void_p(stream)))
+
+    @property
+    def handle(self):
+        return self._h
+
+    def workspace_bytes(self) -> int:
+        return int(lib().multi_lora_workspace_bytes(self._h))
+
+    def geometry(self) -> List[int]:
+        out = (ctypes.c_int32 * GEO_COUNT)()
+        _check(lib().multi_lora_plan_geometry(self._h, out))
+        return list(out)
+
+    @property
+    def R1(self) -> int:
+        g = self.geometry()
+        return g[GEO_R1_LO] + (g[GEO_R1_HI] << 31)
+
+    def dump(self, table: int) -> List[tuple]:
+        cnt = ctypes.c_int64(0)
+        _check(lib().multi_lora_plan_dump(self._h, table, None, 0, ctypes.byref(cnt)))
+        n = cnt.value
+        buf = (ctypes.c_int32 * (4 * max(n, 1)))()
+        _check(lib().multi_lora_plan_dump(self._h, table, buf, n, ctypes.byref(cnt)))
+        return [tuple(buf[4 * i: 4 * i + 4]) for i in range(n)]
+
+    def destroy(self) -> None:
+        if self._h:
+            _check(lib().multi_lora_plan_destroy(self._h))
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def multi_lora_fwd(plan: Plan, X, W, A: Optional[Sequence], B: Optional[Sequence], Y, S, workspace,
+                   flags: int = 0, stream: int = 0) -> None:
+    _check(lib().multi_lora_fwd(plan.handle, _addr(X), _addr(W), _ptr_array(A, plan.N), _ptr_array(B, plan.N),
+                                _addr(Y), _addr(S), _addr(workspace), flags, ctypes.c_void_p(stream)))
+
+
+def multi_lora_bwd(plan: Plan, dY, X, W, A, B, S, dX, dA, dB, workspace, flags: int = 0, stream: int = 0) -> None:
+    _check(lib().multi_lora_bwd(plan.handle, _addr(dY), _addr(X), _addr(W), _ptr_array(A, plan.N),
+                                _ptr_array(B, plan.N), _addr(S), _addr(dX), _ptr_array(dA, plan.N),
+                                _ptr_array(dB, plan.N), _addr(workspace), flags, ctypes.c_void_p(stream)))

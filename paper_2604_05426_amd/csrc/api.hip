@@ -1,0 +1,115 @@
+// multi_lora_fwd / multi_lora_bwd: argument checks, per-call pointer upload, kernel dispatch.
+#include "common.h"
+
+using namespace mlora;
+
+static inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+static int check_flags(uint32_t flags) {
+    if (flags & ~(MLORA_FLAG_BASE_ONLY | MLORA_FLAG_LORA_ONLY)) {
+        set_error("unknown flag bits");
+        return MLORA_ERR_FLAGS;
+    }
+    if ((flags & MLORA_FLAG_BASE_ONLY) && (flags & MLORA_FLAG_LORA_ONLY)) {
+        set_error("MLORA_FLAG_BASE_ONLY and MLORA_FLAG_LORA_ONLY exclude each other");
+        return MLORA_ERR_FLAGS;
+    }
+    return MLORA_OK;
+}
+
+// every adapter with a rank needs its pointers; all of them 16-byte aligned
+static int check_ptr_array(const mlora_plan* p, const void* const* arr, const char* name) {
+    if (!arr) {
+        set_error(std::string(name) + " is NULL");
+        return MLORA_ERR_NULL;
+    }
+    for (int32_t i = 0; i < p->N; ++i) {
+        if (p->ranks[i] == 0) continue;
+        if (!arr[i]) {
+            set_error(std::string(name) + "[i] is NULL for an adapter with rank > 0");
+            return MLORA_ERR_NULL;
+        }
+        if (misaligned(arr[i])) {
+            set_error(std::string(name) + "[i] is not 16-byte aligned");
+            return MLORA_ERR_ALIGN;
+        }
+    }
+    return MLORA_OK;
+}
+
+extern "C" int multi_lora_fwd(mlora_plan* plan, const void* X, const void* W, const void* const* A,
+                              const void* const* B, void* Y, void* S, void* workspace, uint32_t flags,
+                              void* stream) {
+    (void)workspace;
+    if (!plan) {
+        set_error("plan is NULL");
+        return MLORA_ERR_NULL;
+    }
+    int rc = check_flags(flags);
+    if (rc != MLORA_OK) return rc;
+    const bool lora = !(flags & MLORA_FLAG_BASE_ONLY) && plan->N > 0;
+    const bool base = !(flags & MLORA_FLAG_LORA_ONLY);
+    if (plan->T > 0 && (!X || !Y || (base && !W))) {
+        set_error("X / W / Y is NULL");
+        return MLORA_ERR_NULL;
+    }
+    if (lora && plan->R1 > 0 && !S) {
+        set_error("S is NULL");
+        return MLORA_ERR_NULL;
+    }
+    if (misaligned(X) || misaligned(W) || misaligned(Y) || misaligned(S)) {
+        set_error("X / W / Y / S must be 16-byte aligned");
+        return MLORA_ERR_ALIGN;
+    }
+    if (lora) {
+        if ((rc = check_ptr_array(plan, A, "A")) != MLORA_OK) return rc;
+        if ((rc = check_ptr_array(plan, B, "B")) != MLORA_OK) return rc;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    if (lora && (rc = upload_ptrs(plan, A, B, nullptr, nullptr, st)) != MLORA_OK) return rc;
+    if (plan->use_mfma) return mfma_forward(plan, X, W, Y, S, flags, st);
+    return fma_forward(plan, X, W, Y, S, flags, st);
+}
+
+extern "C" int multi_lora_bwd(mlora_plan* plan, const void* dY, const void* X, const void* W,
+                              const void* const* A, const void* const* B, const void* S, void* dX,
+                              void* const* dA, void* const* dB, void* workspace, uint32_t flags,
+                              void* stream) {
+    if (!plan) {
+        set_error("plan is NULL");
+        return MLORA_ERR_NULL;
+    }
+    int rc = check_flags(flags);
+    if (rc != MLORA_OK) return rc;
+    const bool lora = !(flags & MLORA_FLAG_BASE_ONLY) && plan->N > 0;
+    const bool base = !(flags & MLORA_FLAG_LORA_ONLY);
+    if (plan->T > 0 && (!dY || !dX || (base && !W) || (lora && !X))) {
+        set_error("dY / X / W / dX is NULL");
+        return MLORA_ERR_NULL;
+    }
+    if (lora && plan->R1 > 0 && !S) {
+        set_error("S is NULL");
+        return MLORA_ERR_NULL;
+    }
+    if (misaligned(dY) || misaligned(X) || misaligned(W) || misaligned(S) || misaligned(dX) ||
+        misaligned(workspace)) {
+        set_error("dY / X / W / S / dX / workspace must be 16-byte aligned");
+        return MLORA_ERR_ALIGN;
+    }
+    if (lora) {
+        if (multi_lora_workspace_bytes(plan) > 0 && !workspace) {
+            set_error("workspace is NULL but multi_lora_workspace_bytes(plan) > 0");
+            return MLORA_ERR_WORKSPACE;
+        }
+        if ((rc = check_ptr_array(plan, A, "A")) != MLORA_OK) return rc;
+        if ((rc = check_ptr_array(plan, B, "B")) != MLORA_OK) return rc;
+        if ((rc = check_ptr_array(plan, (const void* const*)dA, "dA")) != MLORA_OK) return rc;
+        if ((rc = check_ptr_array(plan, (const void* const*)dB, "dB")) != MLORA_OK) return rc;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    if (lora && (rc = upload_ptrs(plan, A, B, dA, dB, st)) != MLORA_OK) return rc;
+    void* dS = workspace;
+    float* partials = workspace ? (float*)((char*)workspace + plan->ws_ds_bytes) : nullptr;
+    if (plan->use_mfma) return mfma_backward(plan, dY, X, W, S, dX, dS, partials, flags, st);
+    return fma_backward(plan, dY, X, W, S, dX, dS, flags, st);
+}

@@ -1,0 +1,107 @@
+// Internal declarations shared by the translation units of libmultilora (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "multi_lora.h"
+
+namespace mlora {
+
+// ---- tiling constants (reported through multi_lora_plan_geometry) ------------------
+constexpr int kBlockRows = 64;       // rows per LoRA block of the shrink kernels
+constexpr int kGemmTileRows = 256;   // fused GEMM macro tile
+constexpr int kGemmTileCols = 256;
+constexpr int kWgradChunkRows = 1024; // tokens reduced by one weight-gradient work item
+
+// One entry of any plan table: 4 x int32 (meaning depends on the table).
+struct Entry4 {
+    int32_t a, b, c, d;
+};
+
+// Per-adapter pointers, refreshed by every fwd/bwd call (device resident).
+struct AdapterPtrs {
+    const void* A;
+    const void* B;
+    void* dA;
+    void* dB;
+};
+
+// Device-resident view of a plan, passed by value to kernels.
+struct PlanView {
+    int32_t N;
+    int64_t T, k, n;
+    const int32_t* off;     // [N+1] segment offsets (rows)
+    const int32_t* rank;    // [N]
+    const float* scale;     // [N]
+    const int64_t* soff;    // [N+1] element offsets of S_i / dS_i in the ragged buffers
+    const AdapterPtrs* ptrs; // [N]
+    const Entry4* row_blocks;  int32_t n_row_blocks;
+    const Entry4* gemm_tiles;  int32_t n_gemm_tiles;
+    const Entry4* wgrad_chunks; int32_t n_wgrad_chunks;
+    const int32_t* wgrad_chunk_start; // [N+1] first chunk of each adapter
+};
+
+}  // namespace mlora
+
+struct mlora_plan {
+    int dtype = 0;
+    int64_t T = 0, k = 0, n = 0;
+    int32_t N = 0;
+    std::vector<int32_t> ranks;
+    std::vector<float> scales;
+    std::vector<int64_t> off;
+    std::vector<int64_t> soff;       // N+1
+    std::vector<int32_t> wchunk_start; // N+1
+    std::vector<int32_t> off32;      // N+1, upload source (kept alive for the async copy)
+    std::vector<int64_t> part_off;   // N+1, upload source
+    int64_t R1 = 0;
+    bool use_mfma = false;
+    int32_t n_row_blocks = 0, n_gemm_tiles = 0, n_wgrad_chunks = 0;
+    int32_t max_rank = 0;
+    int32_t max_chunks_per_adapter = 0;
+    // one device allocation carved into the tables below
+    void* d_block = nullptr;
+    size_t d_block_bytes = 0;
+    mlora::PlanView view{};
+    mlora::AdapterPtrs* d_ptrs = nullptr;
+    void* d_probs = nullptr;          // descriptor scratch of the FMA grouped GEMM
+    int64_t* d_part_off = nullptr;    // [N] float offset of each adapter's partial weight-gradient block
+    bool has_empty_ranked = false;    // some adapter has a rank but no tokens (its dA, dB are zero-filled)
+    size_t ws_ds_bytes = 0;           // workspace: dS
+    size_t ws_partial_bytes = 0;      // workspace: fp32 partial weight gradients
+    hipStream_t build_stream = nullptr;
+    int num_cus = 256;
+};
+
+namespace mlora {
+
+void set_error(const std::string& msg);
+int hip_fail(hipError_t e, const char* what);
+
+#define MLORA_HIP_TRY(expr)                                   \
+    do {                                                      \
+        hipError_t e__ = (expr);                              \
+        if (e__ != hipSuccess) return ::mlora::hip_fail(e__, #expr); \
+    } while (0)
+
+// plan.hip
+int upload_ptrs(mlora_plan* p, const void* const* A, const void* const* B, void* const* dA,
+                void* const* dB, hipStream_t st);
+
+// grouped_fma.hip : descriptor-driven grouped GEMM on the vector ALUs (fp32 accumulate)
+int fma_forward(mlora_plan* p, const void* X, const void* W, void* Y, void* S, uint32_t flags,
+                hipStream_t st);
+int fma_backward(mlora_plan* p, const void* dY, const void* X, const void* W, const void* S,
+                 void* dX, void* dS, uint32_t flags, hipStream_t st);
+
+// mfma_*.hip : bf16 MFMA kernels
+int mfma_forward(mlora_plan* p, const void* X, const void* W, void* Y, void* S, uint32_t flags,
+                 hipStream_t st);
+int mfma_backward(mlora_plan* p, const void* dY, const void* X, const void* W, const void* S,
+                  void* dX, void* dS, float* partials, uint32_t flags, hipStream_t st);
+
+}  // namespace mlora

@@ -1,0 +1,82 @@
+// Device helpers shared by the bf16 MFMA kernels (gfx950 / CDNA4, 64-wide wavefronts).
+#pragma once
+
+#include "common.h"
+
+namespace mlora {
+
+typedef uint16_t u16;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float bf2f(u16 v) { return __uint_as_float(((uint32_t)v) << 16); }
+
+// fp32 -> bf16, round to nearest even, NaN preserved
+__device__ __forceinline__ u16 f2bf(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u16)((u >> 16) | 0x40);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (u16)(u >> 16);
+}
+
+__device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+    return (uint32_t)f2bf(lo) | ((uint32_t)f2bf(hi) << 16);
+}
+
+// v_mfma_f32_32x32x16_bf16:  C[32x32] += A[32x16] * B[16x32].
+// Lane l supplies A[row l%32][8*(l/32) .. +7] and B[8*(l/32) .. +7][col l%32];
+// it receives C[(i/4)*8 + (l/32)*4 + i%4][l%32] in c[i], i = 0..15.
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ bf16x8 lds_read_frag(const u16* p) {
+    return *reinterpret_cast<const bf16x8*>(p);
+}
+
+// ds_read_b64_tr_b16: within each group of 16 lanes, lane j supplies the address of 4
+// consecutive 16-bit elements; lanes 4q..4q+3 together name 16 elements of "row" q
+// (q = 0..3), and lane i of the group receives element i of rows 0..3.  Reading a
+// row-major [contraction][column] tile this way hands every lane 4 consecutive
+// contraction values of one column, which is what the MFMA operands want.
+__device__ __forceinline__ s16x4 lds_read_tr(const u16* p) {
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (__attribute__((address_space(3))) s16x4*)(uintptr_t)(uint32_t)(uintptr_t)p);
+}
+
+// Two transposing reads (contraction rows r0..r0+3 and r0+4..r0+7) -> one MFMA operand.
+__device__ __forceinline__ bf16x8 lds_read_frag_tr(const u16* p_lo, const u16* p_hi) {
+    const s16x4 lo = lds_read_tr(p_lo);
+    const s16x4 hi = lds_read_tr(p_hi);
+    const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, v);
+}
+
+__device__ __forceinline__ uint4 zero4() { return make_uint4(0u, 0u, 0u, 0u); }
+
+// 8 consecutive bf16 starting at p; the first `valid` (0..8) are read, the rest are zero.
+// `vec_ok` says p is 16-byte aligned (then a full chunk is one 128-bit load).
+__device__ __forceinline__ uint4 load_chunk(const u16* p, int valid, bool vec_ok) {
+    if (valid >= 8 && vec_ok) return *reinterpret_cast<const uint4*>(p);
+    uint32_t w[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+        if (e < valid) w[e >> 1] |= ((uint32_t)p[e]) << ((e & 1) * 16);
+    return make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+__device__ __forceinline__ uint4 scale_chunk(uint4 v, float s) {
+    uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const float lo = __uint_as_float(w[e] << 16) * s;
+        const float hi = __uint_as_float(w[e] & 0xffff0000u) * s;
+        w[e] = pack2(lo, hi);
+    }
+    return make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+}  // namespace mlora

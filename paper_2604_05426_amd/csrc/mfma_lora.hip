@@ -1,0 +1,383 @@
+// Grouped low-rank kernels for bf16 on gfx950 MFMA: shrink, gradient shrink, weight gradients.
+//
+// Paper Sec. 5.1: the LoRA GEMMs are memory-bandwidth bound (r << k, n); all adapters run in
+// one launch over a schedule table of (adapter, block) entries and only the diagonal blocks
+// S_i = X_i A_i are computed.  App. A.1: blocks map to token ranges through the per-adapter
+// offsets, the boundary block is masked at the segment end, ranks are masked (columns beyond
+// r_i contribute zero).
+#include "mfma_common.h"
+
+namespace mlora {
+
+// =========================================================================================
+// Shrink:   S_i  = X_i A_i            (FWD: A_i is [k][r], column index contiguous -> transposing reads)
+// dShrink:  dS_i = s_i dY_i B_i^T     (!FWD: B_i is [r][n], contraction contiguous)
+// One workgroup per row block (64 rows of one adapter); the 4 wavefronts split the contraction
+// (each takes one 16-wide slice of every 64-wide step) and their partial tiles are summed in LDS.
+// =========================================================================================
+constexpr int SR = 64;            // rows per block == kBlockRows
+constexpr int SK = 64;            // contraction step
+constexpr int SA_LD = SK + 8;     // X / dY tile [64][72]
+constexpr int SBN_LD = 128 + 32;  // FWD small tile [64 contraction][160]
+constexpr int SBT_LD = SK + 8;    // !FWD small tile [128 rank rows][72]
+constexpr int SA_TILE = SR * SA_LD;                 // 4608
+constexpr int SB_TILE = 64 * SBN_LD;                // 10240 >= 128 * 72 = 9216
+constexpr int S_STAGE = SA_TILE + SB_TILE;
+static_assert(kBlockRows == SR, "row-block table and shrink kernel must agree");
+
+struct ShrinkArgs {
+    const u16* src; int64_t ld;   // X (ld k) or dY (ld n)
+    u16* out;                     // ragged S or dS
+    int32_t Kdim;                 // k or n
+    PlanView pv;
+};
+
+template <bool FWD>
+__global__ __launch_bounds__(256) void shrink_kernel(ShrinkArgs g) {
+    __shared__ __attribute__((aligned(16))) u16 lds[2 * S_STAGE];
+    static_assert(2 * S_STAGE * 2 >= SR * 132 * 4, "reduction buffer fits in the staging buffers");
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const Entry4 e = g.pv.row_blocks[blockIdx.x];
+    const int i = e.a, row0 = e.c, rows = e.d;
+    const int r = g.pv.rank[i];
+    const int rpad = (r + 31) & ~31;
+    const int nblk = rpad / 32;
+    const u16* F = (const u16*)(FWD ? g.pv.ptrs[i].A : g.pv.ptrs[i].B);
+    const bool f_vec = FWD ? ((r & 7) == 0) : true;
+    const float s = FWD ? 1.0f : g.pv.scale[i];
+
+    f32x16 acc[2][4];
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+            for (int q = 0; q < 16; ++q) acc[mb][nb][q] = 0.f;
+
+    const int nk = (g.Kdim + SK - 1) / SK;
+    uint4 ra[2], rb[4];
+    auto gload = [&](int kt) {
+        const int k0 = kt * SK;
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) {
+            const int row = (tid >> 3) + 32 * jj, kc = tid & 7;
+            const int gk = k0 + kc * 8;
+            ra[jj] = (row < rows && gk < g.Kdim)
+                         ? *reinterpret_cast<const uint4*>(g.src + (int64_t)(row0 + row) * g.ld + gk) : zero4();
+        }
+        if (FWD) {   // A_i[k0 + krow][chunk c of the rank]
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) {
+                const int krow = (tid >> 4) + 16 * jj, cc = tid & 15;
+                rb[jj] = zero4();
+                if (cc * 8 < rpad && k0 + krow < g.Kdim)
+                    rb[jj] = load_chunk(F + (int64_t)(k0 + krow) * r + cc * 8, min(8, r - cc * 8), f_vec);
+            }
+        } else {     // B_i[rho][k0 + chunk]
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) {
+                const int rho = (tid >> 3) + 32 * jj, kc = tid & 7;
+                const int gk = k0 + kc * 8;
+                rb[jj] = (rho < r && gk < g.Kdim)
+                             ? *reinterpret_cast<const uint4*>(F + (int64_t)rho * g.ld + gk) : zero4();
+            }
+        }
+    };
+    auto lstore = [&](int stage) {
+        u16* As = lds + stage * S_STAGE;
+        u16* Bs = As + SA_TILE;
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) {
+            const int row = (tid >> 3) + 32 * jj, kc = tid & 7;
+            *reinterpret_cast<uint4*>(As + row * SA_LD + kc * 8) = ra[jj];
+        }
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            if (FWD) {
+                const int krow = (tid >> 4) + 16 * jj, cc = tid & 15;
+                *reinterpret_cast<uint4*>(Bs + krow * SBN_LD + cc * 8) = rb[jj];
+            } else {
+                const int rho = (tid >> 3) + 32 * jj, kc = tid & 7;
+                *reinterpret_cast<uint4*>(Bs + rho * SBT_LD + kc * 8) = rb[jj];
+            }
+        }
+    };
+    const int lm = lane & 31, h = lane >> 5, gq = lane >> 4, j = lane & 15;
+    auto compute = [&](int stage) {
+        const u16* As = lds + stage * S_STAGE;
+        const u16* Bs = As + SA_TILE;
+        const int ks = wave;   // this wavefront's 16-wide slice of the 64-wide step
+        bf16x8 a[2];
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb) a[mb] = lds_read_frag(As + (mb * 32 + lm) * SA_LD + ks * 16 + h * 8);
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb) {
+            if (nb < nblk) {
+                bf16x8 b;
+                if (FWD) {
+                    const u16* p = Bs + (ks * 16 + 8 * (gq >> 1) + (j >> 2)) * SBN_LD + nb * 32 + 16 * (gq & 1) + 4 * (j & 3);
+                    b = lds_read_frag_tr(p, p + 4 * SBN_LD);
+                } else {
+                    b = lds_read_frag(Bs + (nb * 32 + lm) * SBT_LD + ks * 16 + h * 8);
+                }
+#pragma unroll
+                for (int mb = 0; mb < 2; ++mb) acc[mb][nb] = mfma32(a[mb], b, acc[mb][nb]);
+            }
+        }
+    };
+
+    gload(0);
+    lstore(0);
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        const int cur = kt & 1;
+        if (kt + 1 < nk) gload(kt + 1);
+        compute(cur);
+        if (kt + 1 < nk) lstore(cur ^ 1);
+        __syncthreads();
+    }
+
+    // sum the four wavefronts' partial tiles in a fixed order (deterministic), then store
+    float* red = reinterpret_cast<float*>(lds);   // [64][132]
+    constexpr int RLD = 132;
+    for (int w = 0; w < 4; ++w) {
+        if (wave == w) {
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                for (int nb = 0; nb < 4; ++nb) {
+                    if (nb >= nblk) continue;
+#pragma unroll
+                    for (int q = 0; q < 16; ++q) {
+                        const int row = mb * 32 + (q >> 2) * 8 + h * 4 + (q & 3);
+                        float* d = red + row * RLD + nb * 32 + lm;
+                        *d = (w == 0) ? acc[mb][nb][q] : (*d + acc[mb][nb][q]);
+                    }
+                }
+        }
+        __syncthreads();
+    }
+    const int64_t so = g.pv.soff[i];
+    const int seg0 = g.pv.off[i];
+    u16* out = g.out + so + (int64_t)(row0 - seg0) * r;
+    for (int idx = tid; idx < rows * r; idx += 256) {
+        const int row = idx / r, col = idx - row * r;
+        out[idx] = f2bf(s * red[row * RLD + col]);
+    }
+}
+
+// =========================================================================================
+// Weight gradients (token reductions):
+//   dA_i[kappa][rho] = sum_t X[t][kappa] dS[t][rho]          out [k][r]
+//   dB_i[rho][nu]    = s_i sum_t S[t][rho] dY[t][nu]         out [r][n]  (stored transposed)
+// Work item = (token chunk of one adapter, 128-column panel of X or dY).  Both MFMA operands
+// have the token index as the row index in memory, so both are read with transposing loads.
+// A chunk that covers its whole segment stores the result directly; otherwise fp32 partials go
+// to the workspace and a second kernel adds them in chunk order (no atomics, deterministic).
+// =========================================================================================
+constexpr int WP = 128;          // panel columns
+constexpr int WT = 64;           // tokens per step
+constexpr int W_LD = 128 + 32;   // both tiles [64 tokens][160]
+constexpr int W_TILE = WT * W_LD;
+constexpr int W_STAGE = 2 * W_TILE;
+
+struct WgradArgs {
+    const u16* X; const u16* dY; const u16* S; const u16* dS;
+    float* partials;
+    int32_t panels_k, panels_n;
+    PlanView pv;
+    const int64_t* part_off;   // [N] float offset of adapter i's partial block (chunks > 1 only)
+};
+
+__global__ __launch_bounds__(256) void wgrad_kernel(WgradArgs g) {
+    __shared__ __attribute__((aligned(16))) u16 lds[2 * W_STAGE];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int panels = g.panels_k + g.panels_n;
+    const int ce = blockIdx.x / panels;
+    int panel = blockIdx.x - ce * panels;
+    const Entry4 e = g.pv.wgrad_chunks[ce];
+    const int i = e.a, chunk = e.b, row0 = e.c, rows = e.d;
+    const bool isA = panel < g.panels_k;
+    if (!isA) panel -= g.panels_k;
+    const int r = g.pv.rank[i];
+    const int rpad = (r + 31) & ~31;
+    const int nblk = rpad / 32;
+    const int64_t so = g.pv.soff[i];
+    const int seg0 = g.pv.off[i];
+    const int width = (int)(isA ? g.pv.k : g.pv.n);
+    const u16* big = isA ? g.X : g.dY;
+    const u16* small = (isA ? g.dS : g.S) + so + (int64_t)(row0 - seg0) * r;
+    const int col0 = panel * WP;
+    const bool s_vec = ((r & 7) == 0) && ((so & 7) == 0);
+
+    f32x16 acc[4];
+#pragma unroll
+    for (int nb = 0; nb < 4; ++nb)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) acc[nb][q] = 0.f;
+
+    const int nt = (rows + WT - 1) / WT;
+    uint4 ra[4], rb[4];
+    auto gload = [&](int tt) {
+        const int t0 = tt * WT;
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            const int trow = (tid >> 4) + 16 * jj, cc = tid & 15;
+            const int col = col0 + cc * 8;
+            const bool ok = (t0 + trow < rows);
+            ra[jj] = (ok && col < width)
+                         ? *reinterpret_cast<const uint4*>(big + (int64_t)(row0 + t0 + trow) * width + col) : zero4();
+            rb[jj] = zero4();
+            if (ok && cc * 8 < rpad)
+                rb[jj] = load_chunk(small + (int64_t)(t0 + trow) * r + cc * 8, min(8, r - cc * 8), s_vec);
+        }
+    };
+    auto lstore = [&](int stage) {
+        u16* Xs = lds + stage * W_STAGE;
+        u16* Ss = Xs + W_TILE;
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            const int trow = (tid >> 4) + 16 * jj, cc = tid & 15;
+            *reinterpret_cast<uint4*>(Xs + trow * W_LD + cc * 8) = ra[jj];
+            *reinterpret_cast<uint4*>(Ss + trow * W_LD + cc * 8) = rb[jj];
+        }
+    };
+    const int lm = lane & 31, h = lane >> 5, gq = lane >> 4, j = lane & 15;
+    auto compute = [&](int stage) {
+        const u16* Xs = lds + stage * W_STAGE;
+        const u16* Ss = Xs + W_TILE;
+#pragma unroll
+        for (int ks = 0; ks < WT / 16; ++ks) {
+            const int trow = ks * 16 + 8 * (gq >> 1) + (j >> 2);
+            const int coff = 16 * (gq & 1) + 4 * (j & 3);
+            const u16* pa = Xs + trow * W_LD + wave * 32 + coff;
+            const bf16x8 a = lds_read_frag_tr(pa, pa + 4 * W_LD);
+#pragma unroll
+            for (int nb = 0; nb < 4; ++nb) {
+                if (nb < nblk) {
+                    const u16* pb = Ss + trow * W_LD + nb * 32 + coff;
+                    const bf16x8 b = lds_read_frag_tr(pb, pb + 4 * W_LD);
+                    acc[nb] = mfma32(a, b, acc[nb]);
+                }
+            }
+        }
+    };
+    if (nt > 0) {
+        gload(0);
+        lstore(0);
+    }
+    __syncthreads();
+    for (int tt = 0; tt < nt; ++tt) {
+        const int cur = tt & 1;
+        if (tt + 1 < nt) gload(tt + 1);
+        compute(cur);
+        if (tt + 1 < nt) lstore(cur ^ 1);
+        __syncthreads();
+    }
+
+    const int nchunks = g.pv.wgrad_chunk_start[i + 1] - g.pv.wgrad_chunk_start[i];
+    const float s = isA ? 1.0f : g.pv.scale[i];
+    const int64_t kk = g.pv.k, nn = g.pv.n;
+#pragma unroll
+    for (int nb = 0; nb < 4; ++nb) {
+        if (nb >= nblk) continue;
+        const int rho = nb * 32 + lm;
+        if (rho >= r) continue;
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+            const int c = col0 + wave * 32 + (q >> 2) * 8 + h * 4 + (q & 3);
+            if (c >= width) continue;
+            const int64_t idx = isA ? ((int64_t)c * r + rho) : ((int64_t)rho * nn + c);
+            if (nchunks == 1) {
+                u16* out = (u16*)(isA ? g.pv.ptrs[i].dA : g.pv.ptrs[i].dB);
+                out[idx] = f2bf(s * acc[nb][q]);
+            } else {
+                float* part = g.partials + g.part_off[i] + (int64_t)chunk * (kk + nn) * r + (isA ? 0 : kk * r);
+                part[idx] = s * acc[nb][q];
+            }
+        }
+    }
+}
+
+// Adds the chunk partials of one adapter in chunk order and rounds once.
+__global__ __launch_bounds__(256) void wgrad_reduce_kernel(WgradArgs g) {
+    const int i = blockIdx.y;
+    const int nchunks = g.pv.wgrad_chunk_start[i + 1] - g.pv.wgrad_chunk_start[i];
+    if (nchunks <= 1) return;
+    const int r = g.pv.rank[i];
+    const int64_t kk = g.pv.k, nn = g.pv.n;
+    const int64_t per = (kk + nn) * r;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= per) return;
+    const float* part = g.partials + g.part_off[i] + idx;
+    float v = 0.f;
+    for (int c = 0; c < nchunks; ++c) v += part[(int64_t)c * per];
+    if (idx < kk * r) ((u16*)g.pv.ptrs[i].dA)[idx] = f2bf(v);
+    else ((u16*)g.pv.ptrs[i].dB)[idx - kk * r] = f2bf(v);
+}
+
+// Zero-fills dA_i, dB_i of adapters that have a rank but no tokens (no work item reaches them).
+__global__ void wgrad_zero_empty_kernel(PlanView pv) {
+    const int i = blockIdx.y;
+    const int r = pv.rank[i];
+    if (r == 0 || pv.off[i + 1] != pv.off[i]) return;
+    const int64_t kk = pv.k, nn = pv.n;
+    const int64_t per = (kk + nn) * r;
+    for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < per; idx += (int64_t)gridDim.x * 256) {
+        if (idx < kk * r) ((u16*)pv.ptrs[i].dA)[idx] = 0;
+        else ((u16*)pv.ptrs[i].dB)[idx - kk * r] = 0;
+    }
+}
+
+// ---- host launchers ---------------------------------------------------------------------
+
+int mfma_gemm_fwd(mlora_plan* p, const void* X, const void* W, void* Y, const void* S, uint32_t flags, hipStream_t st);
+int mfma_gemm_bwd(mlora_plan* p, const void* dY, const void* W, void* dX, const void* dS, uint32_t flags, hipStream_t st);
+
+int mfma_forward(mlora_plan* p, const void* X, const void* W, void* Y, void* S, uint32_t flags, hipStream_t st) {
+    const bool lora = !(flags & MLORA_FLAG_BASE_ONLY) && p->N > 0;
+    if (lora && p->n_row_blocks > 0) {
+        ShrinkArgs a{};
+        a.src = (const u16*)X; a.ld = p->k; a.out = (u16*)S; a.Kdim = (int32_t)p->k; a.pv = p->view;
+        hipLaunchKernelGGL(shrink_kernel<true>, dim3(p->n_row_blocks), dim3(256), 0, st, a);
+        MLORA_HIP_TRY(hipGetLastError());
+    }
+    return mfma_gemm_fwd(p, X, W, Y, S, flags, st);
+}
+
+int mfma_backward(mlora_plan* p, const void* dY, const void* X, const void* W, const void* S, void* dX, void* dS,
+                  float* partials, uint32_t flags, hipStream_t st) {
+    const bool lora = !(flags & MLORA_FLAG_BASE_ONLY) && p->N > 0;
+    if (lora && p->n_row_blocks > 0) {
+        ShrinkArgs a{};
+        a.src = (const u16*)dY; a.ld = p->n; a.out = (u16*)dS; a.Kdim = (int32_t)p->n; a.pv = p->view;
+        hipLaunchKernelGGL(shrink_kernel<false>, dim3(p->n_row_blocks), dim3(256), 0, st, a);
+        MLORA_HIP_TRY(hipGetLastError());
+    }
+    int rc = mfma_gemm_bwd(p, dY, W, dX, dS, flags, st);
+    if (rc != MLORA_OK) return rc;
+    if (lora) {
+        WgradArgs w{};
+        w.X = (const u16*)X; w.dY = (const u16*)dY; w.S = (const u16*)S; w.dS = (const u16*)dS;
+        w.partials = partials;
+        w.panels_k = (int32_t)((p->k + WP - 1) / WP);
+        w.panels_n = (int32_t)((p->n + WP - 1) / WP);
+        w.pv = p->view;
+        w.part_off = p->d_part_off;
+        if (p->n_wgrad_chunks > 0) {
+            const int64_t grid = (int64_t)p->n_wgrad_chunks * (w.panels_k + w.panels_n);
+            hipLaunchKernelGGL(wgrad_kernel, dim3((unsigned)grid), dim3(256), 0, st, w);
+            if (p->max_chunks_per_adapter > 1) {
+                const int64_t per = (p->k + p->n) * (int64_t)p->max_rank;
+                hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)((per + 255) / 256), p->N), dim3(256), 0, st, w);
+            }
+        }
+        if (p->has_empty_ranked) {
+            hipLaunchKernelGGL(wgrad_zero_empty_kernel, dim3(64, p->N), dim3(256), 0, st, p->view);
+        }
+        MLORA_HIP_TRY(hipGetLastError());
+    }
+    return MLORA_OK;
+}
+
+}  // namespace mlora

@@ -1,0 +1,388 @@
+// Plan: argument validation, device-built schedule tables, per-call pointer upload.
+//
+// The paper builds a table of (adapter_idx, block_idx) pairs on the CPU before each
+// forward pass and maps each block to a token range through per-adapter start/end
+// offsets, masking the boundary block (App. A.1, "schedule-driven dispatch").  Here the
+// host only validates and sizes; the tables themselves are built by device kernels from
+// the offsets and ranks, once per segmentation, and shared by every layer of a step.
+#include <cmath>
+#include <cstring>
+
+#include "common.h"
+
+namespace mlora {
+
+static thread_local std::string g_last_error;
+
+void set_error(const std::string& msg) { g_last_error = msg; }
+
+int hip_fail(hipError_t e, const char* what) {
+    set_error(std::string("HIP error: ") + hipGetErrorString(e) + " in " + what);
+    return MLORA_ERR_HIP;
+}
+
+static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// ---- device kernels -----------------------------------------------------------------
+
+// Sequential prefix sums over the adapters (N <= 4096, done by one thread).
+__global__ void plan_scan_kernel(int32_t N, const int32_t* off, const int32_t* rank, int64_t* soff,
+                                 int32_t* rb_start, int32_t* wc_start, int block_rows,
+                                 int chunk_rows) {
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    int64_t s = 0;
+    int32_t rb = 0, wc = 0;
+    for (int32_t i = 0; i < N; ++i) {
+        soff[i] = s;
+        rb_start[i] = rb;
+        wc_start[i] = wc;
+        const int32_t Ti = off[i + 1] - off[i];
+        const int32_t r = rank[i];
+        s += (int64_t)Ti * r;
+        if (Ti > 0 && r > 0) {
+            rb += (Ti + block_rows - 1) / block_rows;
+            wc += (Ti + chunk_rows - 1) / chunk_rows;
+        }
+    }
+    soff[N] = s;
+    rb_start[N] = rb;
+    wc_start[N] = wc;
+}
+
+// index of the adapter whose [start[i], start[i+1]) holds e  (start non-decreasing)
+__device__ inline int32_t find_owner(const int32_t* start, int32_t N, int32_t e) {
+    int32_t lo = 0, hi = N;  // invariant: start[lo] <= e < start[hi]
+    while (hi - lo > 1) {
+        const int32_t mid = (lo + hi) >> 1;
+        if (start[mid] <= e) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// Fills a block table: entry e of adapter i = (i, b, off[i] + b*rows_per, min(rows_per, rest)).
+__global__ void plan_fill_blocks_kernel(int32_t N, const int32_t* off, const int32_t* start,
+                                        int rows_per, Entry4* out, int32_t count) {
+    const int32_t e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= count) return;
+    // adapters without entries have start[i] == start[i+1]; the owner is the last i with start[i] <= e
+    // that also has start[i+1] > e, which the search below finds because start is non-decreasing.
+    int32_t lo = 0, hi = N;
+    while (hi - lo > 1) {
+        const int32_t mid = (lo + hi) >> 1;
+        if (start[mid] <= e) lo = mid; else hi = mid;
+    }
+    const int32_t i = lo;
+    const int32_t b = e - start[i];
+    const int32_t row0 = off[i] + b * rows_per;
+    const int32_t rest = off[i + 1] - row0;
+    out[e] = Entry4{i, b, row0, rest < rows_per ? rest : rows_per};
+}
+
+// Row tiles of the flat buffer and the adapters they touch.
+__global__ void plan_fill_gemm_tiles_kernel(int32_t N, const int32_t* off, int32_t T, int tile_rows,
+                                            Entry4* out, int32_t count) {
+    const int32_t e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= count) return;
+    const int32_t row0 = e * tile_rows;
+    const int32_t rows = (T - row0) < tile_rows ? (T - row0) : tile_rows;
+    int32_t lo = 0, hi = 0;
+    if (N > 0) {
+        lo = find_owner(off, N, row0);
+        hi = find_owner(off, N, row0 + rows - 1) + 1;
+    }
+    out[e] = Entry4{row0, rows, lo, hi};
+}
+
+struct PtrBatch {
+    AdapterPtrs p[32];
+};
+
+__global__ void upload_ptrs_kernel(AdapterPtrs* dst, PtrBatch batch, int32_t base, int32_t count) {
+    const int32_t i = threadIdx.x;
+    if (i < count) dst[base + i] = batch.p[i];
+}
+
+int upload_ptrs(mlora_plan* p, const void* const* A, const void* const* B, void* const* dA,
+                void* const* dB, hipStream_t st) {
+    for (int32_t base = 0; base < p->N; base += 32) {
+        PtrBatch batch;
+        std::memset(&batch, 0, sizeof(batch));
+        const int32_t cnt = (p->N - base) < 32 ? (p->N - base) : 32;
+        for (int32_t j = 0; j < cnt; ++j) {
+            batch.p[j].A = A ? A[base + j] : nullptr;
+            batch.p[j].B = B ? B[base + j] : nullptr;
+            batch.p[j].dA = dA ? dA[base + j] : nullptr;
+            batch.p[j].dB = dB ? dB[base + j] : nullptr;
+        }
+        hipLaunchKernelGGL(upload_ptrs_kernel, dim3(1), dim3(32), 0, st, p->d_ptrs, batch, base, cnt);
+    }
+    MLORA_HIP_TRY(hipGetLastError());
+    return MLORA_OK;
+}
+
+}  // namespace mlora
+
+using namespace mlora;
+
+// ---- C ABI -----------------------------------------------------------------------------
+
+extern "C" const char* multi_lora_last_error(void) { return g_last_error.c_str(); }
+
+extern "C" const char* multi_lora_version(void) { return "0.1"; }
+
+extern "C" int multi_lora_validate(int dtype, int64_t T, int64_t k, int64_t n, int32_t N,
+                                   const int32_t* ranks, const float* scales,
+                                   const int64_t* seg_offsets) {
+    if (dtype != MLORA_F32 && dtype != MLORA_BF16) {
+        set_error("dtype must be MLORA_F32 or MLORA_BF16");
+        return MLORA_ERR_DTYPE;
+    }
+    const int64_t kMaxDim = (int64_t)1 << 30;
+    if (T < 0 || T > kMaxDim || k < 1 || k > kMaxDim || n < 1 || n > kMaxDim) {
+        set_error("T must be in [0, 2^30] and k, n in [1, 2^30]");
+        return MLORA_ERR_SHAPE;
+    }
+    if (N < 0 || N > MLORA_MAX_ADAPTERS) {
+        set_error("N must be in [0, MLORA_MAX_ADAPTERS]");
+        return MLORA_ERR_SHAPE;
+    }
+    if (!seg_offsets) {
+        set_error("seg_offsets is NULL");
+        return MLORA_ERR_NULL;
+    }
+    if (N > 0 && (!ranks || !scales)) {
+        set_error("ranks / scales is NULL");
+        return MLORA_ERR_NULL;
+    }
+    if (seg_offsets[0] != 0) {
+        set_error("seg_offsets[0] must be 0");
+        return MLORA_ERR_SEGMENTS;
+    }
+    for (int32_t i = 0; i < N; ++i) {
+        if (seg_offsets[i + 1] < seg_offsets[i]) {
+            set_error("seg_offsets must be non-decreasing (segments may not overlap)");
+            return MLORA_ERR_SEGMENTS;
+        }
+    }
+    if (seg_offsets[N] != T) {
+        set_error("seg_offsets[N] must equal T (every row belongs to exactly one adapter)");
+        return MLORA_ERR_SEGMENTS;
+    }
+    for (int32_t i = 0; i < N; ++i) {
+        if (ranks[i] < 0 || ranks[i] > MLORA_MAX_RANK) {
+            set_error("rank outside [0, MLORA_MAX_RANK]");
+            return MLORA_ERR_RANK;
+        }
+        if (!std::isfinite(scales[i])) {
+            set_error("scale is not finite");
+            return MLORA_ERR_SCALE;
+        }
+    }
+    return MLORA_OK;
+}
+
+extern "C" int multi_lora_plan_create(mlora_plan** out, int dtype, int64_t T, int64_t k, int64_t n,
+                                      int32_t N, const int32_t* ranks, const float* scales,
+                                      const int64_t* seg_offsets, void* stream) {
+    if (!out) {
+        set_error("out is NULL");
+        return MLORA_ERR_NULL;
+    }
+    *out = nullptr;
+    const int rc = multi_lora_validate(dtype, T, k, n, N, ranks, scales, seg_offsets);
+    if (rc != MLORA_OK) return rc;
+
+    mlora_plan* p = new mlora_plan();
+    p->dtype = dtype;
+    p->T = T; p->k = k; p->n = n; p->N = N;
+    p->ranks.assign(ranks, ranks + N);
+    p->scales.assign(scales, scales + N);
+    p->off.assign(seg_offsets, seg_offsets + N + 1);
+    p->soff.resize(N + 1);
+    p->wchunk_start.resize(N + 1);
+    p->build_stream = (hipStream_t)stream;
+    // bf16 with 16-byte row granularity goes to the MFMA kernels, everything else to the FMA kernels
+    p->use_mfma = (dtype == MLORA_BF16) && (k % 8 == 0) && (n % 8 == 0);
+
+    // host-side sizes (the device rebuilds the same numbers; multi_lora_plan_dump exposes them)
+    int64_t s = 0;
+    int64_t rb = 0, wc = 0;
+    for (int32_t i = 0; i < N; ++i) {
+        p->soff[i] = s;
+        p->wchunk_start[i] = (int32_t)wc;
+        const int64_t Ti = p->off[i + 1] - p->off[i];
+        s += Ti * ranks[i];
+        if (Ti > 0 && ranks[i] > 0) {
+            rb += ceil_div(Ti, kBlockRows);
+            const int64_t c = ceil_div(Ti, kWgradChunkRows);
+            wc += c;
+            if (c > p->max_chunks_per_adapter) p->max_chunks_per_adapter = (int32_t)c;
+        }
+        if (ranks[i] > p->max_rank) p->max_rank = ranks[i];
+    }
+    p->soff[N] = s;
+    p->wchunk_start[N] = (int32_t)wc;
+    p->R1 = s;
+    p->n_row_blocks = (int32_t)rb;
+    p->n_wgrad_chunks = (int32_t)wc;
+    p->n_gemm_tiles = (int32_t)ceil_div(T, kGemmTileRows);
+
+    const size_t esz = dtype == MLORA_BF16 ? 2 : 4;
+    auto up256 = [](size_t v) { return (v + 255) & ~(size_t)255; };
+    p->ws_ds_bytes = up256((size_t)p->R1 * esz);
+    // fp32 partials of dA_i, dB_i for adapters whose tokens are split over several chunks
+    size_t part = 0;   // in floats
+    std::vector<int64_t>& part_off = p->part_off;
+    part_off.assign(N + 1, 0);
+    for (int32_t i = 0; i < N; ++i) {
+        const int64_t c = p->wchunk_start[i + 1] - p->wchunk_start[i];
+        part_off[i] = (int64_t)part;
+        if (c > 1) part += (size_t)c * (size_t)(k + n) * (size_t)ranks[i];
+        if (ranks[i] > 0 && p->off[i + 1] == p->off[i]) p->has_empty_ranked = true;
+    }
+    p->ws_partial_bytes = up256(part * sizeof(float));
+
+    // carve one device allocation
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t r = o; o += up256(bytes); return r; };
+    const size_t o_off = take(sizeof(int32_t) * (N + 1));
+    const size_t o_rank = take(sizeof(int32_t) * (N + 1));
+    const size_t o_scale = take(sizeof(float) * (N + 1));
+    const size_t o_soff = take(sizeof(int64_t) * (N + 1));
+    const size_t o_rbs = take(sizeof(int32_t) * (N + 1));
+    const size_t o_wcs = take(sizeof(int32_t) * (N + 1));
+    const size_t o_ptrs = take(sizeof(AdapterPtrs) * (N + 1));
+    const size_t o_rb = take(sizeof(Entry4) * (size_t)(p->n_row_blocks + 1));
+    const size_t o_gt = take(sizeof(Entry4) * (size_t)(p->n_gemm_tiles + 1));
+    const size_t o_wc = take(sizeof(Entry4) * (size_t)(p->n_wgrad_chunks + 1));
+    const size_t o_probs = take(128 * (size_t)(5 * N + 8));
+    const size_t o_part = take(sizeof(int64_t) * (N + 1));
+    p->d_block_bytes = o;
+
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
+            p->num_cus = cus;
+        e = hipMalloc(&p->d_block, p->d_block_bytes);
+    }
+    if (e != hipSuccess) {
+        delete p;
+        return hip_fail(e, "hipMalloc(plan tables)");
+    }
+    char* base = (char*)p->d_block;
+    int32_t* d_off = (int32_t*)(base + o_off);
+    int32_t* d_rank = (int32_t*)(base + o_rank);
+    float* d_scale = (float*)(base + o_scale);
+    int64_t* d_soff = (int64_t*)(base + o_soff);
+    int32_t* d_rbs = (int32_t*)(base + o_rbs);
+    int32_t* d_wcs = (int32_t*)(base + o_wcs);
+    p->d_ptrs = (AdapterPtrs*)(base + o_ptrs);
+    Entry4* d_rb = (Entry4*)(base + o_rb);
+    Entry4* d_gt = (Entry4*)(base + o_gt);
+    Entry4* d_wc = (Entry4*)(base + o_wc);
+    p->d_probs = base + o_probs;
+    p->d_part_off = (int64_t*)(base + o_part);
+
+    hipStream_t st = p->build_stream;
+    std::vector<int32_t>& off32 = p->off32;
+    off32.resize(N + 1);
+    for (int32_t i = 0; i <= N; ++i) off32[i] = (int32_t)p->off[i];
+    auto fail = [&](hipError_t err, const char* what) {
+        (void)hipFree(p->d_block);
+        delete p;
+        return hip_fail(err, what);
+    };
+    if ((e = hipMemcpyAsync(d_off, off32.data(), sizeof(int32_t) * (N + 1), hipMemcpyHostToDevice, st)) != hipSuccess)
+        return fail(e, "hipMemcpyAsync(offsets)");
+    if (N > 0) {
+        if ((e = hipMemcpyAsync(d_rank, p->ranks.data(), sizeof(int32_t) * N, hipMemcpyHostToDevice, st)) != hipSuccess)
+            return fail(e, "hipMemcpyAsync(ranks)");
+        if ((e = hipMemcpyAsync(d_scale, p->scales.data(), sizeof(float) * N, hipMemcpyHostToDevice, st)) != hipSuccess)
+            return fail(e, "hipMemcpyAsync(scales)");
+    }
+    if ((e = hipMemcpyAsync(p->d_part_off, part_off.data(), sizeof(int64_t) * (N + 1), hipMemcpyHostToDevice, st)) != hipSuccess)
+        return fail(e, "hipMemcpyAsync(partial offsets)");
+    hipLaunchKernelGGL(plan_scan_kernel, dim3(1), dim3(64), 0, st, N, d_off, d_rank, d_soff, d_rbs, d_wcs,
+                       kBlockRows, kWgradChunkRows);
+    if (p->n_row_blocks > 0)
+        hipLaunchKernelGGL(plan_fill_blocks_kernel, dim3((p->n_row_blocks + 255) / 256), dim3(256), 0, st, N,
+                           d_off, d_rbs, kBlockRows, d_rb, p->n_row_blocks);
+    if (p->n_wgrad_chunks > 0)
+        hipLaunchKernelGGL(plan_fill_blocks_kernel, dim3((p->n_wgrad_chunks + 255) / 256), dim3(256), 0, st, N,
+                           d_off, d_wcs, kWgradChunkRows, d_wc, p->n_wgrad_chunks);
+    if (p->n_gemm_tiles > 0)
+        hipLaunchKernelGGL(plan_fill_gemm_tiles_kernel, dim3((p->n_gemm_tiles + 255) / 256), dim3(256), 0, st, N,
+                           d_off, (int32_t)T, kGemmTileRows, d_gt, p->n_gemm_tiles);
+    if ((e = hipGetLastError()) != hipSuccess) return fail(e, "plan build kernels");
+
+    PlanView& v = p->view;
+    v.N = N; v.T = T; v.k = k; v.n = n;
+    v.off = d_off; v.rank = d_rank; v.scale = d_scale; v.soff = d_soff; v.ptrs = p->d_ptrs;
+    v.row_blocks = d_rb; v.n_row_blocks = p->n_row_blocks;
+    v.gemm_tiles = d_gt; v.n_gemm_tiles = p->n_gemm_tiles;
+    v.wgrad_chunks = d_wc; v.n_wgrad_chunks = p->n_wgrad_chunks;
+    v.wgrad_chunk_start = d_wcs;
+    *out = p;
+    return MLORA_OK;
+}
+
+extern "C" int multi_lora_plan_destroy(mlora_plan* plan) {
+    if (!plan) return MLORA_OK;
+    hipError_t e = hipSuccess;
+    if (plan->d_block) e = hipFree(plan->d_block);
+    delete plan;
+    if (e != hipSuccess) return hip_fail(e, "hipFree(plan tables)");
+    return MLORA_OK;
+}
+
+extern "C" size_t multi_lora_workspace_bytes(const mlora_plan* plan) {
+    if (!plan) return 0;
+    return plan->ws_ds_bytes + plan->ws_partial_bytes;
+}
+
+extern "C" int multi_lora_plan_geometry(const mlora_plan* plan, int32_t* out) {
+    if (!plan || !out) {
+        set_error("plan / out is NULL");
+        return MLORA_ERR_NULL;
+    }
+    for (int i = 0; i < MLORA_GEO_COUNT; ++i) out[i] = 0;
+    out[MLORA_GEO_BLOCK_ROWS] = kBlockRows;
+    out[MLORA_GEO_GEMM_TILE_ROWS] = kGemmTileRows;
+    out[MLORA_GEO_GEMM_TILE_COLS] = kGemmTileCols;
+    out[MLORA_GEO_WGRAD_CHUNK_ROWS] = kWgradChunkRows;
+    out[MLORA_GEO_R1_LO] = (int32_t)(plan->R1 & 0x7fffffff);
+    out[MLORA_GEO_R1_HI] = (int32_t)(plan->R1 >> 31);
+    out[MLORA_GEO_USES_MFMA] = plan->use_mfma ? 1 : 0;
+    return MLORA_OK;
+}
+
+extern "C" int multi_lora_plan_dump(const mlora_plan* plan, int which, int32_t* entries, int64_t cap,
+                                    int64_t* count) {
+    if (!plan || !count) {
+        set_error("plan / count is NULL");
+        return MLORA_ERR_NULL;
+    }
+    const Entry4* src = nullptr;
+    int64_t cnt = 0;
+    switch (which) {
+        case MLORA_TABLE_ROW_BLOCKS: src = plan->view.row_blocks; cnt = plan->n_row_blocks; break;
+        case MLORA_TABLE_GEMM_ROW_TILES: src = plan->view.gemm_tiles; cnt = plan->n_gemm_tiles; break;
+        case MLORA_TABLE_WGRAD_CHUNKS: src = plan->view.wgrad_chunks; cnt = plan->n_wgrad_chunks; break;
+        default:
+            set_error("unknown table id");
+            return MLORA_ERR_FLAGS;
+    }
+    *count = cnt;
+    const int64_t ncopy = cnt < cap ? cnt : cap;
+    if (ncopy > 0) {
+        if (!entries) {
+            set_error("entries is NULL");
+            return MLORA_ERR_NULL;
+        }
+        MLORA_HIP_TRY(hipStreamSynchronize(plan->build_stream));
+        MLORA_HIP_TRY(hipMemcpy(entries, src, sizeof(Entry4) * (size_t)ncopy, hipMemcpyDeviceToHost));
+    }
+    return MLORA_OK;
+}

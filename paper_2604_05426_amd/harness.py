@@ -1,0 +1,84 @@
+"""Device-side plumbing around the C ABI: upload a Workload, allocate outputs with torch,
+call multi_lora_fwd / multi_lora_bwd, fetch results.  No arithmetic of the layer happens here.
+"""
+from __future__ import annotations
+
+from typing import List, Optional
+
+import numpy as np
+import torch
+
+from . import binding as ml
+from .workloads import Workload, bf16_bits
+
+
+def to_device(a: np.ndarray, dtype: str, device) -> torch.Tensor:
+    """float32 host array (holding values exact in `dtype`) -> device tensor of that dtype."""
+    if dtype == "bf16":
+        bits = bf16_bits(a).view(np.int16)
+        return torch.from_numpy(bits).to(device).view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device)
+
+
+def to_host(t: torch.Tensor) -> np.ndarray:
+    """device tensor -> float64 numpy (exact widening)."""
+    return t.detach().to(torch.float32).cpu().numpy().astype(np.float64)
+
+
+class DeviceLayer:
+    """One multi-LoRA layer resident on the GPU: inputs, outputs, plan and workspace."""
+
+    def __init__(self, w: Workload, device: str = "cuda:0", canary: Optional[float] = None):
+        if not torch.cuda.is_available():
+            raise RuntimeError("DeviceLayer needs a GPU; there is no CPU fallback")
+        self.w = w
+        self.device = torch.device(device)
+        self.tdtype = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+        self.mdtype = ml.BF16 if w.dtype == "bf16" else ml.F32
+        dev, dt = self.device, w.dtype
+        self.X, self.W, self.dY = to_device(w.X, dt, dev), to_device(w.W, dt, dev), to_device(w.dY, dt, dev)
+        self.A = [to_device(a, dt, dev) for a in w.A]
+        self.B = [to_device(b, dt, dev) for b in w.B]
+        fill = float("nan") if canary is None else canary
+
+        def out(*shape):
+            return torch.full(shape, fill, dtype=self.tdtype, device=dev)
+
+        self.Y, self.dX = out(w.T, w.n), out(w.T, w.k)
+        self.S = out(max(w.R1, 1))
+        self.dA = [out(w.k, r) for r in w.ranks]
+        self.dB = [out(r, w.n) for r in w.ranks]
+        self.stream = torch.cuda.current_stream(dev).cuda_stream
+        self.plan = ml.Plan(self.mdtype, w.T, w.k, w.n, w.ranks, w.scales, w.offsets, stream=self.stream)
+        self.ws_bytes = self.plan.workspace_bytes()
+        self.workspace = torch.zeros(max(self.ws_bytes, 256), dtype=torch.uint8, device=dev)
+
+    def forward(self, flags: int = 0) -> None:
+        ml.multi_lora_fwd(self.plan, self.X, self.W, self.A, self.B, self.Y, self.S, self.workspace,
+                          flags, self.stream)
+
+    def backward(self, flags: int = 0) -> None:
+        ml.multi_lora_bwd(self.plan, self.dY, self.X, self.W, self.A, self.B, self.S, self.dX,
+                          self.dA, self.dB, self.workspace, flags, self.stream)
+
+    def sync(self) -> None:
+        torch.cuda.synchronize(self.device)
+
+    # ---- results as float64 numpy ------------------------------------------------------
+    def S_list(self) -> List[np.ndarray]:
+        s = to_host(self.S)
+        out, o = [], 0
+        for t, r in zip(self.w.seg_lens, self.w.ranks):
+            out.append(s[o:o + t * r].reshape(t, r))
+            o += t * r
+        return out
+
+    def dS_list(self) -> List[np.ndarray]:
+        esz = 2 if self.w.dtype == "bf16" else 4
+        raw = self.workspace[: self.w.R1 * esz].view(self.tdtype) if self.w.R1 else self.workspace[:0].view(self.tdtype)
+        s = to_host(raw)
+        out, o = [], 0
+        for t, r in zip(self.w.seg_lens, self.w.ranks):
+            out.append(s[o:o + t * r].reshape(t, r))
+            o += t * r
+        return out

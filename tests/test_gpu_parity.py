@@ -1,0 +1,206 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element on
+the same seeded inputs.  Tolerances: relative Frobenius error <= 1e-2 for bf16 tensors and
+<= 1e-5 for fp32 runs; integer bookkeeping bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import multilora_oracle as orc
+from oracle import tile_tables as tt
+from paper_2604_05426_amd import binding as ml
+from paper_2604_05426_amd import workloads as wl
+from paper_2604_05426_amd.harness import DeviceLayer, to_host
+from util import rel_fro, sample_cols, sample_rows
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"bf16": 1e-2, "f32": 1e-5}
+
+
+def check_full(w, tol=None, label=""):
+    """Run fwd+bwd on the GPU and compare every output with the full oracle."""
+    tol = TOL[w.dtype] if tol is None else tol
+    print(f"[case] {label or w.name} dtype={w.dtype} T={w.T} k={w.k} n={w.n} ranks={w.ranks} lens={w.seg_lens}", flush=True)
+    dl = DeviceLayer(w)
+    dl.forward()
+    dl.backward()
+    dl.sync()
+    fw = orc.forward(w.X, w.W, w.A, w.B, w.scales, w.offsets)
+    bw = orc.backward(w.dY, w.X, w.W, w.A, w.B, w.scales, w.offsets)
+    errs = {"Y": rel_fro(to_host(dl.Y), fw.Y), "dX": rel_fro(to_host(dl.dX), bw.dX)}
+    S, dS = dl.S_list(), dl.dS_list()
+    for i in range(w.N):
+        errs[f"S{i}"] = rel_fro(S[i], fw.S[i])
+        errs[f"dS{i}"] = rel_fro(dS[i], bw.dS[i])
+        errs[f"dA{i}"] = rel_fro(to_host(dl.dA[i]), bw.dA[i])
+        errs[f"dB{i}"] = rel_fro(to_host(dl.dB[i]), bw.dB[i])
+    worst = max(errs.items(), key=lambda kv: kv[1])
+    print(f"        worst {worst[0]} = {worst[1]:.3e}", flush=True)
+    bad = {k: v for k, v in errs.items() if not v <= tol}
+    assert not bad, bad
+    return dl, fw, bw
+
+
+# ---- bookkeeping ------------------------------------------------------------------------
+def test_plan_tables_bit_exact():
+    rng = np.random.default_rng(0)
+    cases = [([0, 5, 5, 12], [8, 8, 16]), ([0, 0], [4]), ([0, 300], [0])]
+    for _ in range(12):
+        N = int(rng.integers(1, 40))
+        lens = [int(x) for x in rng.integers(0, 3000, size=N)]
+        ranks = [int(x) for x in rng.choice([0, 1, 4, 8, 33, 64, 128], size=N)]
+        cases.append(([0] + [int(x) for x in np.cumsum(lens)], ranks))
+    for off, ranks in cases:
+        T = off[-1]
+        plan = ml.Plan(ml.BF16, T, 64, 64, ranks, [1.0] * len(ranks), off)
+        geo = plan.geometry()
+        assert plan.dump(ml.TABLE_ROW_BLOCKS) == tt.row_blocks(off, ranks, geo[ml.GEO_BLOCK_ROWS])
+        assert plan.dump(ml.TABLE_WGRAD_CHUNKS) == tt.row_blocks(off, ranks, geo[ml.GEO_WGRAD_CHUNK_ROWS])
+        assert plan.dump(ml.TABLE_GEMM_ROW_TILES) == tt.gemm_row_tiles(off, geo[ml.GEO_GEMM_TILE_ROWS])
+        lens = [off[i + 1] - off[i] for i in range(len(ranks))]
+        assert plan.R1 == sum(t * r for t, r in zip(lens, ranks))
+        plan.destroy()
+
+
+# ---- config 1: tiny fp32 ------------------------------------------------------------------
+def test_config_tiny_fp32_full_oracle():
+    check_full(wl.config(0))
+
+
+def test_fp32_ragged_small():
+    w = wl.small_case(seed=21, dtype="f32", k=200, n=136, ranks=(4, 16, 0, 33, 128, 8),
+                      seg_lens=(129, 1, 70, 257, 65, 0), b_sigma=0.3)
+    check_full(w)
+
+
+# ---- bf16 MFMA path: ragged small cases spanning several tiles ------------------------------
+@pytest.mark.parametrize("seed,k,n,ranks,lens", [
+    (31, 512, 768, (4, 16, 0, 33, 128, 8), (129, 1, 70, 257, 300, 0)),
+    (32, 320, 264, (1, 3, 12, 100, 64), (63, 257, 5, 200, 1100)),     # k, n not multiples of the tile
+    (33, 1024, 512, (8, 8, 16, 64), (256, 256, 512, 1300)),           # a segment split over wgrad chunks
+    (34, 64, 8, (128,), (2100,)),
+])
+def test_bf16_ragged_small(seed, k, n, ranks, lens):
+    w = wl.small_case(seed=seed, dtype="bf16", k=k, n=n, ranks=ranks, seg_lens=lens,
+                      scales=[2.0, 0.5, 1.0, 16.0 / 33.0, 0.125, 3.0][: len(ranks)], b_sigma=0.3)
+    check_full(w)
+
+
+def test_bf16_odd_widths_use_fma_kernels():
+    w = wl.small_case(seed=35, dtype="bf16", k=100, n=52, ranks=(4, 7, 0, 16), seg_lens=(33, 64, 10, 70),
+                      scales=(2.0, 0.5, 1.0, 1.5), b_sigma=0.3)
+    dl, _, _ = check_full(w)
+    assert dl.plan.geometry()[ml.GEO_USES_MFMA] == 0
+
+
+def test_bf16_aligned_uses_mfma_kernels():
+    w = wl.small_case(seed=36, dtype="bf16", k=128, n=128, ranks=(8,), seg_lens=(100,), scales=(1.0,))
+    dl, _, _ = check_full(w)
+    assert dl.plan.geometry()[ml.GEO_USES_MFMA] == 1
+
+
+# ---- flags -------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_base_only_and_lora_only_modes(dtype):
+    w = wl.small_case(seed=41, dtype=dtype, k=256, n=384, ranks=(4, 16, 0, 40, 8), seg_lens=(129, 1, 70, 257, 90),
+                      scales=(2.0, 0.5, 1.0, 0.4, 3.0), b_sigma=0.3)
+    tol = TOL[dtype]
+    fw = orc.forward(w.X, w.W, w.A, w.B, w.scales, w.offsets, want_base=True)
+    bw = orc.backward(w.dY, w.X, w.W, w.A, w.B, w.scales, w.offsets)
+    dl = DeviceLayer(w)
+    dl.forward(ml.FLAG_BASE_ONLY); dl.backward(ml.FLAG_BASE_ONLY); dl.sync()
+    assert rel_fro(to_host(dl.Y), fw.Ybase) <= tol
+    dXbase = w.dY.astype(np.float64) @ w.W.astype(np.float64).T
+    assert rel_fro(to_host(dl.dX), dXbase) <= tol
+    # LoRA-only: Y and dX start at zero, so they end up holding the LoRA terms alone
+    dl.Y.zero_(); dl.dX.zero_()
+    dl.forward(ml.FLAG_LORA_ONLY); dl.backward(ml.FLAG_LORA_ONLY); dl.sync()
+    assert rel_fro(to_host(dl.Y), fw.Y - fw.Ybase) <= tol
+    assert rel_fro(to_host(dl.dX), bw.dX - dXbase) <= tol
+    for i in range(w.N):
+        assert rel_fro(to_host(dl.dA[i]), bw.dA[i]) <= tol and rel_fro(to_host(dl.dB[i]), bw.dB[i]) <= tol
+    # LoRA-only on top of a base-only result reproduces the fused result within tolerance
+    dl.forward(ml.FLAG_BASE_ONLY); dl.forward(ml.FLAG_LORA_ONLY); dl.sync()
+    assert rel_fro(to_host(dl.Y), fw.Y) <= tol
+
+
+# ---- degenerate shapes ----------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_no_adapters_and_no_tokens(dtype):
+    w = wl.make_workload("noadapters", dtype, 128, 64, [], [], [], seed=50)
+    assert w.T == 0
+    dl = DeviceLayer(w); dl.forward(); dl.backward(); dl.sync()           # T = 0, N = 0: nothing to do
+    w = wl.make_workload("rank0", dtype, 128, 64, [0], [37], [1.0], seed=51)
+    dl, fw, _ = check_full(w)                                                # plain X W
+    w = wl.make_workload("emptyseg", dtype, 128, 64, [8, 16], [0, 300], [1.0, 2.0], seed=52)
+    dl, _, _ = check_full(w)                                                 # adapter 0 has a rank but no tokens
+    assert torch.all(dl.dA[0] == 0) and torch.all(dl.dB[0] == 0)
+
+
+def test_single_token_segments():
+    w = wl.make_workload("ones", "bf16", 256, 256, [4, 8, 16, 32, 5], [1, 1, 1, 1, 1],
+                         [1.0, 2.0, 0.5, 0.25, 3.0], seed=53, b_sigma=0.3)
+    check_full(w)
+
+
+# ---- determinism and isolation ----------------------------------------------------------------------
+def test_repeat_runs_are_bit_identical_and_adapters_are_isolated():
+    w = wl.small_case(seed=61, dtype="bf16", k=512, n=512, ranks=(8, 64, 16), seg_lens=(300, 1200, 77),
+                      scales=(2.0, 0.25, 1.0), b_sigma=0.3)
+    dl = DeviceLayer(w); dl.forward(); dl.backward(); dl.sync()
+    first = [t.clone() for t in (dl.Y, dl.dX, dl.S, *dl.dA, *dl.dB)]
+    dl.forward(); dl.backward(); dl.sync()
+    for a, b in zip(first, (dl.Y, dl.dX, dl.S, *dl.dA, *dl.dB)):
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+    # perturb adapter 1: rows of the other segments and the other adapters' gradients keep their bits
+    dl.A[1].mul_(1.5); dl.B[1].add_(0.25)
+    dl.forward(); dl.backward(); dl.sync()
+    lo, hi = w.offsets[1], w.offsets[2]
+    keep = torch.ones(w.T, dtype=torch.bool, device=dl.Y.device); keep[lo:hi] = False
+    assert torch.equal(first[0][keep].view(torch.int16), dl.Y[keep].view(torch.int16))
+    assert torch.equal(first[1][keep].view(torch.int16), dl.dX[keep].view(torch.int16))
+    assert not torch.equal(first[0][lo:hi].view(torch.int16), dl.Y[lo:hi].view(torch.int16))
+    for i in (0, 2):
+        assert torch.equal(first[3 + i].view(torch.int16), dl.dA[i].view(torch.int16))
+        assert torch.equal(first[6 + i].view(torch.int16), dl.dB[i].view(torch.int16))
+
+
+def test_equal_length_batch_matches_same_data_run_as_ragged_neighbours():
+    # equal token counts are just a special case of the ragged path (the paper's bmm fast path and
+    # its grouped_mm path must agree): results for an adapter do not depend on its neighbours' lengths
+    base = wl.small_case(seed=62, dtype="bf16", k=256, n=256, ranks=(16, 16, 16), seg_lens=(128, 128, 128),
+                         scales=(1.0, 1.0, 1.0), b_sigma=0.3)
+    dl = DeviceLayer(base); dl.forward(); dl.backward(); dl.sync()
+    # same middle adapter, neighbours shortened -> ragged offsets
+    keep = np.r_[0:50, 128:256, 256:300]
+    rag = wl.Workload(name="rag", dtype="bf16", T=len(keep), k=256, n=256, ranks=base.ranks, scales=base.scales,
+                      offsets=[0, 50, 178, 222], X=base.X[keep], W=base.W, A=base.A, B=base.B, dY=base.dY[keep])
+    dr = DeviceLayer(rag); dr.forward(); dr.backward(); dr.sync()
+    assert rel_fro(to_host(dr.Y[50:178]), to_host(dl.Y[128:256])) <= 1e-6
+    assert rel_fro(to_host(dr.dA[1]), to_host(dl.dA[1])) <= 1e-2
+    assert rel_fro(to_host(dr.dX[50:178]), to_host(dl.dX[128:256])) <= 1e-6
+
+
+# ---- error paths that need a live plan ----------------------------------------------------------------
+def test_fwd_bwd_argument_errors():
+    w = wl.small_case(seed=63, dtype="bf16", k=64, n=64, ranks=(8,), seg_lens=(10,), scales=(1.0,))
+    dl = DeviceLayer(w)
+    with pytest.raises(ml.MultiLoraError) as e:
+        ml.multi_lora_fwd(dl.plan, dl.X, dl.W, dl.A, dl.B, dl.Y, dl.S, dl.workspace, 3, dl.stream)
+    assert e.value.status == -9
+    with pytest.raises(ml.MultiLoraError) as e:
+        ml.multi_lora_fwd(dl.plan, dl.X, dl.W, dl.A, dl.B, dl.Y, dl.S, dl.workspace, 64, dl.stream)
+    assert e.value.status == -9
+    with pytest.raises(ml.MultiLoraError) as e:
+        ml.multi_lora_fwd(dl.plan, None, dl.W, dl.A, dl.B, dl.Y, dl.S, dl.workspace, 0, dl.stream)
+    assert e.value.status == -1
+    with pytest.raises(ml.MultiLoraError) as e:
+        ml.multi_lora_fwd(dl.plan, dl.X.data_ptr() + 2, dl.W, dl.A, dl.B, dl.Y, dl.S, dl.workspace, 0, dl.stream)
+    assert e.value.status == -6
+    with pytest.raises(ml.MultiLoraError) as e:
+        ml.multi_lora_fwd(dl.plan, dl.X, dl.W, [None], dl.B, dl.Y, dl.S, dl.workspace, 0, dl.stream)
+    assert e.value.status == -1
+    with pytest.raises(ml.MultiLoraError) as e:
+        ml.multi_lora_bwd(dl.plan, dl.dY, dl.X, dl.W, dl.A, dl.B, dl.S, dl.dX, dl.dA, dl.dB, None, 0, dl.stream)
+    assert e.value.status == -7
+    dl.forward(); dl.backward(); dl.sync()      # the plan still works after rejected calls
