@@ -1,0 +1,186 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused multi-LoRA layer (forward + backward) on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config I] [--no-cpu]
+
+A step is one pass of the whole hot path -- multi_lora_fwd then multi_lora_bwd in fused mode --
+over one synthetic batch that is already resident in HBM.  The default workload is the
+Llama-8B q_proj config (8 adapters x 2048 tokens, ranks 8..64, W 4096 x 4096, bf16).
+Prints one JSON line: whole-job tokens/s, ms per step, the roofline of the dominant kernel
+(per-kernel times from HIP events recorded on the launch stream), the LoRA-only path against
+the HBM roofline, and the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_MFMA_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
+PEAK_HBM_GBS = 8000.0            # MI355X HBM3E
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=2, help="benchmark config number 1..5 (default 2: Llama-8B q_proj)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--no-extra", action="store_true", help="skip the per-kernel / LoRA-only passes")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
+              "run with --gpus 1. Adapters would shard across GPUs as disjoint row segments.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2604_05426_amd import binding as ml
+    from paper_2604_05426_amd import workloads as wl
+    from paper_2604_05426_amd.harness import DeviceLayer
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        return 3
+    ml.lib()   # fail loudly if the extension is missing
+
+    index = args.config - 1
+    w = wl.config(index)
+    dl = DeviceLayer(w, canary=0.0)
+    K, W = args.steps, args.warmup
+    T, k, n, R1 = w.T, w.k, w.n, w.R1
+    e = 2 if w.dtype == "bf16" else 4
+    sum_r = sum(r for r, t in zip(w.ranks, w.seg_lens) if t > 0)
+
+    def step(flags=0):
+        dl.forward(flags)
+        dl.backward(flags)
+
+    def timed(fn, reps):
+        start, end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        start.record()
+        for _ in range(reps):
+            fn()
+        end.record()
+        torch.cuda.synchronize()
+        return start.elapsed_time(end) / reps
+
+    for _ in range(W):
+        step()
+    ms_step = timed(step, K)
+
+    flops_base = 4.0 * T * k * n
+    flops_lora = 6.0 * R1 * (k + n)
+    flops = flops_base + flops_lora
+    tokens_per_s = T / (ms_step * 1e-3)
+    out = {
+        "metric": "multi-LoRA layer fwd+bwd tokens/s", "value": tokens_per_s, "unit": "tokens/s",
+        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": ms_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": f"config{args.config}:{w.name}", "T": T, "k": k, "n": n, "adapters": w.N,
+                   "ranks": w.ranks, "tokens_per_adapter": w.seg_lens, "mode": "fused fwd+bwd"},
+        "tflops": flops / (ms_step * 1e-3) / 1e12,
+        "frac_bf16_mfma_peak_whole_step": flops / (ms_step * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS,
+    }
+
+    if not args.no_extra:
+        # per-kernel times: the same K steps again, every launch bracketed by HIP events on its stream
+        dl.plan.profile_begin(K * 16)
+        for _ in range(K):
+            step()
+        recs = dl.plan.profile_end(K * 16)
+        per = {}
+        for kid, ms in recs:
+            per.setdefault(ml.KERNEL_NAMES[kid], []).append(ms)
+        kern = {name: {"launches_per_step": len(v) / K, "avg_ms": float(np.mean(v))} for name, v in per.items()}
+        # algorithmic work of one launch of each kernel
+        alg = {
+            "gemm_fwd": ("mfma", 2.0 * T * k * n + 2.0 * R1 * n),
+            "gemm_bwd": ("mfma", 2.0 * T * k * n + 2.0 * R1 * k),
+            "shrink": ("hbm", (T * k + sum_r * k + R1) * e),
+            "dshrink": ("hbm", (T * n + sum_r * n + R1) * e),
+            "wgrad": ("hbm", (T * k + T * n + 2 * R1 + sum_r * (k + n)) * e),
+        }
+        for name, (bound, work) in alg.items():
+            if name in kern:
+                t = kern[name]["avg_ms"] * 1e-3
+                if bound == "mfma":
+                    kern[name].update(bound="mfma", achieved_tflops=work / t / 1e12,
+                                      frac=work / t / 1e12 / PEAK_BF16_MFMA_TFLOPS)
+                else:
+                    kern[name].update(bound="hbm", achieved_gbs=work / t / 1e9, frac=work / t / 1e9 / PEAK_HBM_GBS)
+        out["kernels"] = kern
+        dom = max((nm for nm in kern if nm in alg), key=lambda nm: kern[nm]["avg_ms"] * kern[nm]["launches_per_step"])
+        bound, work = alg[dom]
+        t = kern[dom]["avg_ms"] * 1e-3
+        if bound == "mfma":
+            out["roofline"] = {"kernel": dom, "bound": "mfma", "achieved": work / t / 1e12, "peak": PEAK_BF16_MFMA_TFLOPS,
+                               "unit": "TFLOP/s", "frac": work / t / 1e12 / PEAK_BF16_MFMA_TFLOPS, "traffic": None,
+                               "avg_kernel_ms": kern[dom]["avg_ms"]}
+        else:
+            out["roofline"] = {"kernel": dom, "bound": "hbm", "achieved": work / t / 1e9, "peak": PEAK_HBM_GBS,
+                               "unit": "GB/s", "frac": work / t / 1e9 / PEAK_HBM_GBS, "traffic": None,
+                               "avg_kernel_ms": kern[dom]["avg_ms"]}
+
+        # LoRA grouped path alone (W skipped; Y and dX updated in place) against the HBM roofline
+        for _ in range(2):
+            step(ml.FLAG_LORA_ONLY)
+        ms_lf = timed(lambda: dl.forward(ml.FLAG_LORA_ONLY), K)
+        ms_lb = timed(lambda: dl.backward(ml.FLAG_LORA_ONLY), K)
+        small = (2 * sum_r * (k + n) + 2 * R1) * e
+        bytes_f = (T * k + 2 * T * n) * e + (sum_r * (k + n) + 2 * R1) * e
+        bytes_b = (2 * T * n + T * k + 2 * T * k) * e + small + 3 * R1 * e
+        out["lora_path"] = {
+            "mode": "MLORA_FLAG_LORA_ONLY", "fwd_ms": ms_lf, "bwd_ms": ms_lb,
+            "fwd_gbs": bytes_f / (ms_lf * 1e-3) / 1e9, "bwd_gbs": bytes_b / (ms_lb * 1e-3) / 1e9,
+            "frac_hbm": (bytes_f + bytes_b) / ((ms_lf + ms_lb) * 1e-3) / 1e9 / PEAK_HBM_GBS,
+            "algorithmic_bytes_fwd": bytes_f, "algorithmic_bytes_bwd": bytes_b,
+        }
+        # frozen-weight GEMMs alone, for the cost of the LoRA terms inside the fused step
+        for _ in range(2):
+            step(ml.FLAG_BASE_ONLY)
+        ms_base = timed(lambda: step(ml.FLAG_BASE_ONLY), K)
+        out["base_only"] = {"ms_per_step": ms_base, "tflops": flops_base / (ms_base * 1e-3) / 1e12,
+                            "frac_bf16_mfma_peak": flops_base / (ms_base * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS,
+                            "fused_over_base": ms_step / ms_base}
+
+    if not args.no_cpu:
+        # CPU oracle (as it stands) on a bounded sample: the first rows of every adapter's segment
+        from oracle import multilora_oracle as orc
+        def sample(per_adapter):
+            keep, lens = [], []
+            for i in range(w.N):
+                c = min(per_adapter, w.seg_lens[i])
+                keep.extend(range(w.offsets[i], w.offsets[i] + c))
+                lens.append(c)
+            off = [0] + [int(x) for x in np.cumsum(lens)]
+            Xs, dYs = np.ascontiguousarray(w.X[keep]), np.ascontiguousarray(w.dY[keep])
+            t0 = time.perf_counter()
+            fw = orc.forward(Xs, w.W, w.A, w.B, w.scales, off)
+            orc.backward(dYs, Xs, w.W, w.A, w.B, w.scales, off, S=fw.S)
+            return len(keep), time.perf_counter() - t0
+
+        # a short calibration run sizes the sample for roughly 15 s of CPU work (capped at the whole batch)
+        cal_tokens, cal_dt = sample(max(1, 256 // max(1, w.N)))
+        per_adapter = int(max(1, min(max(w.seg_lens), (15.0 / max(cal_dt, 1e-3)) * cal_tokens / max(1, w.N))))
+        ntok, dt = sample(per_adapter)
+        keep = range(ntok)
+        out["cpu_baseline"] = {"value": len(keep) / dt, "unit": "tokens/s", "cores": orc.num_threads(),
+                               "kind": "oracle", "seconds": dt,
+                               "sample": f"first {per_adapter} tokens of each of the {w.N} adapters "
+                                         f"({len(keep)} of {T} tokens), full fwd+bwd, naive fp64 loops"}
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -159,6 +159,29 @@ int multi_lora_bwd(mlora_plan* plan, const void* dY, const void* X, const void* 
                    void* const* dA, void* const* dB, void* workspace, uint32_t flags,
                    void* stream);
 
+/* kernel ids reported by multi_lora_profile_end */
+enum {
+    MLORA_K_SHRINK = 0,      /* S_i = X_i A_i (grouped) */
+    MLORA_K_GEMM_FWD = 1,    /* Y = X W + s_i S_i B_i (fused) */
+    MLORA_K_DSHRINK = 2,     /* dS_i = s_i dY_i B_i^T (grouped) */
+    MLORA_K_GEMM_BWD = 3,    /* dX = dY W^T + dS_i A_i^T (fused) */
+    MLORA_K_WGRAD = 4,       /* dA_i, dB_i token reductions (grouped) */
+    MLORA_K_WGRAD_REDUCE = 5,/* fixed-order sum of chunk partials */
+    MLORA_K_OTHER = 6        /* pointer upload, descriptor set-up, FMA-path launches */
+};
+
+/*
+ * Per-kernel timing for benchmarks (not from the paper; a measurement aid).  Between
+ * multi_lora_profile_begin and multi_lora_profile_end every kernel the plan launches is
+ * bracketed by HIP events recorded on the launch stream.  `max_records` bounds the number of
+ * launches recorded (later ones are ignored).  multi_lora_profile_end waits for the recorded
+ * work, writes up to `cap` (kernel id, milliseconds) pairs to `kernel_ids` / `ms` (host arrays),
+ * the number of records to `count`, and switches recording off.
+ */
+int multi_lora_profile_begin(mlora_plan* plan, int32_t max_records);
+int multi_lora_profile_end(mlora_plan* plan, int32_t* kernel_ids, float* ms, int32_t cap,
+                           int32_t* count);
+
 /* Thread-local text of the last error returned on this thread ("" if none). */
 const char* multi_lora_last_error(void);
 

@@ -28,7 +28,10 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmultilor
 # every symbol include/multi_lora.h declares
 EXPORTS = ["multi_lora_plan_create", "multi_lora_plan_destroy", "multi_lora_validate",
            "multi_lora_workspace_bytes", "multi_lora_plan_geometry", "multi_lora_plan_dump",
-           "multi_lora_fwd", "multi_lora_bwd", "multi_lora_last_error", "multi_lora_version"]
+           "multi_lora_fwd", "multi_lora_bwd", "multi_lora_last_error", "multi_lora_version",
+           "multi_lora_profile_begin", "multi_lora_profile_end"]
+
+KERNEL_NAMES = {0: "shrink", 1: "gemm_fwd", 2: "dshrink", 3: "gemm_bwd", 4: "wgrad", 5: "wgrad_reduce", 6: "other"}
 
 
 class MultiLoraError(RuntimeError):
@@ -65,6 +68,10 @@ def lib() -> ctypes.CDLL:
         L.multi_lora_fwd.restype = ctypes.c_int
         L.multi_lora_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, u32, vp]
         L.multi_lora_bwd.restype = ctypes.c_int
+        L.multi_lora_profile_begin.argtypes = [vp, i32]
+        L.multi_lora_profile_begin.restype = ctypes.c_int
+        L.multi_lora_profile_end.argtypes = [vp, vp, vp, i32, ctypes.POINTER(i32)]
+        L.multi_lora_profile_end.restype = ctypes.c_int
         L.multi_lora_last_error.restype = ctypes.c_char_p
         L.multi_lora_version.restype = ctypes.c_char_p
         _lib = L
@@ -150,6 +157,17 @@ class Plan:
         buf = (ctypes.c_int32 * (4 * max(n, 1)))()
         _check(lib().multi_lora_plan_dump(self._h, table, buf, n, ctypes.byref(cnt)))
         return [tuple(buf[4 * i: 4 * i + 4]) for i in range(n)]
+
+    def profile_begin(self, max_records: int) -> None:
+        _check(lib().multi_lora_profile_begin(self._h, max_records))
+
+    def profile_end(self, cap: int) -> List[tuple]:
+        """[(kernel id, milliseconds), ...] for every launch recorded since profile_begin."""
+        ids = (ctypes.c_int32 * max(cap, 1))()
+        ms = (ctypes.c_float * max(cap, 1))()
+        cnt = ctypes.c_int32(0)
+        _check(lib().multi_lora_profile_end(self._h, ids, ms, cap, ctypes.byref(cnt)))
+        return [(int(ids[i]), float(ms[i])) for i in range(min(cnt.value, cap))]
 
     def destroy(self) -> None:
         if self._h:

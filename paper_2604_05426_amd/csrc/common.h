@@ -75,6 +75,11 @@ struct mlora_plan {
     size_t ws_partial_bytes = 0;      // workspace: fp32 partial weight gradients
     hipStream_t build_stream = nullptr;
     int num_cus = 256;
+    // per-kernel event timing (multi_lora_profile_begin / _end)
+    bool prof_on = false;
+    int32_t prof_used = 0;
+    std::vector<int32_t> prof_kernel;
+    std::vector<hipEvent_t> prof_start, prof_stop;
 };
 
 namespace mlora {
@@ -87,6 +92,23 @@ int hip_fail(hipError_t e, const char* what);
         hipError_t e__ = (expr);                              \
         if (e__ != hipSuccess) return ::mlora::hip_fail(e__, #expr); \
     } while (0)
+
+// Brackets one kernel launch with events while profiling is on (no-op otherwise).
+struct ProfScope {
+    mlora_plan* p;
+    hipStream_t st;
+    int32_t idx = -1;
+    ProfScope(mlora_plan* plan, int kernel, hipStream_t stream) : p(plan), st(stream) {
+        if (p->prof_on && p->prof_used < (int32_t)p->prof_start.size()) {
+            idx = p->prof_used++;
+            p->prof_kernel[idx] = kernel;
+            (void)hipEventRecord(p->prof_start[idx], st);
+        }
+    }
+    ~ProfScope() {
+        if (idx >= 0) (void)hipEventRecord(p->prof_stop[idx], st);
+    }
+};
 
 // plan.hip
 int upload_ptrs(mlora_plan* p, const void* const* A, const void* const* B, void* const* dA,

@@ -218,6 +218,7 @@ template <typename T>
 static int run_grouped(mlora_plan* p, const FmaOperands& ops, int op, int slot, hipStream_t st) {
     if (p->N == 0) return MLORA_OK;
     GProb* probs = (GProb*)((char*)p->d_probs + (size_t)128 * ((size_t)slot * (p->N + 1)));
+    ProfScope prof(p, MLORA_K_OTHER, st);
     hipLaunchKernelGGL(fma_make_probs_kernel<T>, dim3(1), dim3(256), 0, st, p->view, ops, op, probs);
     const int64_t tiles = grouped_tiles(p, op);
     if (tiles > 0)
@@ -234,6 +235,7 @@ static int run_single(mlora_plan* p, const void* A, const void* B, void* C, int6
     g.A = A; g.B = B; g.C = C; g.lda = lda; g.ldb = ldb; g.ldc = ldc;
     g.M = (int32_t)M; g.N = (int32_t)N; g.K = (int32_t)K; g.transB = transB; g.alpha = 1.0f;
     GProb* probs = (GProb*)((char*)p->d_probs + (size_t)128 * ((size_t)4 * (p->N + 1)));
+    ProfScope prof(p, MLORA_K_OTHER, st);
     hipLaunchKernelGGL(fma_single_prob_kernel, dim3(1), dim3(64), 0, st, g, probs);
     hipLaunchKernelGGL(fma_grouped_gemm_kernel<T>, dim3((unsigned)tiles2(M, N)), dim3(256), 0, st, probs, 1);
     MLORA_HIP_TRY(hipGetLastError());

@@ -241,6 +241,7 @@ static int launch_gemm(mlora_plan* p, bool fwd, const void* Aop, const void* W, 
     g.pv = p->view;
     const int total = g.tiles_m * g.tiles_n;
     const int grid = ((total + 7) / 8) * 8;
+    ProfScope prof(p, fwd ? MLORA_K_GEMM_FWD : MLORA_K_GEMM_BWD, st);
     if (fwd) hipLaunchKernelGGL(fused_gemm_kernel<true>, dim3(grid), dim3(256), 0, st, g);
     else     hipLaunchKernelGGL(fused_gemm_kernel<false>, dim3(grid), dim3(256), 0, st, g);
     MLORA_HIP_TRY(hipGetLastError());

@@ -339,6 +339,7 @@ int mfma_forward(mlora_plan* p, const void* X, const void* W, void* Y, void* S, 
     if (lora && p->n_row_blocks > 0) {
         ShrinkArgs a{};
         a.src = (const u16*)X; a.ld = p->k; a.out = (u16*)S; a.Kdim = (int32_t)p->k; a.pv = p->view;
+        ProfScope prof(p, MLORA_K_SHRINK, st);
         hipLaunchKernelGGL(shrink_kernel<true>, dim3(p->n_row_blocks), dim3(256), 0, st, a);
         MLORA_HIP_TRY(hipGetLastError());
     }
@@ -351,6 +352,7 @@ int mfma_backward(mlora_plan* p, const void* dY, const void* X, const void* W, c
     if (lora && p->n_row_blocks > 0) {
         ShrinkArgs a{};
         a.src = (const u16*)dY; a.ld = p->n; a.out = (u16*)dS; a.Kdim = (int32_t)p->n; a.pv = p->view;
+        ProfScope prof(p, MLORA_K_DSHRINK, st);
         hipLaunchKernelGGL(shrink_kernel<false>, dim3(p->n_row_blocks), dim3(256), 0, st, a);
         MLORA_HIP_TRY(hipGetLastError());
     }
@@ -366,13 +368,18 @@ int mfma_backward(mlora_plan* p, const void* dY, const void* X, const void* W, c
         w.part_off = p->d_part_off;
         if (p->n_wgrad_chunks > 0) {
             const int64_t grid = (int64_t)p->n_wgrad_chunks * (w.panels_k + w.panels_n);
-            hipLaunchKernelGGL(wgrad_kernel, dim3((unsigned)grid), dim3(256), 0, st, w);
+            {
+                ProfScope prof(p, MLORA_K_WGRAD, st);
+                hipLaunchKernelGGL(wgrad_kernel, dim3((unsigned)grid), dim3(256), 0, st, w);
+            }
             if (p->max_chunks_per_adapter > 1) {
                 const int64_t per = (p->k + p->n) * (int64_t)p->max_rank;
+                ProfScope prof(p, MLORA_K_WGRAD_REDUCE, st);
                 hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)((per + 255) / 256), p->N), dim3(256), 0, st, w);
             }
         }
         if (p->has_empty_ranked) {
+            ProfScope prof(p, MLORA_K_OTHER, st);
             hipLaunchKernelGGL(wgrad_zero_empty_kernel, dim3(64, p->N), dim3(256), 0, st, p->view);
         }
         MLORA_HIP_TRY(hipGetLastError());

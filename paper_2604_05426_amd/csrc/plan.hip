@@ -114,6 +114,7 @@ int upload_ptrs(mlora_plan* p, const void* const* A, const void* const* B, void*
             batch.p[j].dA = dA ? dA[base + j] : nullptr;
             batch.p[j].dB = dB ? dB[base + j] : nullptr;
         }
+        ProfScope prof(p, MLORA_K_OTHER, st);
         hipLaunchKernelGGL(upload_ptrs_kernel, dim3(1), dim3(32), 0, st, p->d_ptrs, batch, base, cnt);
     }
     MLORA_HIP_TRY(hipGetLastError());
@@ -328,8 +329,76 @@ extern "C" int multi_lora_plan_create(mlora_plan** out, int dtype, int64_t T, in
     return MLORA_OK;
 }
 
+static void free_events(mlora_plan* plan) {
+    for (hipEvent_t ev : plan->prof_start) (void)hipEventDestroy(ev);
+    for (hipEvent_t ev : plan->prof_stop) (void)hipEventDestroy(ev);
+    plan->prof_start.clear();
+    plan->prof_stop.clear();
+    plan->prof_kernel.clear();
+    plan->prof_used = 0;
+    plan->prof_on = false;
+}
+
+extern "C" int multi_lora_profile_begin(mlora_plan* plan, int32_t max_records) {
+    if (!plan) {
+        set_error("plan is NULL");
+        return MLORA_ERR_NULL;
+    }
+    if (max_records < 1 || max_records > (1 << 20)) {
+        set_error("max_records must be in [1, 2^20]");
+        return MLORA_ERR_SHAPE;
+    }
+    free_events(plan);
+    plan->prof_start.resize(max_records);
+    plan->prof_stop.resize(max_records);
+    plan->prof_kernel.assign(max_records, MLORA_K_OTHER);
+    for (int32_t i = 0; i < max_records; ++i) {
+        hipError_t e = hipEventCreate(&plan->prof_start[i]);
+        if (e == hipSuccess) e = hipEventCreate(&plan->prof_stop[i]);
+        if (e != hipSuccess) {
+            plan->prof_start.resize(i);
+            plan->prof_stop.resize(i);
+            free_events(plan);
+            return hip_fail(e, "hipEventCreate");
+        }
+    }
+    plan->prof_on = true;
+    return MLORA_OK;
+}
+
+extern "C" int multi_lora_profile_end(mlora_plan* plan, int32_t* kernel_ids, float* ms, int32_t cap,
+                                      int32_t* count) {
+    if (!plan || !count) {
+        set_error("plan / count is NULL");
+        return MLORA_ERR_NULL;
+    }
+    plan->prof_on = false;
+    const int32_t used = plan->prof_used;
+    *count = used;
+    int rc = MLORA_OK;
+    for (int32_t i = 0; i < used && i < cap; ++i) {
+        if (!kernel_ids || !ms) {
+            set_error("kernel_ids / ms is NULL");
+            rc = MLORA_ERR_NULL;
+            break;
+        }
+        hipError_t e = hipEventSynchronize(plan->prof_stop[i]);
+        float t = 0.f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&t, plan->prof_start[i], plan->prof_stop[i]);
+        if (e != hipSuccess) {
+            rc = hip_fail(e, "hipEventElapsedTime");
+            break;
+        }
+        kernel_ids[i] = plan->prof_kernel[i];
+        ms[i] = t;
+    }
+    free_events(plan);
+    return rc;
+}
+
 extern "C" int multi_lora_plan_destroy(mlora_plan* plan) {
     if (!plan) return MLORA_OK;
+    free_events(plan);
     hipError_t e = hipSuccess;
     if (plan->d_block) e = hipFree(plan->d_block);
     delete plan;
