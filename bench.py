@@ -34,6 +34,10 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=2, help="benchmark config number 1..5 (default 2: Llama-8B q_proj)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-extra", action="store_true", help="skip the per-kernel / LoRA-only passes")
+    ap.add_argument("--fused-only", action="store_true",
+                    help="skip the LoRA-only and base-only passes (every launch is then the fused-mode one; used under rocprofv3)")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy 3 times (calibrates FETCH_SIZE / WRITE_SIZE under rocprofv3 --pmc)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
@@ -131,6 +135,7 @@ def main() -> int:
                                "unit": "GB/s", "frac": work / t / 1e9 / PEAK_HBM_GBS, "traffic": None,
                                "avg_kernel_ms": kern[dom]["avg_ms"]}
 
+    if not args.no_extra and not args.fused_only:
         # LoRA grouped path alone (W skipped; Y and dX updated in place) against the HBM roofline
         for _ in range(2):
             step(ml.FLAG_LORA_ONLY)
@@ -152,6 +157,14 @@ def main() -> int:
         out["base_only"] = {"ms_per_step": ms_base, "tflops": flops_base / (ms_base * 1e-3) / 1e12,
                             "frac_bf16_mfma_peak": flops_base / (ms_base * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS,
                             "fused_over_base": ms_step / ms_base}
+
+    if args.calib_copy:
+        src = torch.zeros(1 << 30, dtype=torch.uint8, device=dl.device)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        out["calib_copy_bytes"] = 1 << 30
 
     if not args.no_cpu:
         # CPU oracle (as it stands) on a bounded sample: the first rows of every adapter's segment
