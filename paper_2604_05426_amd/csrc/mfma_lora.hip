@@ -12,17 +12,24 @@ namespace mlora {
 // =========================================================================================
 // Shrink:   S_i  = X_i A_i            (FWD: A_i is [k][r], column index contiguous -> transposing reads)
 // dShrink:  dS_i = s_i dY_i B_i^T     (!FWD: B_i is [r][n], contraction contiguous)
-// One workgroup per row block (64 rows of one adapter); the 4 wavefronts split the contraction
-// (each takes one 16-wide slice of every 64-wide step) and their partial tiles are summed in LDS.
+// One workgroup per row block (64 rows of one adapter), 8 wavefronts.  The work is a pure
+// stream of X (or dY), so the kernel is built for bytes in flight: every wavefront owns a
+// contiguous slice of the contraction and runs its own register-prefetch -> private LDS tile
+// -> MFMA pipeline with no workgroup barrier in the loop, so eight independent streams per
+// CU keep loads outstanding.  The eight partial tiles are added in LDS in wavefront order
+// (deterministic) and rounded once.
 // =========================================================================================
-constexpr int SR = 64;            // rows per block == kBlockRows
-constexpr int SK = 64;            // contraction step
-constexpr int SA_LD = SK + 8;     // X / dY tile [64][72]
-constexpr int SBN_LD = 128 + 32;  // FWD small tile [64 contraction][160]
-constexpr int SBT_LD = SK + 8;    // !FWD small tile [128 rank rows][72]
-constexpr int SA_TILE = SR * SA_LD;                 // 4608
-constexpr int SB_TILE = 64 * SBN_LD;                // 10240 >= 128 * 72 = 9216
-constexpr int S_STAGE = SA_TILE + SB_TILE;
+constexpr int SR = 64;             // rows per block == kBlockRows
+constexpr int SKS = 32;            // contraction elements per wavefront step
+constexpr int SNW = 8;             // wavefronts per workgroup
+constexpr int SX_LD = SKS + 8;     // X / dY tile [64][40]: 80-byte rows, conflict-free 128-bit reads
+constexpr int SX_TILE = SR * SX_LD;
+constexpr int SBN_LD = 128 + 32;   // FWD small tile [32 contraction][160]
+constexpr int SB_TILE = 32 * SBN_LD;   // == 128 * SX_LD, the !FWD small tile [128 rank rows][40]
+static_assert(SB_TILE == 128 * SX_LD, "both small-tile layouts share one buffer size");
+constexpr int S_WAVE = SX_TILE + SB_TILE;   // per-wavefront private LDS (elements)
+constexpr int S_RLD = 132;                  // fp32 reduction tile row
+static_assert(SNW * S_WAVE * 2 >= SR * S_RLD * 4, "reduction tile fits in the staging buffers");
 static_assert(kBlockRows == SR, "row-block table and shrink kernel must agree");
 
 struct ShrinkArgs {
@@ -33,9 +40,9 @@ struct ShrinkArgs {
 };
 
 template <bool FWD>
-__global__ __launch_bounds__(256) void shrink_kernel(ShrinkArgs g) {
-    __shared__ __attribute__((aligned(16))) u16 lds[2 * S_STAGE];
-    static_assert(2 * S_STAGE * 2 >= SR * 132 * 4, "reduction buffer fits in the staging buffers");
+__global__ __launch_bounds__(64 * SNW) void shrink_kernel(ShrinkArgs g) {
+    __shared__ __attribute__((aligned(16))) u16 lds[SNW * S_WAVE];
+    typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const Entry4 e = g.pv.row_blocks[blockIdx.x];
     const int i = e.a, row0 = e.c, rows = e.d;
@@ -45,6 +52,8 @@ __global__ __launch_bounds__(256) void shrink_kernel(ShrinkArgs g) {
     const u16* F = (const u16*)(FWD ? g.pv.ptrs[i].A : g.pv.ptrs[i].B);
     const bool f_vec = FWD ? ((r & 7) == 0) : true;
     const float s = FWD ? 1.0f : g.pv.scale[i];
+    u16* Xs = lds + wave * S_WAVE;
+    u16* Fs = Xs + SX_TILE;
 
     f32x16 acc[2][4];
 #pragma unroll
@@ -54,93 +63,91 @@ __global__ __launch_bounds__(256) void shrink_kernel(ShrinkArgs g) {
 #pragma unroll
             for (int q = 0; q < 16; ++q) acc[mb][nb][q] = 0.f;
 
-    const int nk = (g.Kdim + SK - 1) / SK;
-    uint4 ra[2], rb[4];
-    auto gload = [&](int kt) {
-        const int k0 = kt * SK;
+    // this wavefront's slice of the contraction, in steps of 32
+    const int steps = (g.Kdim + SKS - 1) / SKS;
+    const int per = (steps + SNW - 1) / SNW;
+    const int s_begin = wave * per, s_end = min(steps, s_begin + per);
+
+    uint4 rx[4], rf[8];
+    auto gload = [&](int step) {
+        const int k0 = step * SKS;
 #pragma unroll
-        for (int jj = 0; jj < 2; ++jj) {
-            const int row = (tid >> 3) + 32 * jj, kc = tid & 7;
-            const int gk = k0 + kc * 8;
-            ra[jj] = (row < rows && gk < g.Kdim)
+        for (int jj = 0; jj < 4; ++jj) {
+            const int row = (lane >> 2) + 16 * jj, gk = k0 + (lane & 3) * 8;
+            rx[jj] = (row < rows && gk < g.Kdim)
                          ? *reinterpret_cast<const uint4*>(g.src + (int64_t)(row0 + row) * g.ld + gk) : zero4();
         }
-        if (FWD) {   // A_i[k0 + krow][chunk c of the rank]
 #pragma unroll
-            for (int jj = 0; jj < 4; ++jj) {
-                const int krow = (tid >> 4) + 16 * jj, cc = tid & 15;
-                rb[jj] = zero4();
-                if (cc * 8 < rpad && k0 + krow < g.Kdim)
-                    rb[jj] = load_chunk(F + (int64_t)(k0 + krow) * r + cc * 8, min(8, r - cc * 8), f_vec);
-            }
-        } else {     // B_i[rho][k0 + chunk]
-#pragma unroll
-            for (int jj = 0; jj < 4; ++jj) {
-                const int rho = (tid >> 3) + 32 * jj, kc = tid & 7;
-                const int gk = k0 + kc * 8;
-                rb[jj] = (rho < r && gk < g.Kdim)
-                             ? *reinterpret_cast<const uint4*>(F + (int64_t)rho * g.ld + gk) : zero4();
+        for (int jj = 0; jj < 8; ++jj) {
+            const int idx = lane + 64 * jj;
+            rf[jj] = zero4();
+            if (FWD) {   // A_i[k0 + kr][cc * 8 ..]
+                const int kr = idx >> 4, cc = idx & 15;
+                if (cc * 8 < rpad && k0 + kr < g.Kdim)
+                    rf[jj] = load_chunk(F + (int64_t)(k0 + kr) * r + cc * 8, min(8, r - cc * 8), f_vec);
+            } else {     // B_i[rho][k0 + c * 8 ..]
+                const int rho = idx >> 2, gk = k0 + (idx & 3) * 8;
+                if (rho < r && gk < g.Kdim) rf[jj] = *reinterpret_cast<const uint4*>(F + (int64_t)rho * g.ld + gk);
             }
         }
     };
-    auto lstore = [&](int stage) {
-        u16* As = lds + stage * S_STAGE;
-        u16* Bs = As + SA_TILE;
-#pragma unroll
-        for (int jj = 0; jj < 2; ++jj) {
-            const int row = (tid >> 3) + 32 * jj, kc = tid & 7;
-            *reinterpret_cast<uint4*>(As + row * SA_LD + kc * 8) = ra[jj];
-        }
+    auto lstore = [&]() {
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {
+            const int row = (lane >> 2) + 16 * jj;
+            *reinterpret_cast<uint4*>(Xs + row * SX_LD + (lane & 3) * 8) = rx[jj];
+        }
+#pragma unroll
+        for (int jj = 0; jj < 8; ++jj) {
+            const int idx = lane + 64 * jj;
             if (FWD) {
-                const int krow = (tid >> 4) + 16 * jj, cc = tid & 15;
-                *reinterpret_cast<uint4*>(Bs + krow * SBN_LD + cc * 8) = rb[jj];
+                const int kr = idx >> 4, cc = idx & 15;
+                if (cc * 8 < rpad) *reinterpret_cast<uint4*>(Fs + kr * SBN_LD + cc * 8) = rf[jj];
             } else {
-                const int rho = (tid >> 3) + 32 * jj, kc = tid & 7;
-                *reinterpret_cast<uint4*>(Bs + rho * SBT_LD + kc * 8) = rb[jj];
+                const int rho = idx >> 2;
+                if (rho < rpad) *reinterpret_cast<uint4*>(Fs + rho * SX_LD + (idx & 3) * 8) = rf[jj];
             }
         }
     };
     const int lm = lane & 31, h = lane >> 5, gq = lane >> 4, j = lane & 15;
-    auto compute = [&](int stage) {
-        const u16* As = lds + stage * S_STAGE;
-        const u16* Bs = As + SA_TILE;
-        const int ks = wave;   // this wavefront's 16-wide slice of the 64-wide step
-        bf16x8 a[2];
+    auto compute = [&]() {
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb) a[mb] = lds_read_frag(As + (mb * 32 + lm) * SA_LD + ks * 16 + h * 8);
+        for (int ks = 0; ks < SKS / 16; ++ks) {
+            bf16x8 a[2];
 #pragma unroll
-        for (int nb = 0; nb < 4; ++nb) {
-            if (nb < nblk) {
-                bf16x8 b;
-                if (FWD) {
-                    const u16* p = Bs + (ks * 16 + 8 * (gq >> 1) + (j >> 2)) * SBN_LD + nb * 32 + 16 * (gq & 1) + 4 * (j & 3);
-                    b = lds_read_frag_tr(p, p + 4 * SBN_LD);
-                } else {
-                    b = lds_read_frag(Bs + (nb * 32 + lm) * SBT_LD + ks * 16 + h * 8);
+            for (int mb = 0; mb < 2; ++mb) a[mb] = lds_read_frag(Xs + (mb * 32 + lm) * SX_LD + ks * 16 + h * 8);
+#pragma unroll
+            for (int nb = 0; nb < 4; ++nb) {
+                if (nb < nblk) {
+                    bf16x8 b;
+                    if (FWD) {
+                        const u16* p = Fs + (ks * 16 + 8 * (gq >> 1) + (j >> 2)) * SBN_LD + nb * 32 + 16 * (gq & 1) + 4 * (j & 3);
+                        b = lds_read_frag_tr(p, p + 4 * SBN_LD);
+                    } else {
+                        b = lds_read_frag(Fs + (nb * 32 + lm) * SX_LD + ks * 16 + h * 8);
+                    }
+#pragma unroll
+                    for (int mb = 0; mb < 2; ++mb) acc[mb][nb] = mfma32(a[mb], b, acc[mb][nb]);
                 }
-#pragma unroll
-                for (int mb = 0; mb < 2; ++mb) acc[mb][nb] = mfma32(a[mb], b, acc[mb][nb]);
             }
         }
     };
 
-    gload(0);
-    lstore(0);
-    __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-        const int cur = kt & 1;
-        if (kt + 1 < nk) gload(kt + 1);
-        compute(cur);
-        if (kt + 1 < nk) lstore(cur ^ 1);
-        __syncthreads();
+    // LDS tiles are private to the wavefront and LDS operations of one wavefront execute in order,
+    // so the loop needs no workgroup barrier: write the tile, start the next loads, compute.
+    if (s_begin < s_end) {
+        gload(s_begin);
+        for (int st = s_begin; st < s_end; ++st) {
+            lstore();
+            if (st + 1 < s_end) gload(st + 1);
+            compute();
+        }
     }
+    __syncthreads();
 
-    // sum the four wavefronts' partial tiles in a fixed order (deterministic), then store
+    // add the eight partial tiles in wavefront order, then store
     float* red = reinterpret_cast<float*>(lds);   // [64][132]
-    constexpr int RLD = 132;
-    for (int w = 0; w < 4; ++w) {
+    for (int w = 0; w < SNW; ++w) {
         if (wave == w) {
 #pragma unroll
             for (int mb = 0; mb < 2; ++mb)
@@ -150,7 +157,7 @@ __global__ __launch_bounds__(256) void shrink_kernel(ShrinkArgs g) {
 #pragma unroll
                     for (int q = 0; q < 16; ++q) {
                         const int row = mb * 32 + (q >> 2) * 8 + h * 4 + (q & 3);
-                        float* d = red + row * RLD + nb * 32 + lm;
+                        float* d = red + row * S_RLD + nb * 32 + lm;
                         *d = (w == 0) ? acc[mb][nb][q] : (*d + acc[mb][nb][q]);
                     }
                 }
@@ -160,9 +167,9 @@ __global__ __launch_bounds__(256) void shrink_kernel(ShrinkArgs g) {
     const int64_t so = g.pv.soff[i];
     const int seg0 = g.pv.off[i];
     u16* out = g.out + so + (int64_t)(row0 - seg0) * r;
-    for (int idx = tid; idx < rows * r; idx += 256) {
+    for (int idx = tid; idx < rows * r; idx += 64 * SNW) {
         const int row = idx / r, col = idx - row * r;
-        out[idx] = f2bf(s * red[row * RLD + col]);
+        out[idx] = f2bf(s * red[row * S_RLD + col]);
     }
 }
 
@@ -340,7 +347,7 @@ int mfma_forward(mlora_plan* p, const void* X, const void* W, void* Y, void* S, 
         ShrinkArgs a{};
         a.src = (const u16*)X; a.ld = p->k; a.out = (u16*)S; a.Kdim = (int32_t)p->k; a.pv = p->view;
         ProfScope prof(p, MLORA_K_SHRINK, st);
-        hipLaunchKernelGGL(shrink_kernel<true>, dim3(p->n_row_blocks), dim3(256), 0, st, a);
+        hipLaunchKernelGGL(shrink_kernel<true>, dim3(p->n_row_blocks), dim3(64 * SNW), 0, st, a);
         MLORA_HIP_TRY(hipGetLastError());
     }
     return mfma_gemm_fwd(p, X, W, Y, S, flags, st);
@@ -353,7 +360,7 @@ int mfma_backward(mlora_plan* p, const void* dY, const void* X, const void* W, c
         ShrinkArgs a{};
         a.src = (const u16*)dY; a.ld = p->n; a.out = (u16*)dS; a.Kdim = (int32_t)p->n; a.pv = p->view;
         ProfScope prof(p, MLORA_K_DSHRINK, st);
-        hipLaunchKernelGGL(shrink_kernel<false>, dim3(p->n_row_blocks), dim3(256), 0, st, a);
+        hipLaunchKernelGGL(shrink_kernel<false>, dim3(p->n_row_blocks), dim3(64 * SNW), 0, st, a);
         MLORA_HIP_TRY(hipGetLastError());
     }
     int rc = mfma_gemm_bwd(p, dY, W, dX, dS, flags, st);
