@@ -15,7 +15,8 @@ namespace mlora {
 constexpr int kBlockRows = 64;       // rows per LoRA block of the shrink kernels
 constexpr int kGemmTileRows = 256;   // fused GEMM macro tile
 constexpr int kGemmTileCols = 256;
-constexpr int kWgradChunkRows = 1024; // tokens reduced by one weight-gradient work item
+constexpr int kWgradMinChunkRows = 512;  // smallest token chunk one weight-gradient work item reduces
+constexpr int kWgradPanelCols = 128;     // columns of X / dY one weight-gradient work item covers
 
 // One entry of any plan table: 4 x int32 (meaning depends on the table).
 struct Entry4 {
@@ -63,6 +64,7 @@ struct mlora_plan {
     int32_t n_row_blocks = 0, n_gemm_tiles = 0, n_wgrad_chunks = 0;
     int32_t max_rank = 0;
     int32_t max_chunks_per_adapter = 0;
+    int32_t wgrad_chunk_rows = 0;     // token chunk of the weight-gradient items (chosen per plan)
     // one device allocation carved into the tables below
     void* d_block = nullptr;
     size_t d_block_bytes = 0;

@@ -24,12 +24,7 @@ constexpr int SKS = 32;            // contraction elements per wavefront step
 constexpr int SNW = 8;             // wavefronts per workgroup
 constexpr int SX_LD = SKS + 8;     // X / dY tile [64][40]: 80-byte rows, conflict-free 128-bit reads
 constexpr int SX_TILE = SR * SX_LD;
-constexpr int SBN_LD = 128 + 32;   // FWD small tile [32 contraction][160]
-constexpr int SB_TILE = 32 * SBN_LD;   // == 128 * SX_LD, the !FWD small tile [128 rank rows][40]
-static_assert(SB_TILE == 128 * SX_LD, "both small-tile layouts share one buffer size");
-constexpr int S_WAVE = SX_TILE + SB_TILE;   // per-wavefront private LDS (elements)
-constexpr int S_RLD = 132;                  // fp32 reduction tile row
-static_assert(SNW * S_WAVE * 2 >= SR * S_RLD * 4, "reduction tile fits in the staging buffers");
+constexpr int S_RLD = 132;         // fp32 reduction tile row
 static_assert(kBlockRows == SR, "row-block table and shrink kernel must agree");
 
 struct ShrinkArgs {
@@ -39,10 +34,17 @@ struct ShrinkArgs {
     PlanView pv;
 };
 
-template <bool FWD>
+// MAXNB: rank blocks of 32 the kernel is built for (2: every rank <= 64, 4: ranks up to 128).
+// DEPTH: register prefetch depth in steps (the small-rank build has registers to spare for 2).
+template <bool FWD, int MAXNB, int DEPTH>
 __global__ __launch_bounds__(64 * SNW) void shrink_kernel(ShrinkArgs g) {
+    constexpr int SBN_LD = MAXNB == 2 ? 96 : 160;                 // FWD small tile [32 contraction][LD] (192 / 320-byte rows)
+    constexpr int SB_TILE = (32 * SBN_LD > MAXNB * 32 * SX_LD) ? 32 * SBN_LD : MAXNB * 32 * SX_LD;
+    constexpr int S_WAVE = SX_TILE + SB_TILE;                     // per-wavefront private LDS (elements)
+    constexpr int NF = MAXNB * 2;                                 // small-tile chunks per lane per step
+    constexpr int CPRF = MAXNB * 4;                               // FWD: 16-byte chunks per small-tile row
+    static_assert(SNW * S_WAVE * 2 >= SR * S_RLD * 4, "reduction tile fits in the staging buffers");
     __shared__ __attribute__((aligned(16))) u16 lds[SNW * S_WAVE];
-    typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const Entry4 e = g.pv.row_blocks[blockIdx.x];
     const int i = e.a, row0 = e.c, rows = e.d;
@@ -55,11 +57,11 @@ __global__ __launch_bounds__(64 * SNW) void shrink_kernel(ShrinkArgs g) {
     u16* Xs = lds + wave * S_WAVE;
     u16* Fs = Xs + SX_TILE;
 
-    f32x16 acc[2][4];
+    f32x16 acc[2][MAXNB];
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-        for (int nb = 0; nb < 4; ++nb)
+        for (int nb = 0; nb < MAXNB; ++nb)
 #pragma unroll
             for (int q = 0; q < 16; ++q) acc[mb][nb][q] = 0.f;
 
@@ -68,44 +70,45 @@ __global__ __launch_bounds__(64 * SNW) void shrink_kernel(ShrinkArgs g) {
     const int per = (steps + SNW - 1) / SNW;
     const int s_begin = wave * per, s_end = min(steps, s_begin + per);
 
-    uint4 rx[4], rf[8];
-    auto gload = [&](int step) {
+    uint4 rx[DEPTH][4], rf[DEPTH][NF];
+    auto gload = [&](int step, int set) {
         const int k0 = step * SKS;
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {
             const int row = (lane >> 2) + 16 * jj, gk = k0 + (lane & 3) * 8;
-            rx[jj] = (row < rows && gk < g.Kdim)
-                         ? *reinterpret_cast<const uint4*>(g.src + (int64_t)(row0 + row) * g.ld + gk) : zero4();
+            rx[set][jj] = (row < rows && gk < g.Kdim)
+                              ? *reinterpret_cast<const uint4*>(g.src + (int64_t)(row0 + row) * g.ld + gk) : zero4();
         }
 #pragma unroll
-        for (int jj = 0; jj < 8; ++jj) {
+        for (int jj = 0; jj < NF; ++jj) {
             const int idx = lane + 64 * jj;
-            rf[jj] = zero4();
+            rf[set][jj] = zero4();
             if (FWD) {   // A_i[k0 + kr][cc * 8 ..]
-                const int kr = idx >> 4, cc = idx & 15;
+                const int kr = idx / CPRF, cc = idx % CPRF;
                 if (cc * 8 < rpad && k0 + kr < g.Kdim)
-                    rf[jj] = load_chunk(F + (int64_t)(k0 + kr) * r + cc * 8, min(8, r - cc * 8), f_vec);
+                    rf[set][jj] = load_chunk(F + (int64_t)(k0 + kr) * r + cc * 8, min(8, r - cc * 8), f_vec);
             } else {     // B_i[rho][k0 + c * 8 ..]
                 const int rho = idx >> 2, gk = k0 + (idx & 3) * 8;
-                if (rho < r && gk < g.Kdim) rf[jj] = *reinterpret_cast<const uint4*>(F + (int64_t)rho * g.ld + gk);
+                if (rho < r && gk < g.Kdim)
+                    rf[set][jj] = *reinterpret_cast<const uint4*>(F + (int64_t)rho * g.ld + gk);
             }
         }
     };
-    auto lstore = [&]() {
+    auto lstore = [&](int set) {
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {
             const int row = (lane >> 2) + 16 * jj;
-            *reinterpret_cast<uint4*>(Xs + row * SX_LD + (lane & 3) * 8) = rx[jj];
+            *reinterpret_cast<uint4*>(Xs + row * SX_LD + (lane & 3) * 8) = rx[set][jj];
         }
 #pragma unroll
-        for (int jj = 0; jj < 8; ++jj) {
+        for (int jj = 0; jj < NF; ++jj) {
             const int idx = lane + 64 * jj;
             if (FWD) {
-                const int kr = idx >> 4, cc = idx & 15;
-                if (cc * 8 < rpad) *reinterpret_cast<uint4*>(Fs + kr * SBN_LD + cc * 8) = rf[jj];
+                const int kr = idx / CPRF, cc = idx % CPRF;
+                if (cc * 8 < rpad) *reinterpret_cast<uint4*>(Fs + kr * SBN_LD + cc * 8) = rf[set][jj];
             } else {
                 const int rho = idx >> 2;
-                if (rho < rpad) *reinterpret_cast<uint4*>(Fs + rho * SX_LD + (idx & 3) * 8) = rf[jj];
+                if (rho < rpad) *reinterpret_cast<uint4*>(Fs + rho * SX_LD + (idx & 3) * 8) = rf[set][jj];
             }
         }
     };
@@ -117,7 +120,7 @@ __global__ __launch_bounds__(64 * SNW) void shrink_kernel(ShrinkArgs g) {
 #pragma unroll
             for (int mb = 0; mb < 2; ++mb) a[mb] = lds_read_frag(Xs + (mb * 32 + lm) * SX_LD + ks * 16 + h * 8);
 #pragma unroll
-            for (int nb = 0; nb < 4; ++nb) {
+            for (int nb = 0; nb < MAXNB; ++nb) {
                 if (nb < nblk) {
                     bf16x8 b;
                     if (FWD) {
@@ -136,11 +139,17 @@ __global__ __launch_bounds__(64 * SNW) void shrink_kernel(ShrinkArgs g) {
     // LDS tiles are private to the wavefront and LDS operations of one wavefront execute in order,
     // so the loop needs no workgroup barrier: write the tile, start the next loads, compute.
     if (s_begin < s_end) {
-        gload(s_begin);
-        for (int st = s_begin; st < s_end; ++st) {
-            lstore();
-            if (st + 1 < s_end) gload(st + 1);
+        gload(s_begin, 0);
+        if (DEPTH == 2 && s_begin + 1 < s_end) gload(s_begin + 1, DEPTH - 1);
+        for (int st = s_begin; st < s_end; st += DEPTH) {
+            lstore(0);
+            if (st + DEPTH < s_end) gload(st + DEPTH, 0);
             compute();
+            if (DEPTH == 2 && st + 1 < s_end) {
+                lstore(DEPTH - 1);
+                if (st + 3 < s_end) gload(st + 3, DEPTH - 1);
+                compute();
+            }
         }
     }
     __syncthreads();
@@ -152,7 +161,7 @@ __global__ __launch_bounds__(64 * SNW) void shrink_kernel(ShrinkArgs g) {
 #pragma unroll
             for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-                for (int nb = 0; nb < 4; ++nb) {
+                for (int nb = 0; nb < MAXNB; ++nb) {
                     if (nb >= nblk) continue;
 #pragma unroll
                     for (int q = 0; q < 16; ++q) {
@@ -173,6 +182,14 @@ __global__ __launch_bounds__(64 * SNW) void shrink_kernel(ShrinkArgs g) {
     }
 }
 
+template <bool FWD>
+static void launch_shrink(mlora_plan* p, const ShrinkArgs& a, hipStream_t st) {
+    if (p->max_rank <= 64)
+        hipLaunchKernelGGL((shrink_kernel<FWD, 2, 2>), dim3(p->n_row_blocks), dim3(64 * SNW), 0, st, a);
+    else
+        hipLaunchKernelGGL((shrink_kernel<FWD, 4, 1>), dim3(p->n_row_blocks), dim3(64 * SNW), 0, st, a);
+}
+
 // =========================================================================================
 // Weight gradients (token reductions):
 //   dA_i[kappa][rho] = sum_t X[t][kappa] dS[t][rho]          out [k][r]
@@ -182,7 +199,7 @@ __global__ __launch_bounds__(64 * SNW) void shrink_kernel(ShrinkArgs g) {
 // A chunk that covers its whole segment stores the result directly; otherwise fp32 partials go
 // to the workspace and a second kernel adds them in chunk order (no atomics, deterministic).
 // =========================================================================================
-constexpr int WP = 128;          // panel columns
+constexpr int WP = kWgradPanelCols;   // panel columns (128)
 constexpr int WT = 64;           // tokens per step
 constexpr int W_LD = 128 + 32;   // both tiles [64 tokens][160]
 constexpr int W_TILE = WT * W_LD;
@@ -224,29 +241,29 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradArgs g) {
         for (int q = 0; q < 16; ++q) acc[nb][q] = 0.f;
 
     const int nt = (rows + WT - 1) / WT;
-    uint4 ra[4], rb[4];
-    auto gload = [&](int tt) {
+    uint4 ra[2][4], rb[2][4];   // two register sets: tiles of even / odd index, two steps of loads in flight
+    auto gload = [&](int tt, int set) {
         const int t0 = tt * WT;
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {
             const int trow = (tid >> 4) + 16 * jj, cc = tid & 15;
             const int col = col0 + cc * 8;
             const bool ok = (t0 + trow < rows);
-            ra[jj] = (ok && col < width)
-                         ? *reinterpret_cast<const uint4*>(big + (int64_t)(row0 + t0 + trow) * width + col) : zero4();
-            rb[jj] = zero4();
+            ra[set][jj] = (ok && col < width)
+                              ? *reinterpret_cast<const uint4*>(big + (int64_t)(row0 + t0 + trow) * width + col) : zero4();
+            rb[set][jj] = zero4();
             if (ok && cc * 8 < rpad)
-                rb[jj] = load_chunk(small + (int64_t)(t0 + trow) * r + cc * 8, min(8, r - cc * 8), s_vec);
+                rb[set][jj] = load_chunk(small + (int64_t)(t0 + trow) * r + cc * 8, min(8, r - cc * 8), s_vec);
         }
     };
-    auto lstore = [&](int stage) {
+    auto lstore = [&](int stage, int set) {
         u16* Xs = lds + stage * W_STAGE;
         u16* Ss = Xs + W_TILE;
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {
             const int trow = (tid >> 4) + 16 * jj, cc = tid & 15;
-            *reinterpret_cast<uint4*>(Xs + trow * W_LD + cc * 8) = ra[jj];
-            *reinterpret_cast<uint4*>(Ss + trow * W_LD + cc * 8) = rb[jj];
+            *reinterpret_cast<uint4*>(Xs + trow * W_LD + cc * 8) = ra[set][jj];
+            *reinterpret_cast<uint4*>(Ss + trow * W_LD + cc * 8) = rb[set][jj];
         }
     };
     const int lm = lane & 31, h = lane >> 5, gq = lane >> 4, j = lane & 15;
@@ -269,17 +286,27 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradArgs g) {
             }
         }
     };
+    // Tile u travels in register set u & 1 and is computed from LDS stage u & 1.  At the top of step t
+    // tile t+1 is written to the other stage (last read before the previous barrier) and the loads
+    // of tile t+3 start, so every tile's loads have two whole steps to land.
     if (nt > 0) {
-        gload(0);
-        lstore(0);
+        gload(0, 0);
+        if (nt > 1) gload(1, 1);
+        lstore(0, 0);
+        if (nt > 2) gload(2, 0);
     }
     __syncthreads();
-    for (int tt = 0; tt < nt; ++tt) {
-        const int cur = tt & 1;
-        if (tt + 1 < nt) gload(tt + 1);
-        compute(cur);
-        if (tt + 1 < nt) lstore(cur ^ 1);
+    for (int tt = 0; tt < nt; tt += 2) {
+        if (tt + 1 < nt) lstore(1, 1);
+        if (tt + 3 < nt) gload(tt + 3, 1);
+        compute(0);
         __syncthreads();
+        if (tt + 1 < nt) {
+            if (tt + 2 < nt) lstore(0, 0);
+            if (tt + 4 < nt) gload(tt + 4, 0);
+            compute(1);
+            __syncthreads();
+        }
     }
 
     const int nchunks = g.pv.wgrad_chunk_start[i + 1] - g.pv.wgrad_chunk_start[i];
@@ -347,7 +374,7 @@ int mfma_forward(mlora_plan* p, const void* X, const void* W, void* Y, void* S, 
         ShrinkArgs a{};
         a.src = (const u16*)X; a.ld = p->k; a.out = (u16*)S; a.Kdim = (int32_t)p->k; a.pv = p->view;
         ProfScope prof(p, MLORA_K_SHRINK, st);
-        hipLaunchKernelGGL(shrink_kernel<true>, dim3(p->n_row_blocks), dim3(64 * SNW), 0, st, a);
+        launch_shrink<true>(p, a, st);
         MLORA_HIP_TRY(hipGetLastError());
     }
     return mfma_gemm_fwd(p, X, W, Y, S, flags, st);
@@ -360,7 +387,7 @@ int mfma_backward(mlora_plan* p, const void* dY, const void* X, const void* W, c
         ShrinkArgs a{};
         a.src = (const u16*)dY; a.ld = p->n; a.out = (u16*)dS; a.Kdim = (int32_t)p->n; a.pv = p->view;
         ProfScope prof(p, MLORA_K_DSHRINK, st);
-        hipLaunchKernelGGL(shrink_kernel<false>, dim3(p->n_row_blocks), dim3(64 * SNW), 0, st, a);
+        launch_shrink<false>(p, a, st);
         MLORA_HIP_TRY(hipGetLastError());
     }
     int rc = mfma_gemm_bwd(p, dY, W, dX, dS, flags, st);

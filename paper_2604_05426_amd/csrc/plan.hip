@@ -205,6 +205,31 @@ extern "C" int multi_lora_plan_create(mlora_plan** out, int dtype, int64_t T, in
     // bf16 with 16-byte row granularity goes to the MFMA kernels, everything else to the FMA kernels
     p->use_mfma = (dtype == MLORA_BF16) && (k % 8 == 0) && (n % 8 == 0);
 
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
+            p->num_cus = cus;
+    }
+    // Weight-gradient work items are (token chunk, 128-column panel).  Balance heterogeneous segment
+    // lengths across the CUs: keep whole segments when that already yields two items per CU (no
+    // partial sums at all), otherwise halve the chunk until it does or the minimum is reached.
+    {
+        const int64_t panels = ceil_div(k, kWgradPanelCols) + ceil_div(n, kWgradPanelCols);
+        int64_t chunk = (int64_t)1 << 30;
+        for (;;) {
+            int64_t items = 0;
+            for (int32_t i = 0; i < N; ++i) {
+                const int64_t Ti = seg_offsets[i + 1] - seg_offsets[i];
+                if (Ti > 0 && ranks[i] > 0) items += ceil_div(Ti, chunk) * panels;
+            }
+            if (items >= 2 * (int64_t)p->num_cus || chunk <= kWgradMinChunkRows) break;
+            chunk /= 2;
+        }
+        p->wgrad_chunk_rows = (int32_t)chunk;
+    }
+
     // host-side sizes (the device rebuilds the same numbers; multi_lora_plan_dump exposes them)
     int64_t s = 0;
     int64_t rb = 0, wc = 0;
@@ -215,7 +240,7 @@ extern "C" int multi_lora_plan_create(mlora_plan** out, int dtype, int64_t T, in
         s += Ti * ranks[i];
         if (Ti > 0 && ranks[i] > 0) {
             rb += ceil_div(Ti, kBlockRows);
-            const int64_t c = ceil_div(Ti, kWgradChunkRows);
+            const int64_t c = ceil_div(Ti, p->wgrad_chunk_rows);
             wc += c;
             if (c > p->max_chunks_per_adapter) p->max_chunks_per_adapter = (int32_t)c;
         }
@@ -260,14 +285,7 @@ extern "C" int multi_lora_plan_create(mlora_plan** out, int dtype, int64_t T, in
     const size_t o_part = take(sizeof(int64_t) * (N + 1));
     p->d_block_bytes = o;
 
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e == hipSuccess) {
-        int cus = 0;
-        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
-            p->num_cus = cus;
-        e = hipMalloc(&p->d_block, p->d_block_bytes);
-    }
+    if (e == hipSuccess) e = hipMalloc(&p->d_block, p->d_block_bytes);
     if (e != hipSuccess) {
         delete p;
         return hip_fail(e, "hipMalloc(plan tables)");
@@ -306,13 +324,13 @@ extern "C" int multi_lora_plan_create(mlora_plan** out, int dtype, int64_t T, in
     if ((e = hipMemcpyAsync(p->d_part_off, part_off.data(), sizeof(int64_t) * (N + 1), hipMemcpyHostToDevice, st)) != hipSuccess)
         return fail(e, "hipMemcpyAsync(partial offsets)");
     hipLaunchKernelGGL(plan_scan_kernel, dim3(1), dim3(64), 0, st, N, d_off, d_rank, d_soff, d_rbs, d_wcs,
-                       kBlockRows, kWgradChunkRows);
+                       kBlockRows, p->wgrad_chunk_rows);
     if (p->n_row_blocks > 0)
         hipLaunchKernelGGL(plan_fill_blocks_kernel, dim3((p->n_row_blocks + 255) / 256), dim3(256), 0, st, N,
                            d_off, d_rbs, kBlockRows, d_rb, p->n_row_blocks);
     if (p->n_wgrad_chunks > 0)
         hipLaunchKernelGGL(plan_fill_blocks_kernel, dim3((p->n_wgrad_chunks + 255) / 256), dim3(256), 0, st, N,
-                           d_off, d_wcs, kWgradChunkRows, d_wc, p->n_wgrad_chunks);
+                           d_off, d_wcs, p->wgrad_chunk_rows, d_wc, p->n_wgrad_chunks);
     if (p->n_gemm_tiles > 0)
         hipLaunchKernelGGL(plan_fill_gemm_tiles_kernel, dim3((p->n_gemm_tiles + 255) / 256), dim3(256), 0, st, N,
                            d_off, (int32_t)T, kGemmTileRows, d_gt, p->n_gemm_tiles);
@@ -420,7 +438,7 @@ extern "C" int multi_lora_plan_geometry(const mlora_plan* plan, int32_t* out) {
     out[MLORA_GEO_BLOCK_ROWS] = kBlockRows;
     out[MLORA_GEO_GEMM_TILE_ROWS] = kGemmTileRows;
     out[MLORA_GEO_GEMM_TILE_COLS] = kGemmTileCols;
-    out[MLORA_GEO_WGRAD_CHUNK_ROWS] = kWgradChunkRows;
+    out[MLORA_GEO_WGRAD_CHUNK_ROWS] = plan->wgrad_chunk_rows;
     out[MLORA_GEO_R1_LO] = (int32_t)(plan->R1 & 0x7fffffff);
     out[MLORA_GEO_R1_HI] = (int32_t)(plan->R1 >> 31);
     out[MLORA_GEO_USES_MFMA] = plan->use_mfma ? 1 : 0;
