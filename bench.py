@@ -123,16 +123,27 @@ def main() -> int:
                 else:
                     kern[name].update(bound="hbm", achieved_gbs=work / t / 1e9, frac=work / t / 1e9 / PEAK_HBM_GBS)
         out["kernels"] = kern
+        # HBM-side traffic per launch from the committed rocprofv3 --pmc summary (FETCH_SIZE / WRITE_SIZE, scaled by a
+        # copy kernel of known size); it was measured on this workload only
+        traffic = {}
+        prof = os.path.join(ROOT, "profiles", "bench_config2_pmc_traffic_mfma.md")
+        if args.config == 2 and os.path.exists(prof):
+            names = {"fused_gemm_kernel<true>": "gemm_fwd", "fused_gemm_kernel<false>": "gemm_bwd",
+                     "shrink_kernel<true": "shrink", "shrink_kernel<false": "dshrink", "wgrad_kernel": "wgrad"}
+            for line in open(prof):
+                parts = line.split()
+                if len(parts) == 3 and parts[0] == "traffic_bytes" and parts[1] in names:
+                    traffic[names[parts[1]]] = float(parts[2])
         dom = max((nm for nm in kern if nm in alg), key=lambda nm: kern[nm]["avg_ms"] * kern[nm]["launches_per_step"])
         bound, work = alg[dom]
         t = kern[dom]["avg_ms"] * 1e-3
         if bound == "mfma":
             out["roofline"] = {"kernel": dom, "bound": "mfma", "achieved": work / t / 1e12, "peak": PEAK_BF16_MFMA_TFLOPS,
-                               "unit": "TFLOP/s", "frac": work / t / 1e12 / PEAK_BF16_MFMA_TFLOPS, "traffic": None,
+                               "unit": "TFLOP/s", "frac": work / t / 1e12 / PEAK_BF16_MFMA_TFLOPS, "traffic": traffic.get(dom),
                                "avg_kernel_ms": kern[dom]["avg_ms"]}
         else:
             out["roofline"] = {"kernel": dom, "bound": "hbm", "achieved": work / t / 1e9, "peak": PEAK_HBM_GBS,
-                               "unit": "GB/s", "frac": work / t / 1e9 / PEAK_HBM_GBS, "traffic": None,
+                               "unit": "GB/s", "frac": work / t / 1e9 / PEAK_HBM_GBS, "traffic": traffic.get(dom),
                                "avg_kernel_ms": kern[dom]["avg_ms"]}
 
     if not args.no_extra and not args.fused_only:

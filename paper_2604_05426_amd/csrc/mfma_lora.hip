@@ -363,10 +363,191 @@ __global__ void wgrad_zero_empty_kernel(PlanView pv) {
     }
 }
 
+// =========================================================================================
+// Expand-add, the decoupled form (paper Sec. 5.1 / App. A.1 "fused base-output addition"):
+//   FWD:  Y_i  += s_i S_i B_i          (Y holds the base output on entry)
+//   !FWD: dX_i += dS_i A_i^T
+// Serves MLORA_FLAG_LORA_ONLY.  Memory bound (one read and one write of the output), so it
+// is built as a stream: work item = (64-row block of one adapter, 256 output columns), four
+// wavefronts with 64 columns each, no workgroup barrier.  Each wavefront issues the loads of
+// its old output tile first, multiplies from register-resident S fragments (B_i goes through
+// a small private LDS tile for the transposing read; A_i^T fragments come straight from
+// memory), transposes its result through private LDS and adds into the old tile with full
+// 128-byte row segments.
+// =========================================================================================
+constexpr int XC = 256;               // output columns per work item
+constexpr int X_BLD = 64 + 32;        // FWD B_i tile row: 192-byte rows for the transposing reads
+
+struct ExpandArgs {
+    u16* C; int64_t ldc;     // Y [T,n] or dX [T,k]
+    const u16* E;            // ragged S or dS
+    int32_t Ncols, col_tiles;
+    PlanView pv;
+};
+
+// MAXKS: 16-wide rank steps the kernel is built for (4: every rank <= 64, 8: ranks up to 128).
+// All loads of a work item (old output tile, S fragments, B_i / A_i^T operands) are issued before the
+// first MFMA, so a wavefront pays the memory latency once.
+template <bool FWD, int MAXKS>
+__global__ __launch_bounds__(256) void expand_add_kernel(ExpandArgs g) {
+    constexpr int X_WAVE = MAXKS * 16 * X_BLD;   // private LDS per wavefront (elements): the B_i tile; >= 64 x 36 floats
+    static_assert(X_WAVE * 2 >= 64 * 36 * 4, "fp32 epilogue staging fits in the private region");
+    __shared__ __attribute__((aligned(16))) u16 lds[4 * X_WAVE];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lm = lane & 31, h = lane >> 5, gq = lane >> 4, j = lane & 15;
+    const Entry4 e = g.pv.row_blocks[blockIdx.x / g.col_tiles];
+    const int ct = blockIdx.x % g.col_tiles;
+    const int i = e.a, row0 = e.c, rows = e.d;
+    const int r = g.pv.rank[i];
+    const int ksteps = (r + 15) / 16;
+    const int64_t so = g.pv.soff[i];
+    const int seg0 = g.pv.off[i];
+    const float s = FWD ? g.pv.scale[i] : 1.0f;
+    const u16* F = (const u16*)(FWD ? g.pv.ptrs[i].B : g.pv.ptrs[i].A);
+    const int col0 = ct * XC + wave * 64;
+    u16* Ws = lds + wave * X_WAVE;
+    if (col0 >= g.Ncols) return;   // whole wavefront beyond the edge (no workgroup barrier is used below)
+
+    // 1. old output tile: 64 rows x 64 columns per wavefront, 8 chunks per lane
+    uint4 old[8];
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+        const int rr = it * 8 + (lane >> 3), c = lane & 7;
+        const int col = col0 + c * 8;
+        old[it] = (rr < rows && col < g.Ncols)
+                      ? *reinterpret_cast<const uint4*>(g.C + (int64_t)(row0 + rr) * g.ldc + col) : zero4();
+    }
+    // 2. operands for every rank step
+    const bool e_vec = ((r & 7) == 0) && ((so & 7) == 0);
+    const bool f_vec = FWD ? true : ((r & 7) == 0);
+    uint4 av[2][MAXKS], bv[2][MAXKS];
+#pragma unroll
+    for (int ks = 0; ks < MAXKS; ++ks) {
+        const int rho = ks * 16 + h * 8;
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb) {
+            const int rr = mb * 32 + lm;
+            av[mb][ks] = zero4();
+            if (ks < ksteps && rr < rows && rho < r)
+                av[mb][ks] = load_chunk(g.E + so + (int64_t)(row0 + rr - seg0) * r + rho, min(8, r - rho), e_vec);
+        }
+        if (FWD) {   // B_i rows ks*16 .. ks*16+15, this wavefront's 64 columns: 2 chunks per lane
+#pragma unroll
+            for (int jj = 0; jj < 2; ++jj) {
+                const int kr = ks * 16 + (lane >> 3) + 8 * jj, c = lane & 7;
+                const int col = col0 + c * 8;
+                bv[jj][ks] = zero4();
+                if (ks < ksteps && kr < r && col < g.Ncols)
+                    bv[jj][ks] = *reinterpret_cast<const uint4*>(F + (int64_t)kr * g.Ncols + col);
+            }
+        } else {     // A_i rows = output columns, contraction contiguous: MFMA operand layout straight from memory
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb) {
+                const int col = col0 + nb * 32 + lm;
+                bv[nb][ks] = zero4();
+                if (ks < ksteps && col < g.Ncols && rho < r)
+                    bv[nb][ks] = load_chunk(F + (int64_t)col * r + rho, min(8, r - rho), f_vec);
+            }
+        }
+    }
+    if (FWD) {
+#pragma unroll
+        for (int ks = 0; ks < MAXKS; ++ks)
+#pragma unroll
+            for (int jj = 0; jj < 2; ++jj) {
+                const int kr = ks * 16 + (lane >> 3) + 8 * jj, c = lane & 7;
+                if (ks < ksteps) *reinterpret_cast<uint4*>(Ws + kr * X_BLD + c * 8) = bv[jj][ks];
+            }
+    }
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+            for (int q = 0; q < 16; ++q) acc[mb][nb][q] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < MAXKS; ++ks) {
+        if (ks < ksteps) {
+            bf16x8 a[2], b[2];
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
+                a[mb] = __builtin_bit_cast(bf16x8, s != 1.0f ? scale_chunk(av[mb][ks], s) : av[mb][ks]);
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb) {
+                if (FWD) {
+                    const u16* p = Ws + (ks * 16 + 8 * (gq >> 1) + (j >> 2)) * X_BLD + nb * 32 + 16 * (gq & 1) + 4 * (j & 3);
+                    b[nb] = lds_read_frag_tr(p, p + 4 * X_BLD);
+                } else {
+                    b[nb] = __builtin_bit_cast(bf16x8, bv[nb][ks]);
+                }
+            }
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                for (int nb = 0; nb < 2; ++nb) acc[mb][nb] = mfma32(b[nb], a[mb], acc[mb][nb]);   // transposed block
+        }
+    }
+
+    // 3. transpose through private LDS, add the old tile, one rounding, store
+    // fp32 staging: [64 rows][36 floats] per 32-column half, two passes
+    float* Fs = reinterpret_cast<float*>(Ws);   // X_WAVE * 2 bytes = 9216 B = 64 rows * 36 floats
+    constexpr int F_LD = 36;
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float4 v = make_float4(acc[mb][nb][4 * q + 0], acc[mb][nb][4 * q + 1], acc[mb][nb][4 * q + 2],
+                                             acc[mb][nb][4 * q + 3]);
+                *reinterpret_cast<float4*>(Fs + (mb * 32 + lm) * F_LD + q * 8 + h * 4) = v;
+            }
+        // this half covers columns col0 + nb*32 .. +31 = chunks c = nb*4 .. nb*4+3 of every row
+#pragma unroll
+        for (int it = 0; it < 8; ++it) {
+            const int rr = it * 8 + (lane >> 3), c = lane & 7;
+            if ((c >> 2) != nb) continue;
+            const int col = col0 + c * 8;
+            if (rr >= rows || col >= g.Ncols) continue;
+            const float* src = Fs + rr * F_LD + (c & 3) * 8;
+            const float4 lo = *reinterpret_cast<const float4*>(src);
+            const float4 hi = *reinterpret_cast<const float4*>(src + 4);
+            const uint32_t ov[4] = {old[it].x, old[it].y, old[it].z, old[it].w};
+            const float nv[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+            uint32_t res[4];
+#pragma unroll
+            for (int p2 = 0; p2 < 4; ++p2)
+                res[p2] = pack2(nv[2 * p2] + __uint_as_float(ov[p2] << 16),
+                                nv[2 * p2 + 1] + __uint_as_float(ov[p2] & 0xffff0000u));
+            *reinterpret_cast<uint4*>(g.C + (int64_t)(row0 + rr) * g.ldc + col) = make_uint4(res[0], res[1], res[2], res[3]);
+        }
+    }
+}
+
 // ---- host launchers ---------------------------------------------------------------------
 
 int mfma_gemm_fwd(mlora_plan* p, const void* X, const void* W, void* Y, const void* S, uint32_t flags, hipStream_t st);
 int mfma_gemm_bwd(mlora_plan* p, const void* dY, const void* W, void* dX, const void* dS, uint32_t flags, hipStream_t st);
+
+static int launch_expand(mlora_plan* p, bool fwd, void* C, const void* E, hipStream_t st) {
+    if (p->n_row_blocks == 0) return MLORA_OK;
+    ExpandArgs a{};
+    a.C = (u16*)C; a.E = (const u16*)E; a.pv = p->view;
+    a.Ncols = (int32_t)(fwd ? p->n : p->k);
+    a.ldc = a.Ncols;
+    a.col_tiles = (a.Ncols + XC - 1) / XC;
+    const int64_t grid = (int64_t)p->n_row_blocks * a.col_tiles;
+    ProfScope prof(p, fwd ? MLORA_K_GEMM_FWD : MLORA_K_GEMM_BWD, st);
+    const bool small = p->max_rank <= 64;
+    if (fwd && small)       hipLaunchKernelGGL((expand_add_kernel<true, 4>), dim3((unsigned)grid), dim3(256), 0, st, a);
+    else if (fwd)           hipLaunchKernelGGL((expand_add_kernel<true, 8>), dim3((unsigned)grid), dim3(256), 0, st, a);
+    else if (small)         hipLaunchKernelGGL((expand_add_kernel<false, 4>), dim3((unsigned)grid), dim3(256), 0, st, a);
+    else                    hipLaunchKernelGGL((expand_add_kernel<false, 8>), dim3((unsigned)grid), dim3(256), 0, st, a);
+    MLORA_HIP_TRY(hipGetLastError());
+    return MLORA_OK;
+}
 
 int mfma_forward(mlora_plan* p, const void* X, const void* W, void* Y, void* S, uint32_t flags, hipStream_t st) {
     const bool lora = !(flags & MLORA_FLAG_BASE_ONLY) && p->N > 0;
@@ -377,6 +558,7 @@ int mfma_forward(mlora_plan* p, const void* X, const void* W, void* Y, void* S, 
         launch_shrink<true>(p, a, st);
         MLORA_HIP_TRY(hipGetLastError());
     }
+    if (flags & MLORA_FLAG_LORA_ONLY) return launch_expand(p, true, Y, S, st);
     return mfma_gemm_fwd(p, X, W, Y, S, flags, st);
 }
 
@@ -390,7 +572,7 @@ int mfma_backward(mlora_plan* p, const void* dY, const void* X, const void* W, c
         launch_shrink<false>(p, a, st);
         MLORA_HIP_TRY(hipGetLastError());
     }
-    int rc = mfma_gemm_bwd(p, dY, W, dX, dS, flags, st);
+    int rc = (flags & MLORA_FLAG_LORA_ONLY) ? launch_expand(p, false, dX, dS, st) : mfma_gemm_bwd(p, dY, W, dX, dS, flags, st);
     if (rc != MLORA_OK) return rc;
     if (lora) {
         WgradArgs w{};
