@@ -79,6 +79,8 @@ def test_fp32_ragged_small():
     (32, 320, 264, (1, 3, 12, 100, 64), (63, 257, 5, 200, 1100)),     # k, n not multiples of the tile
     (33, 1024, 512, (8, 8, 16, 64), (256, 256, 512, 1300)),           # a segment split over wgrad chunks
     (34, 64, 8, (128,), (2100,)),
+    (37, 200, 136, (8, 128, 24), (100, 333, 64)),                     # both contractions end in a partial 64-wide tile
+    (38, 256, 512, (96, 40), (190, 70)),                              # ranks above 64 select the wide-rank kernels
 ])
 def test_bf16_ragged_small(seed, k, n, ranks, lens):
     w = wl.small_case(seed=seed, dtype="bf16", k=k, n=n, ranks=ranks, seg_lens=lens,
@@ -99,10 +101,28 @@ def test_bf16_aligned_uses_mfma_kernels():
     assert dl.plan.geometry()[ml.GEO_USES_MFMA] == 1
 
 
+def test_many_adapters_span_several_pointer_batches():
+    rng = np.random.default_rng(7)
+    N = 45
+    ranks = [int(x) for x in rng.choice([0, 4, 8, 16, 24], size=N)]
+    lens = [int(x) for x in rng.integers(0, 60, size=N)]
+    w = wl.make_workload("many", "bf16", 128, 192, ranks, lens, [float(x) for x in rng.choice([0.5, 1.0, 2.0], size=N)],
+                         seed=39, b_sigma=0.3)
+    check_full(w)
+
+
+def test_all_segments_empty():
+    for dtype in ("bf16", "f32"):
+        w = wl.make_workload("empty", dtype, 64, 64, [8, 16], [0, 0], [1.0, 2.0], seed=40)
+        dl = DeviceLayer(w); dl.forward(); dl.backward(); dl.sync()
+        for i in range(2):
+            assert torch.all(dl.dA[i] == 0) and torch.all(dl.dB[i] == 0)
+
+
 # ---- flags -------------------------------------------------------------------------------------
-@pytest.mark.parametrize("dtype", ["bf16", "f32"])
-def test_base_only_and_lora_only_modes(dtype):
-    w = wl.small_case(seed=41, dtype=dtype, k=256, n=384, ranks=(4, 16, 0, 40, 8), seg_lens=(129, 1, 70, 257, 90),
+@pytest.mark.parametrize("dtype,ranks", [("bf16", (4, 16, 0, 40, 8)), ("f32", (4, 16, 0, 40, 8)), ("bf16", (4, 100, 0, 128, 7))])
+def test_base_only_and_lora_only_modes(dtype, ranks):
+    w = wl.small_case(seed=41, dtype=dtype, k=256, n=392, ranks=ranks, seg_lens=(129, 1, 70, 257, 90),
                       scales=(2.0, 0.5, 1.0, 0.4, 3.0), b_sigma=0.3)
     tol = TOL[dtype]
     fw = orc.forward(w.X, w.W, w.A, w.B, w.scales, w.offsets, want_base=True)
@@ -203,4 +223,7 @@ def test_fwd_bwd_argument_errors():
     with pytest.raises(ml.MultiLoraError) as e:
         ml.multi_lora_bwd(dl.plan, dl.dY, dl.X, dl.W, dl.A, dl.B, dl.S, dl.dX, dl.dA, dl.dB, None, 0, dl.stream)
     assert e.value.status == -7
+    with pytest.raises(ml.MultiLoraError) as e:
+        ml.multi_lora_fwd(dl.plan, dl.X, dl.W, [dl.A[0].data_ptr() + 8], dl.B, dl.Y, dl.S, dl.workspace, 0, dl.stream)
+    assert e.value.status == -6
     dl.forward(); dl.backward(); dl.sync()      # the plan still works after rejected calls
