@@ -134,14 +134,20 @@ def main() -> int:
                 parts = line.split()
                 if len(parts) == 3 and parts[0] == "traffic_bytes" and parts[1] in names:
                     traffic[names[parts[1]]] = float(parts[2])
-        dom = max((nm for nm in kern if nm in alg), key=lambda nm: kern[nm]["avg_ms"] * kern[nm]["launches_per_step"])
-        bound, work = alg[dom]
-        t = kern[dom]["avg_ms"] * 1e-3
+        named = [nm for nm in kern if nm in alg]
+        if not named:
+            # fp32 / odd-width plans run every step through the grouped FMA kernel on the vector ALUs
+            out["roofline"] = {"kernel": "fma_grouped_gemm_kernel (all launches of a step)", "bound": "alu",
+                               "achieved": flops / (ms_step * 1e-3) / 1e12, "peak": 157.3, "unit": "TFLOP/s",
+                               "frac": flops / (ms_step * 1e-3) / 1e12 / 157.3, "traffic": None}
+        dom = max(named, key=lambda nm: kern[nm]["avg_ms"] * kern[nm]["launches_per_step"]) if named else None
+        bound, work = alg[dom] if dom else (None, 0.0)
+        t = kern[dom]["avg_ms"] * 1e-3 if dom else 1.0
         if bound == "mfma":
             out["roofline"] = {"kernel": dom, "bound": "mfma", "achieved": work / t / 1e12, "peak": PEAK_BF16_MFMA_TFLOPS,
                                "unit": "TFLOP/s", "frac": work / t / 1e12 / PEAK_BF16_MFMA_TFLOPS, "traffic": traffic.get(dom),
                                "avg_kernel_ms": kern[dom]["avg_ms"]}
-        else:
+        elif bound == "hbm":
             out["roofline"] = {"kernel": dom, "bound": "hbm", "achieved": work / t / 1e9, "peak": PEAK_HBM_GBS,
                                "unit": "GB/s", "frac": work / t / 1e9 / PEAK_HBM_GBS, "traffic": traffic.get(dom),
                                "avg_kernel_ms": kern[dom]["avg_ms"]}

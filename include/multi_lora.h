@@ -77,7 +77,11 @@ typedef enum {
                                    4 x int32 per entry: first row, rows, first adapter touched,
                                    last adapter touched + 1. */
     MLORA_TABLE_WGRAD_CHUNKS = 2 /* token chunks reduced by the weight-gradient kernels, 4 x int32:
-                                   adapter, chunk index within the adapter, first global row, rows. */
+                                   adapter, chunk index within the adapter, first global row, rows.
+                                   Same entries as a block table with MLORA_GEO_WGRAD_CHUNK_ROWS rows per
+                                   block, but ordered by decreasing cost rows x (64 + rank), ties in
+                                   canonical order (the device-side balancing of heterogeneous segments);
+                                   tables above 16384 entries keep the canonical order. */
 } mlora_table;
 
 /* geometry words returned by multi_lora_plan_geometry */

@@ -16,6 +16,7 @@ constexpr int kBlockRows = 64;       // rows per LoRA block of the shrink kernel
 constexpr int kGemmTileRows = 256;   // fused GEMM macro tile
 constexpr int kGemmTileCols = 256;
 constexpr int kWgradMinChunkRows = 512;  // smallest token chunk one weight-gradient work item reduces
+constexpr int kMaxSortedChunks = 16384;  // larger weight-gradient tables keep the canonical order
 constexpr int kWgradPanelCols = 128;     // columns of X / dY one weight-gradient work item covers
 
 // One entry of any plan table: 4 x int32 (meaning depends on the table).

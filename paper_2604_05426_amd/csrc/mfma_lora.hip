@@ -35,8 +35,9 @@ struct ShrinkArgs {
 };
 
 // MAXNB: rank blocks of 32 the kernel is built for (2: every rank <= 64, 4: ranks up to 128).
-// DEPTH: register prefetch depth in steps (the small-rank build has registers to spare for 2).
-template <bool FWD, int MAXNB, int DEPTH>
+// DX / DF: register prefetch depth in steps for the streamed operand (X or dY, comes from HBM) and for
+// the adapter matrix (cache resident); the wide-rank build only has registers for DX = 2, DF = 1.
+template <bool FWD, int MAXNB, int DX, int DF>
 __global__ __launch_bounds__(64 * SNW) void shrink_kernel(ShrinkArgs g) {
     constexpr int SBN_LD = MAXNB == 2 ? 96 : 160;                 // FWD small tile [32 contraction][LD] (192 / 320-byte rows)
     constexpr int SB_TILE = (32 * SBN_LD > MAXNB * 32 * SX_LD) ? 32 * SBN_LD : MAXNB * 32 * SX_LD;
@@ -70,8 +71,8 @@ __global__ __launch_bounds__(64 * SNW) void shrink_kernel(ShrinkArgs g) {
     const int per = (steps + SNW - 1) / SNW;
     const int s_begin = wave * per, s_end = min(steps, s_begin + per);
 
-    uint4 rx[DEPTH][4], rf[DEPTH][NF];
-    auto gload = [&](int step, int set) {
+    uint4 rx[DX][4], rf[DF][NF];
+    auto gloadX = [&](int step, int set) {
         const int k0 = step * SKS;
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {
@@ -79,6 +80,9 @@ __global__ __launch_bounds__(64 * SNW) void shrink_kernel(ShrinkArgs g) {
             rx[set][jj] = (row < rows && gk < g.Kdim)
                               ? *reinterpret_cast<const uint4*>(g.src + (int64_t)(row0 + row) * g.ld + gk) : zero4();
         }
+    };
+    auto gloadF = [&](int step, int set) {
+        const int k0 = step * SKS;
 #pragma unroll
         for (int jj = 0; jj < NF; ++jj) {
             const int idx = lane + 64 * jj;
@@ -94,12 +98,14 @@ __global__ __launch_bounds__(64 * SNW) void shrink_kernel(ShrinkArgs g) {
             }
         }
     };
-    auto lstore = [&](int set) {
+    auto lstoreX = [&](int set) {
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {
             const int row = (lane >> 2) + 16 * jj;
             *reinterpret_cast<uint4*>(Xs + row * SX_LD + (lane & 3) * 8) = rx[set][jj];
         }
+    };
+    auto lstoreF = [&](int set) {
 #pragma unroll
         for (int jj = 0; jj < NF; ++jj) {
             const int idx = lane + 64 * jj;
@@ -139,15 +145,21 @@ __global__ __launch_bounds__(64 * SNW) void shrink_kernel(ShrinkArgs g) {
     // LDS tiles are private to the wavefront and LDS operations of one wavefront execute in order,
     // so the loop needs no workgroup barrier: write the tile, start the next loads, compute.
     if (s_begin < s_end) {
-        gload(s_begin, 0);
-        if (DEPTH == 2 && s_begin + 1 < s_end) gload(s_begin + 1, DEPTH - 1);
-        for (int st = s_begin; st < s_end; st += DEPTH) {
-            lstore(0);
-            if (st + DEPTH < s_end) gload(st + DEPTH, 0);
+        gloadX(s_begin, 0);
+        if (DX == 2 && s_begin + 1 < s_end) gloadX(s_begin + 1, DX - 1);
+        gloadF(s_begin, 0);
+        if (DF == 2 && s_begin + 1 < s_end) gloadF(s_begin + 1, DF - 1);
+        for (int st = s_begin; st < s_end; st += 2) {
+            lstoreX(0);
+            lstoreF(0);
+            if (st + DX < s_end) gloadX(st + DX, 0);
+            if (st + DF < s_end) gloadF(st + DF, 0);
             compute();
-            if (DEPTH == 2 && st + 1 < s_end) {
-                lstore(DEPTH - 1);
-                if (st + 3 < s_end) gload(st + 3, DEPTH - 1);
+            if (st + 1 < s_end) {
+                lstoreX(DX - 1);
+                lstoreF(DF - 1);
+                if (st + 1 + DX < s_end) gloadX(st + 1 + DX, DX - 1);
+                if (st + 1 + DF < s_end) gloadF(st + 1 + DF, DF - 1);
                 compute();
             }
         }
@@ -185,9 +197,9 @@ __global__ __launch_bounds__(64 * SNW) void shrink_kernel(ShrinkArgs g) {
 template <bool FWD>
 static void launch_shrink(mlora_plan* p, const ShrinkArgs& a, hipStream_t st) {
     if (p->max_rank <= 64)
-        hipLaunchKernelGGL((shrink_kernel<FWD, 2, 2>), dim3(p->n_row_blocks), dim3(64 * SNW), 0, st, a);
+        hipLaunchKernelGGL((shrink_kernel<FWD, 2, 2, 2>), dim3(p->n_row_blocks), dim3(64 * SNW), 0, st, a);
     else
-        hipLaunchKernelGGL((shrink_kernel<FWD, 4, 1>), dim3(p->n_row_blocks), dim3(64 * SNW), 0, st, a);
+        hipLaunchKernelGGL((shrink_kernel<FWD, 4, 2, 1>), dim3(p->n_row_blocks), dim3(64 * SNW), 0, st, a);
 }
 
 // =========================================================================================
@@ -390,13 +402,15 @@ struct ExpandArgs {
 // first MFMA, so a wavefront pays the memory latency once.
 template <bool FWD, int MAXKS>
 __global__ __launch_bounds__(256) void expand_add_kernel(ExpandArgs g) {
-    constexpr int X_WAVE = MAXKS * 16 * X_BLD;   // private LDS per wavefront (elements): the B_i tile; >= 64 x 36 floats
+    constexpr int X_WAVE = 4 * 16 * X_BLD;       // private LDS per wavefront (elements): 64 rank rows of the B_i tile; >= 64 x 36 floats
     static_assert(X_WAVE * 2 >= 64 * 36 * 4, "fp32 epilogue staging fits in the private region");
     __shared__ __attribute__((aligned(16))) u16 lds[4 * X_WAVE];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int lm = lane & 31, h = lane >> 5, gq = lane >> 4, j = lane & 15;
-    const Entry4 e = g.pv.row_blocks[blockIdx.x / g.col_tiles];
-    const int ct = blockIdx.x % g.col_tiles;
+    // column-tile-major: consecutive workgroups are the row blocks of one adapter under the same 256 columns,
+    // so that adapter's B_i (or A_i) column tile stays cache resident while its row blocks stream by
+    const int ct = blockIdx.x / g.pv.n_row_blocks;
+    const Entry4 e = g.pv.row_blocks[blockIdx.x - ct * g.pv.n_row_blocks];
     const int i = e.a, row0 = e.c, rows = e.d;
     const int r = g.pv.rank[i];
     const int ksteps = (r + 15) / 16;
@@ -450,16 +464,6 @@ __global__ __launch_bounds__(256) void expand_add_kernel(ExpandArgs g) {
             }
         }
     }
-    if (FWD) {
-#pragma unroll
-        for (int ks = 0; ks < MAXKS; ++ks)
-#pragma unroll
-            for (int jj = 0; jj < 2; ++jj) {
-                const int kr = ks * 16 + (lane >> 3) + 8 * jj, c = lane & 7;
-                if (ks < ksteps) *reinterpret_cast<uint4*>(Ws + kr * X_BLD + c * 8) = bv[jj][ks];
-            }
-    }
-
     f32x16 acc[2][2];
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb)
@@ -467,26 +471,41 @@ __global__ __launch_bounds__(256) void expand_add_kernel(ExpandArgs g) {
         for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
             for (int q = 0; q < 16; ++q) acc[mb][nb][q] = 0.f;
+    // the private B_i tile holds 64 rank rows at a time (LDS operations of one wavefront execute in order)
 #pragma unroll
-    for (int ks = 0; ks < MAXKS; ++ks) {
-        if (ks < ksteps) {
-            bf16x8 a[2], b[2];
+    for (int half = 0; half < MAXKS / 4; ++half) {
+        if (FWD) {
 #pragma unroll
-            for (int mb = 0; mb < 2; ++mb)
-                a[mb] = __builtin_bit_cast(bf16x8, s != 1.0f ? scale_chunk(av[mb][ks], s) : av[mb][ks]);
+            for (int k4 = 0; k4 < 4; ++k4)
 #pragma unroll
-            for (int nb = 0; nb < 2; ++nb) {
-                if (FWD) {
-                    const u16* p = Ws + (ks * 16 + 8 * (gq >> 1) + (j >> 2)) * X_BLD + nb * 32 + 16 * (gq & 1) + 4 * (j & 3);
-                    b[nb] = lds_read_frag_tr(p, p + 4 * X_BLD);
-                } else {
-                    b[nb] = __builtin_bit_cast(bf16x8, bv[nb][ks]);
+                for (int jj = 0; jj < 2; ++jj) {
+                    const int ks = half * 4 + k4;
+                    const int kr = k4 * 16 + (lane >> 3) + 8 * jj, c = lane & 7;
+                    if (ks < ksteps) *reinterpret_cast<uint4*>(Ws + kr * X_BLD + c * 8) = bv[jj][ks];
                 }
+        }
+#pragma unroll
+        for (int k4 = 0; k4 < 4; ++k4) {
+            const int ks = half * 4 + k4;
+            if (ks < ksteps) {
+                bf16x8 a[2], b[2];
+#pragma unroll
+                for (int mb = 0; mb < 2; ++mb)
+                    a[mb] = __builtin_bit_cast(bf16x8, s != 1.0f ? scale_chunk(av[mb][ks], s) : av[mb][ks]);
+#pragma unroll
+                for (int nb = 0; nb < 2; ++nb) {
+                    if (FWD) {
+                        const u16* p = Ws + (k4 * 16 + 8 * (gq >> 1) + (j >> 2)) * X_BLD + nb * 32 + 16 * (gq & 1) + 4 * (j & 3);
+                        b[nb] = lds_read_frag_tr(p, p + 4 * X_BLD);
+                    } else {
+                        b[nb] = __builtin_bit_cast(bf16x8, bv[nb][ks]);
+                    }
+                }
+#pragma unroll
+                for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                    for (int nb = 0; nb < 2; ++nb) acc[mb][nb] = mfma32(b[nb], a[mb], acc[mb][nb]);   // transposed block
             }
-#pragma unroll
-            for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-                for (int nb = 0; nb < 2; ++nb) acc[mb][nb] = mfma32(b[nb], a[mb], acc[mb][nb]);   // transposed block
         }
     }
 

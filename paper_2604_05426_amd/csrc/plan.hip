@@ -78,6 +78,25 @@ __global__ void plan_fill_blocks_kernel(int32_t N, const int32_t* off, const int
     out[e] = Entry4{i, b, row0, rest < rows_per ? rest : rows_per};
 }
 
+// Device-side balancing of the weight-gradient items: entries are reordered by decreasing cost
+// (tokens x (64 + rank): the stream of X / dY dominates, the MFMA work grows with the rank), ties in
+// canonical order.  Workgroups are dispatched in index order, so the long items start first and the short
+// ones fill the CUs as they drain (longest-processing-time-first).  Position = number of entries that
+// sort before this one (counting, no atomics: the result is unique).
+__global__ void plan_sort_chunks_kernel(const Entry4* in, const int32_t* rank, Entry4* out, int32_t count) {
+    const int32_t e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= count) return;
+    const Entry4 me = in[e];
+    const int64_t key = (int64_t)me.d * (64 + rank[me.a]);
+    int32_t pos = 0;
+    for (int32_t o = 0; o < count; ++o) {
+        const Entry4 other = in[o];
+        const int64_t ok = (int64_t)other.d * (64 + rank[other.a]);
+        if (ok > key || (ok == key && o < e)) ++pos;
+    }
+    out[pos] = me;
+}
+
 // Row tiles of the flat buffer and the adapters they touch.
 __global__ void plan_fill_gemm_tiles_kernel(int32_t N, const int32_t* off, int32_t T, int tile_rows,
                                             Entry4* out, int32_t count) {
@@ -281,6 +300,7 @@ extern "C" int multi_lora_plan_create(mlora_plan** out, int dtype, int64_t T, in
     const size_t o_rb = take(sizeof(Entry4) * (size_t)(p->n_row_blocks + 1));
     const size_t o_gt = take(sizeof(Entry4) * (size_t)(p->n_gemm_tiles + 1));
     const size_t o_wc = take(sizeof(Entry4) * (size_t)(p->n_wgrad_chunks + 1));
+    const size_t o_wc_tmp = take(sizeof(Entry4) * (size_t)(p->n_wgrad_chunks + 1));
     const size_t o_probs = take(128 * (size_t)(5 * N + 8));
     const size_t o_part = take(sizeof(int64_t) * (N + 1));
     p->d_block_bytes = o;
@@ -328,9 +348,19 @@ extern "C" int multi_lora_plan_create(mlora_plan** out, int dtype, int64_t T, in
     if (p->n_row_blocks > 0)
         hipLaunchKernelGGL(plan_fill_blocks_kernel, dim3((p->n_row_blocks + 255) / 256), dim3(256), 0, st, N,
                            d_off, d_rbs, kBlockRows, d_rb, p->n_row_blocks);
-    if (p->n_wgrad_chunks > 0)
-        hipLaunchKernelGGL(plan_fill_blocks_kernel, dim3((p->n_wgrad_chunks + 255) / 256), dim3(256), 0, st, N,
-                           d_off, d_wcs, p->wgrad_chunk_rows, d_wc, p->n_wgrad_chunks);
+    if (p->n_wgrad_chunks > 0) {
+        Entry4* d_wc_tmp = (Entry4*)(base + o_wc_tmp);
+        const unsigned blocks = (unsigned)((p->n_wgrad_chunks + 255) / 256);
+        if (p->n_wgrad_chunks <= kMaxSortedChunks) {   // canonical table, then reordered by cost
+            hipLaunchKernelGGL(plan_fill_blocks_kernel, dim3(blocks), dim3(256), 0, st, N, d_off, d_wcs,
+                               p->wgrad_chunk_rows, d_wc_tmp, p->n_wgrad_chunks);
+            hipLaunchKernelGGL(plan_sort_chunks_kernel, dim3(blocks), dim3(256), 0, st, d_wc_tmp, d_rank, d_wc,
+                               p->n_wgrad_chunks);
+        } else {
+            hipLaunchKernelGGL(plan_fill_blocks_kernel, dim3(blocks), dim3(256), 0, st, N, d_off, d_wcs,
+                               p->wgrad_chunk_rows, d_wc, p->n_wgrad_chunks);
+        }
+    }
     if (p->n_gemm_tiles > 0)
         hipLaunchKernelGGL(plan_fill_gemm_tiles_kernel, dim3((p->n_gemm_tiles + 255) / 256), dim3(256), 0, st, N,
                            d_off, (int32_t)T, kGemmTileRows, d_gt, p->n_gemm_tiles);

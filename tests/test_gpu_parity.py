@@ -55,7 +55,10 @@ def test_plan_tables_bit_exact():
         plan = ml.Plan(ml.BF16, T, 64, 64, ranks, [1.0] * len(ranks), off)
         geo = plan.geometry()
         assert plan.dump(ml.TABLE_ROW_BLOCKS) == tt.row_blocks(off, ranks, geo[ml.GEO_BLOCK_ROWS])
-        assert plan.dump(ml.TABLE_WGRAD_CHUNKS) == tt.row_blocks(off, ranks, geo[ml.GEO_WGRAD_CHUNK_ROWS])
+        # same entries as the canonical chunk table, reordered by decreasing cost (ties keep canonical order)
+        canon = tt.row_blocks(off, ranks, geo[ml.GEO_WGRAD_CHUNK_ROWS])
+        cost = lambda en: en[3] * (64 + ranks[en[0]])
+        assert plan.dump(ml.TABLE_WGRAD_CHUNKS) == sorted(canon, key=lambda en: -cost(en))
         assert plan.dump(ml.TABLE_GEMM_ROW_TILES) == tt.gemm_row_tiles(off, geo[ml.GEO_GEMM_TILE_ROWS])
         lens = [off[i + 1] - off[i] for i in range(len(ranks))]
         assert plan.R1 == sum(t * r for t, r in zip(lens, ranks))
