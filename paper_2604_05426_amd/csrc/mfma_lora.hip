@@ -407,10 +407,9 @@ __global__ __launch_bounds__(256) void expand_add_kernel(ExpandArgs g) {
     __shared__ __attribute__((aligned(16))) u16 lds[4 * X_WAVE];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int lm = lane & 31, h = lane >> 5, gq = lane >> 4, j = lane & 15;
-    // column-tile-major: consecutive workgroups are the row blocks of one adapter under the same 256 columns,
-    // so that adapter's B_i (or A_i) column tile stays cache resident while its row blocks stream by
-    const int ct = blockIdx.x / g.pv.n_row_blocks;
-    const Entry4 e = g.pv.row_blocks[blockIdx.x - ct * g.pv.n_row_blocks];
+    // row-block-major: consecutive workgroups cover adjacent column tiles of the same 64 rows
+    const Entry4 e = g.pv.row_blocks[blockIdx.x / g.col_tiles];
+    const int ct = blockIdx.x % g.col_tiles;
     const int i = e.a, row0 = e.c, rows = e.d;
     const int r = g.pv.rank[i];
     const int ksteps = (r + 15) / 16;
