@@ -107,7 +107,7 @@ CONFIG_NAMES = ["tiny_fp32", "llama8b_qproj", "hetero_lengths", "llama8b_mlp_up"
 
 
 def config_shape(index: int):
-    """(dtype, k, n, ranks, seg_lens, scales, seed, rng) of BASELINE config ``index`` (0-based).
+    """(dtype, k, n, ranks, seg_lens, scales, seed, rng) of benchmark config ``index`` (0-based).
     Only the small integer draws happen here; tensors are drawn by ``config``."""
     seed = index
     rng = np.random.Generator(np.random.PCG64(seed))
@@ -132,7 +132,7 @@ def config_shape(index: int):
 
 
 def config(index: int) -> Workload:
-    """BASELINE config ``index`` (0-based) with all tensors drawn."""
+    """Benchmark config ``index`` (0-based) with all tensors drawn."""
     dtype, k, n, ranks, lens, scales, seed, rng = config_shape(index)
     return make_workload(CONFIG_NAMES[index], dtype, k, n, ranks, lens, scales, seed, rng=rng)
 
