@@ -44,7 +44,6 @@ __global__ __launch_bounds__(64 * SNW) void shrink_kernel(ShrinkArgs g) {
     constexpr int S_WAVE = SX_TILE + SB_TILE;                     // per-wavefront private LDS (elements)
     constexpr int NF = MAXNB * 2;                                 // small-tile chunks per lane per step
     constexpr int CPRF = MAXNB * 4;                               // FWD: 16-byte chunks per small-tile row
-    static_assert(SNW * S_WAVE * 2 >= SR * S_RLD * 4, "reduction tile fits in the staging buffers");
     __shared__ __attribute__((aligned(16))) u16 lds[SNW * S_WAVE];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const Entry4 e = g.pv.row_blocks[blockIdx.x];
@@ -166,10 +165,15 @@ __global__ __launch_bounds__(64 * SNW) void shrink_kernel(ShrinkArgs g) {
     }
     __syncthreads();
 
-    // add the eight partial tiles in wavefront order, then store
-    float* red = reinterpret_cast<float*>(lds);   // [64][132]
-    for (int w = 0; w < SNW; ++w) {
-        if (wave == w) {
+    // Add the eight partial tiles: NBUF wavefronts at a time write / add into NBUF fp32 buffers (SNW / NBUF
+    // barrier rounds instead of SNW), then every thread sums the buffers in index order.  Fixed order, no atomics.
+    constexpr int RLD = MAXNB * 32 + 4;                       // fp32 row of one buffer
+    constexpr int NBUF = MAXNB == 2 ? 4 : 2;
+    static_assert(NBUF * SR * RLD * 4 <= SNW * S_WAVE * 2, "reduction buffers fit in the staging area");
+    float* red = reinterpret_cast<float*>(lds);
+    for (int round = 0; round < SNW / NBUF; ++round) {
+        if (wave / NBUF == round) {
+            float* buf = red + (wave % NBUF) * (SR * RLD);
 #pragma unroll
             for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
@@ -178,8 +182,8 @@ __global__ __launch_bounds__(64 * SNW) void shrink_kernel(ShrinkArgs g) {
 #pragma unroll
                     for (int q = 0; q < 16; ++q) {
                         const int row = mb * 32 + (q >> 2) * 8 + h * 4 + (q & 3);
-                        float* d = red + row * S_RLD + nb * 32 + lm;
-                        *d = (w == 0) ? acc[mb][nb][q] : (*d + acc[mb][nb][q]);
+                        float* d = buf + row * RLD + nb * 32 + lm;
+                        *d = (round == 0) ? acc[mb][nb][q] : (*d + acc[mb][nb][q]);
                     }
                 }
         }
@@ -190,7 +194,10 @@ __global__ __launch_bounds__(64 * SNW) void shrink_kernel(ShrinkArgs g) {
     u16* out = g.out + so + (int64_t)(row0 - seg0) * r;
     for (int idx = tid; idx < rows * r; idx += 64 * SNW) {
         const int row = idx / r, col = idx - row * r;
-        out[idx] = f2bf(s * red[row * S_RLD + col]);
+        float v = 0.f;
+#pragma unroll
+        for (int b = 0; b < NBUF; ++b) v += red[b * (SR * RLD) + row * RLD + col];
+        out[idx] = f2bf(s * v);
     }
 }
 
