@@ -171,7 +171,8 @@ enum {
     MLORA_K_GEMM_BWD = 3,    /* dX = dY W^T + dS_i A_i^T (fused) */
     MLORA_K_WGRAD = 4,       /* dA_i, dB_i token reductions (grouped) */
     MLORA_K_WGRAD_REDUCE = 5,/* fixed-order sum of chunk partials */
-    MLORA_K_OTHER = 6        /* pointer upload, descriptor set-up, FMA-path launches */
+    MLORA_K_OTHER = 6,       /* pointer upload, descriptor set-up, FMA-path launches */
+    MLORA_K_ADAMW = 7        /* grouped per-adapter AdamW update */
 };
 
 /*
@@ -185,6 +186,29 @@ enum {
 int multi_lora_profile_begin(mlora_plan* plan, int32_t max_records);
 int multi_lora_profile_end(mlora_plan* plan, int32_t* kernel_ids, float* ms, int32_t cap,
                            int32_t* count);
+
+/*
+ * Per-adapter AdamW on the LoRA matrices, one grouped launch for all adapters.  The paper gives every
+ * LoRA job its own optimizer instance (Sec. 5.2) and trains with AdamW, weight decay 0.01, constant
+ * learning rate (App., training details); its 8-bit paged state is not reproduced: the state here is
+ * fp32.  Update, per element, with t = hp[i].step (1-based, per adapter):
+ *     m <- beta1 m + (1-beta1) g ;  v <- beta2 v + (1-beta2) g^2
+ *     master <- master - lr ( (m / (1-beta1^t)) / (sqrt(v / (1-beta2^t)) + eps) + weight_decay master )
+ *     A_i / B_i <- master rounded to the plan dtype
+ * stateA[i] / stateB[i]: device, 3 * numel floats laid out [master | m | v] (numel = k r_i or r_i n).
+ * A, B, dA, dB, stateA, stateB: host arrays of N device pointers (entries of rank-0 adapters ignored);
+ * hp: host [N].  multi_lora_adamw_init copies A_i, B_i into the masters and zeroes m, v.
+ */
+typedef struct {
+    float lr, beta1, beta2, eps, weight_decay;
+    int32_t step;
+} mlora_adamw_hparams;
+
+int multi_lora_adamw_init(mlora_plan* plan, const void* const* A, const void* const* B,
+                          float* const* stateA, float* const* stateB, void* stream);
+int multi_lora_adamw_step(mlora_plan* plan, void* const* A, void* const* B, const void* const* dA,
+                          const void* const* dB, float* const* stateA, float* const* stateB,
+                          const mlora_adamw_hparams* hp, void* stream);
 
 /* Thread-local text of the last error returned on this thread ("" if none). */
 const char* multi_lora_last_error(void);

@@ -29,9 +29,17 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmultilor
 EXPORTS = ["multi_lora_plan_create", "multi_lora_plan_destroy", "multi_lora_validate",
            "multi_lora_workspace_bytes", "multi_lora_plan_geometry", "multi_lora_plan_dump",
            "multi_lora_fwd", "multi_lora_bwd", "multi_lora_last_error", "multi_lora_version",
-           "multi_lora_profile_begin", "multi_lora_profile_end"]
+           "multi_lora_profile_begin", "multi_lora_profile_end",
+           "multi_lora_adamw_init", "multi_lora_adamw_step"]
 
-KERNEL_NAMES = {0: "shrink", 1: "gemm_fwd", 2: "dshrink", 3: "gemm_bwd", 4: "wgrad", 5: "wgrad_reduce", 6: "other"}
+KERNEL_NAMES = {0: "shrink", 1: "gemm_fwd", 2: "dshrink", 3: "gemm_bwd", 4: "wgrad", 5: "wgrad_reduce", 6: "other",
+                7: "adamw"}
+
+
+class AdamwHparams(ctypes.Structure):
+    """mlora_adamw_hparams: one entry per adapter; `step` is that adapter's 1-based step count."""
+    _fields_ = [("lr", ctypes.c_float), ("beta1", ctypes.c_float), ("beta2", ctypes.c_float),
+                ("eps", ctypes.c_float), ("weight_decay", ctypes.c_float), ("step", ctypes.c_int32)]
 
 
 class MultiLoraError(RuntimeError):
@@ -72,6 +80,10 @@ def lib() -> ctypes.CDLL:
         L.multi_lora_profile_begin.restype = ctypes.c_int
         L.multi_lora_profile_end.argtypes = [vp, vp, vp, i32, ctypes.POINTER(i32)]
         L.multi_lora_profile_end.restype = ctypes.c_int
+        L.multi_lora_adamw_init.argtypes = [vp, vp, vp, vp, vp, vp]
+        L.multi_lora_adamw_init.restype = ctypes.c_int
+        L.multi_lora_adamw_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.multi_lora_adamw_step.restype = ctypes.c_int
         L.multi_lora_last_error.restype = ctypes.c_char_p
         L.multi_lora_version.restype = ctypes.c_char_p
         _lib = L
@@ -191,3 +203,21 @@ def multi_lora_bwd(plan: Plan, dY, X, W, A, B, S, dX, dA, dB, workspace, flags: 
     _check(lib().multi_lora_bwd(plan.handle, _addr(dY), _addr(X), _addr(W), _ptr_array(A, plan.N),
                                 _ptr_array(B, plan.N), _addr(S), _addr(dX), _ptr_array(dA, plan.N),
                                 _ptr_array(dB, plan.N), _addr(workspace), flags, ctypes.c_void_p(stream)))
+
+
+def multi_lora_adamw_init(plan: Plan, A, B, stateA, stateB, stream: int = 0) -> None:
+    n = plan.N
+    _check(lib().multi_lora_adamw_init(plan.handle, _ptr_array(A, n), _ptr_array(B, n), _ptr_array(stateA, n),
+                                       _ptr_array(stateB, n), ctypes.c_void_p(stream)))
+
+
+def multi_lora_adamw_step(plan: Plan, A, B, dA, dB, stateA, stateB, hparams: Sequence, stream: int = 0) -> None:
+    """`hparams`: one (lr, beta1, beta2, eps, weight_decay, step) tuple per adapter."""
+    n = plan.N
+    hp = (AdamwHparams * max(n, 1))()
+    for i in range(n):
+        lr, b1, b2, eps, wd, step = hparams[i]
+        hp[i] = AdamwHparams(lr, b1, b2, eps, wd, int(step))
+    _check(lib().multi_lora_adamw_step(plan.handle, _ptr_array(A, n), _ptr_array(B, n), _ptr_array(dA, n),
+                                       _ptr_array(dB, n), _ptr_array(stateA, n), _ptr_array(stateB, n), hp,
+                                       ctypes.c_void_p(stream)))

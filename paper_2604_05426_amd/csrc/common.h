@@ -72,6 +72,7 @@ struct mlora_plan {
     mlora::PlanView view{};
     mlora::AdapterPtrs* d_ptrs = nullptr;
     void* d_probs = nullptr;          // descriptor scratch of the FMA grouped GEMM
+    void* d_adamw = nullptr;          // [N] optimizer entries (pointers + hyper-parameters), refreshed per call
     int64_t* d_part_off = nullptr;    // [N] float offset of each adapter's partial weight-gradient block
     bool has_empty_ranked = false;    // some adapter has a rank but no tokens (its dA, dB are zero-filled)
     size_t ws_ds_bytes = 0;           // workspace: dS

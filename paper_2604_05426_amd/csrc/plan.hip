@@ -303,6 +303,7 @@ extern "C" int multi_lora_plan_create(mlora_plan** out, int dtype, int64_t T, in
     const size_t o_wc_tmp = take(sizeof(Entry4) * (size_t)(p->n_wgrad_chunks + 1));
     const size_t o_probs = take(128 * (size_t)(5 * N + 8));
     const size_t o_part = take(sizeof(int64_t) * (N + 1));
+    const size_t o_adamw = take(96 * (size_t)(N + 1));
     p->d_block_bytes = o;
 
     if (e == hipSuccess) e = hipMalloc(&p->d_block, p->d_block_bytes);
@@ -323,6 +324,7 @@ extern "C" int multi_lora_plan_create(mlora_plan** out, int dtype, int64_t T, in
     Entry4* d_wc = (Entry4*)(base + o_wc);
     p->d_probs = base + o_probs;
     p->d_part_off = (int64_t*)(base + o_part);
+    p->d_adamw = base + o_adamw;
 
     hipStream_t st = p->build_stream;
     std::vector<int32_t>& off32 = p->off32;
