@@ -9,14 +9,21 @@
 // segments; a tile that straddles several adapters runs one masked extension per adapter.
 // Backward input gradient is the mirror image: dX = dY W^T, extended with dS_i and A_i^T.
 //
-// Tile 256 x 256 x 64, 8 wavefronts (2 x 4; two per SIMD so that one wavefront's LDS and
-// barrier waits hide under the other's MFMAs), each 128 x 64 = 4 x 2 MFMA 32x32x16 blocks
-// with fp32 accumulators.  LDS is double-buffered; global loads run one whole tile ahead in
-// registers; MFMA operands are read from LDS one 16-wide step ahead of their use.  The
-// forward's W tile is [k][n] in memory (column index contiguous); it is staged row-major and
-// read with the transposing LDS load.  The MFMA operands are swapped (C^T blocks) so that
-// each lane ends up with 4 consecutive output columns, which lets the epilogue transpose each
-// wavefront's sub-tile through LDS with 64-bit writes and store full 128-byte row segments.
+// Tile 256 x 256 x 64, 8 wavefronts (2 x 4; two per SIMD so that one wavefront's waits hide under the
+// other's MFMAs), each 128 x 64 = 8 x 4 blocks of 16x16x32 MFMAs with fp32 accumulators (on this chip a
+// GEMM of this size runs into the board power limit, and the 16x16x32 form needs measurably less energy
+// per FLOP than 32x32x16).  Operand tiles go from global memory straight into LDS (no staging registers,
+// no LDS store instructions); two 64 KB stages; the loads of tile t+2 are issued right after the barrier
+// that ends the reads of tile t, so they have a whole tile of MFMAs to land.  LDS tiles are unpadded and
+// XOR-swizzled so that both the 1 KB-contiguous direct loads and the fragment reads are conflict free:
+//   X / dY tile and the [col][contraction] weight tile: 256 rows of 128 bytes; the 16-byte chunk c of
+//     row r sits at chunk position c ^ (r & 7);
+//   the forward's W tile is [k][n] in memory (column index contiguous): 64 rows of 512 bytes, chunk c
+//     (8 columns) of row k sits at position c ^ (v(k) << 1), v(k) = (k & 3) | (((k >> 3) & 1) << 2); it
+//     is read with the transposing LDS load.
+// The MFMA operands are swapped (C^T blocks) so that each lane ends up with 4 consecutive output columns,
+// which lets the epilogue transpose each wavefront's sub-tile through LDS with 64-bit writes and store
+// full 128-byte row segments.
 #include "mfma_common.h"
 
 namespace mlora {
@@ -25,20 +32,33 @@ constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int WM = 2, WN = 4;                 // wavefront grid
 constexpr int NTHR = 64 * WM * WN;            // 512
 constexpr int TM = BM / WM, TN = BN / WN;     // 128 x 64 per wavefront
-constexpr int MB = TM / 32, NB = TN / 32;     // 4 x 2 MFMA blocks
-constexpr int CH = (BM * BK / 8) / NTHR;      // 16-byte chunks per thread per operand tile (4)
-constexpr int A_LD = BK + 8;     // 144-byte rows: conflict-free 128-bit fragment reads
-constexpr int BNT_LD = BK + 8;   // [col][contraction] layout
-constexpr int BNN_LD = BN + 32;  // [contraction][col] layout, 576-byte rows for the transposing reads
-constexpr int A_TILE = BM * A_LD;
-constexpr int B_TILE = BN * BNT_LD;
-static_assert(B_TILE == BK * BNN_LD, "both B layouts share one buffer size");
-constexpr int STAGE = A_TILE + B_TILE;
-constexpr int E_LD = TN + 8;     // epilogue staging row
-static_assert(WM * WN * TM * E_LD <= 2 * STAGE, "epilogue staging fits in the tile buffers");
+constexpr int TILE_BYTES = 32768;             // one operand tile
+constexpr int STAGE_BYTES = 2 * TILE_BYTES;   // X tile + W tile
+constexpr int E_LD = TN + 8;                  // epilogue staging row (elements)
+constexpr int EPI_BYTES = WM * WN * TM * E_LD * 2;
+constexpr int LDS_BYTES = EPI_BYTES > 2 * STAGE_BYTES ? EPI_BYTES : 2 * STAGE_BYTES;
 static_assert(kGemmTileRows == BM && kGemmTileCols == BN, "plan geometry and kernel tile must agree");
 
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4v __attribute__((ext_vector_type(4)));
+
+// v_mfma_f32_16x16x32_bf16:  C[16x16] += A[16x32] * B[32x16].
+// Lane l supplies A[row l%16][8*(l/16) .. +7] and B[8*(l/16) .. +7][col l%16];
+// it receives C[4*(l/16) + i][l%16] in c[i], i = 0..3.
+__device__ __forceinline__ f32x4v mfma16(bf16x8 a, bf16x8 b, f32x4v c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+
+// Direct global -> LDS load of 16 bytes per lane: lane i's data lands at LDS byte address lds_base + 16 i
+// (lds_base is wavefront-uniform).  Issued through inline assembly so that the compiler's wait-count
+// insertion does not serialise later LDS reads behind it; the caller waits with an explicit vmcnt and a
+// barrier before anybody reads the data.
+__device__ __forceinline__ void dma16(const void* gsrc, unsigned lds_base) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gsrc), "s"(lds_base) : "memory", "m0");
+}
+// all of this wavefront's direct loads and LDS accesses have completed; then the workgroup barrier
+__device__ __forceinline__ void wait_all_and_barrier() {
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
 
 struct GemmArgs {
     const u16* Aop; int64_t lda;   // X [T,k] (fwd) or dY [T,n] (bwd)
@@ -64,9 +84,13 @@ struct PassDesc {
     int kc;                            // valid contraction length, 1..64
 };
 
+__device__ __forceinline__ int nn_swz(int k) { return (k & 3) | (((k >> 3) & 1) << 2); }
+
+// Writes the pass operands into stage 0 in the same swizzled layouts the main loop uses, zero-filled
+// up to a multiple of 32 in the contraction and outside the rows / columns the pass owns.
 template <bool NN>
-__device__ __forceinline__ void stage_pass(u16* As, u16* Bs, const PassDesc& d, int m0, int n0, int ncols, int tid) {
-    const int kpad = (d.kc + 15) & ~15;
+__device__ __forceinline__ void stage_pass(unsigned char* lds, const PassDesc& d, int m0, int n0, int ncols, int tid) {
+    const int kpad = (d.kc + 31) & ~31;
     const int nch = kpad / 8;
     {
         const int row = tid & (BM - 1);
@@ -79,9 +103,10 @@ __device__ __forceinline__ void stage_pass(u16* As, u16* Bs, const PassDesc& d, 
                 v = load_chunk(src + cc * 8, min(8, d.kc - cc * 8), d.a_vec);
                 if (d.scale != 1.0f) v = scale_chunk(v, d.scale);
             }
-            *reinterpret_cast<uint4*>(As + row * A_LD + cc * 8) = v;
+            *reinterpret_cast<uint4*>(lds + row * 128 + ((cc ^ (row & 7)) << 4)) = v;
         }
     }
+    unsigned char* Bs = lds + TILE_BYTES;
     if (NN) {
         const int nc = tid & 31;
         const int gcol = n0 + nc * 8;
@@ -89,7 +114,7 @@ __device__ __forceinline__ void stage_pass(u16* As, u16* Bs, const PassDesc& d, 
             uint4 v = zero4();
             if (krow < d.kc && gcol < ncols)
                 v = load_chunk(d.b_src + (int64_t)krow * d.b_ld + gcol, min(8, ncols - gcol), d.b_vec);
-            *reinterpret_cast<uint4*>(Bs + krow * BNN_LD + nc * 8) = v;
+            *reinterpret_cast<uint4*>(Bs + krow * 512 + ((nc ^ (nn_swz(krow) << 1)) << 4)) = v;
         }
     } else {
         const int row = tid & (BN - 1);
@@ -98,18 +123,21 @@ __device__ __forceinline__ void stage_pass(u16* As, u16* Bs, const PassDesc& d, 
         for (int cc = tid >> 8; cc < nch; cc += NTHR / BN) {
             uint4 v = zero4();
             if (gcol < ncols) v = load_chunk(src + cc * 8, min(8, d.kc - cc * 8), d.b_vec);
-            *reinterpret_cast<uint4*>(Bs + row * BNT_LD + cc * 8) = v;
+            *reinterpret_cast<uint4*>(Bs + row * 128 + ((cc ^ (row & 7)) << 4)) = v;
         }
     }
 }
 
+#define MLORA_SGB(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
+
 template <bool NN>
 __global__ __launch_bounds__(NTHR) void fused_gemm_kernel(GemmArgs g) {
-    __shared__ __attribute__((aligned(16))) u16 lds[2 * STAGE];
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[LDS_BYTES];
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave % WN;
-    const int lm = lane & 31, h = lane >> 5, gq = lane >> 4, j = lane & 15;
+    const int l16 = lane & 15, g4 = lane >> 4;
 
     // Workgroups are handed to the 8 XCDs round-robin; give each XCD a contiguous run of
     // tiles and walk it in bands of 8 row tiles so that co-resident tiles share W / X panels
@@ -126,129 +154,121 @@ __global__ __launch_bounds__(NTHR) void fused_gemm_kernel(GemmArgs g) {
     const int tn = in_band / band_rows;
     const int m0 = tm * BM, n0 = tn * BN;
 
-    f32x16 acc[MB][NB];
+    // acc[a][b][i] = C[m0 + wm*128 + a*16 + l16][n0 + wn*64 + b*16 + 4*g4 + i]
+    f32x4v acc[8][4];
 #pragma unroll
-    for (int a = 0; a < MB; ++a)
+    for (int a = 0; a < 8; ++a)
 #pragma unroll
-        for (int b = 0; b < NB; ++b)
+        for (int b = 0; b < 4; ++b)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+            for (int i = 0; i < 4; ++i) acc[a][b][i] = 0.f;
 
-    // fragment read offsets (elements)
-    const int a_off = (wm * TM + lm) * A_LD + h * 8;
-    const int bnt_off = (wn * TN + lm) * BNT_LD + h * 8;
-    const int bnn_off = (8 * (gq >> 1) + (j >> 2)) * BNN_LD + wn * TN + 16 * (gq & 1) + 4 * (j & 3);
-    bf16x8 fa[2][MB], fb[2][NB];
-    auto rfrag = [&](int stage, int ks, int buf) {
-        const u16* As = lds + stage * STAGE;
-        const u16* Bs = As + A_TILE;
+    // ---- fragment reads (k32 = 32-wide half of the 64-wide tile, half = upper / lower 64 rows of the wave tile) ----
+    const int a_off0 = (wm * TM + l16) * 128 + ((g4 ^ (l16 & 7)) << 4);
+    const int a_off1 = (wm * TM + l16) * 128 + (((4 + g4) ^ (l16 & 7)) << 4);
+    const int bnt_off0 = TILE_BYTES + (wn * TN + l16) * 128 + ((g4 ^ (l16 & 7)) << 4);
+    const int bnt_off1 = TILE_BYTES + (wn * TN + l16) * 128 + (((4 + g4) ^ (l16 & 7)) << 4);
+    const int vq = ((l16 >> 2) & 3) | ((g4 & 1) << 2);    // nn_swz of the rows this lane reads
+    const int bnn_off = TILE_BYTES + (8 * g4 + (l16 >> 2)) * 512 + (l16 & 3) * 8;
+    bf16x8 fa[2][4], fb[2][4];
+    auto rfa = [&](int stage, int k32, int half, int buf) {
+        const unsigned char* base = lds + stage * STAGE_BYTES + (k32 ? a_off1 : a_off0);
 #pragma unroll
-        for (int a = 0; a < MB; ++a) fa[buf][a] = lds_read_frag(As + a_off + a * 32 * A_LD + ks * 16);
+        for (int a = 0; a < 4; ++a) fa[buf][a] = lds_read_frag(reinterpret_cast<const u16*>(base + (half * 4 + a) * 16 * 128));
+    };
+    auto rfb = [&](int stage, int k32, int buf) {
 #pragma unroll
-        for (int b = 0; b < NB; ++b) {
+        for (int b = 0; b < 4; ++b) {
             if (NN) {
-                const u16* p = Bs + bnn_off + ks * 16 * BNN_LD + b * 32;
-                fb[buf][b] = lds_read_frag_tr(p, p + 4 * BNN_LD);
+                const unsigned char* p = lds + stage * STAGE_BYTES + bnn_off + k32 * 32 * 512 + (((wn * 4 + b) ^ vq) << 5);
+                fb[buf][b] = lds_read_frag_tr(reinterpret_cast<const u16*>(p), reinterpret_cast<const u16*>(p + 4 * 512));
             } else {
-                fb[buf][b] = lds_read_frag(Bs + bnt_off + b * 32 * BNT_LD + ks * 16);
+                fb[buf][b] = lds_read_frag(reinterpret_cast<const u16*>(lds + stage * STAGE_BYTES + (k32 ? bnt_off1 : bnt_off0) + b * 16 * 128));
             }
         }
     };
-    // operands swapped: acc[a][b] holds the transposed 32x32 block (lane = output row, 4 consecutive columns per group)
-    auto mma = [&](int buf, int a_lo, int a_hi) {
+    // operands swapped: each accumulator block holds the transposed 16x16 block (lane = output row, 4 consecutive columns)
+    auto mma = [&](int half, int abuf, int bbuf) {
 #pragma unroll
-        for (int a = a_lo; a < a_hi; ++a)
+        for (int a = 0; a < 4; ++a)
 #pragma unroll
-            for (int b = 0; b < NB; ++b) acc[a][b] = mfma32(fb[buf][b], fa[buf][a], acc[a][b]);
+            for (int b = 0; b < 4; ++b) acc[half * 4 + a][b] = mfma16(fb[bbuf][b], fa[abuf][a], acc[half * 4 + a][b]);
     };
     // ask the scheduler to alternate LDS reads with MFMAs instead of issuing the reads in one burst
-    auto interleave = [&]() {
-        constexpr int NDS = NN ? (MB + 2 * NB) : (MB + NB);
-#pragma unroll
-        for (int i = 0; i < NDS; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // one MFMA
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
-        }
+    constexpr int NDSB = NN ? 8 : 4;
+    auto interleave = [&](int nds) {
+        for (int i = 0; i < nds; ++i) { MLORA_SGB(0x008, 1); MLORA_SGB(0x100, 1); }
+        __builtin_amdgcn_sched_barrier(0);
     };
 
     // ---- contraction over the frozen weight: whole 64-wide tiles -------------------------------
     const int nk = g.skip_base ? 0 : g.Kdim / BK;
     if (nk > 0) {
-        // per-thread global pointers; rows / columns past the edge are clamped to valid memory
-        // (they only feed output rows / columns that are never stored)
-        const u16* pa[CH];
-        const u16* pb[CH];
-        int sa[CH], sb[CH];
+        // per-lane global pointers of the direct loads: 4 instructions per wave per operand, each fills 1 KB of LDS.
+        // Rows / columns past the edge are clamped to valid memory (they only feed outputs that are never stored).
+        const char* pa[4];
+        const char* pb[4];
 #pragma unroll
-        for (int c = 0; c < CH; ++c) {
-            const int row = (tid >> 3) + (NTHR / 8) * c, kc = tid & 7;
-            pa[c] = g.Aop + (int64_t)min(m0 + row, g.M - 1) * g.lda + kc * 8;
-            sa[c] = row * A_LD + kc * 8;
+        for (int c = 0; c < 4; ++c) {
+            const int ii = wave * 4 + c;
+            const int row = ii * 8 + (lane >> 3), ch = (lane & 7) ^ (lane >> 3);
+            pa[c] = reinterpret_cast<const char*>(g.Aop + (int64_t)min(m0 + row, g.M - 1) * g.lda + ch * 8);
             if (NN) {
-                const int krow = (tid >> 5) + (NTHR / 32) * c, nc = tid & 31;
-                pb[c] = g.Bop + (int64_t)krow * g.ldb + min(n0 + nc * 8, g.Ncols - 8);
-                sb[c] = krow * BNN_LD + nc * 8;
+                const int k = ii * 2 + (lane >> 5);
+                const int chn = (lane & 31) ^ (nn_swz(k) << 1);
+                pb[c] = reinterpret_cast<const char*>(g.Bop + (int64_t)k * g.ldb + min(n0 + chn * 8, g.Ncols - 8));
             } else {
-                pb[c] = g.Bop + (int64_t)min(n0 + row, g.Ncols - 1) * g.ldb + kc * 8;
-                sb[c] = row * BNT_LD + kc * 8;
+                pb[c] = reinterpret_cast<const char*>(g.Bop + (int64_t)min(n0 + row, g.Ncols - 1) * g.ldb + ch * 8);
             }
         }
-        const int64_t bstep = NN ? (int64_t)BK * g.ldb : (int64_t)BK;
-        u32x4 ra[CH], rb[CH];
-        auto gload = [&](bool advance) {
-            const int64_t da = advance ? (int64_t)BK : 0, db = advance ? bstep : 0;
+        const int64_t astep = (int64_t)BK * 2, bstep = NN ? (int64_t)BK * g.ldb * 2 : (int64_t)BK * 2;
+        auto load_tile = [&](int stage, bool advance) {
+            const unsigned dst = (unsigned)(uintptr_t)lds + stage * STAGE_BYTES + wave * 4096;
+            const int64_t da = advance ? astep : 0, db = advance ? bstep : 0;
 #pragma unroll
-            for (int c = 0; c < CH; ++c) { ra[c] = *reinterpret_cast<const u32x4*>(pa[c]); pa[c] += da; }
+            for (int c = 0; c < 4; ++c) { dma16(pa[c], dst + c * 1024); pa[c] += da; }
 #pragma unroll
-            for (int c = 0; c < CH; ++c) { rb[c] = *reinterpret_cast<const u32x4*>(pb[c]); pb[c] += db; }
-        };
-        auto lstore = [&](int stage) {
-            u16* As = lds + stage * STAGE;
-            u16* Bs = As + A_TILE;
-#pragma unroll
-            for (int c = 0; c < CH; ++c) *reinterpret_cast<u32x4*>(As + sa[c]) = ra[c];
-#pragma unroll
-            for (int c = 0; c < CH; ++c) *reinterpret_cast<u32x4*>(Bs + sb[c]) = rb[c];
+            for (int c = 0; c < 4; ++c) { dma16(pb[c], dst + TILE_BYTES + c * 1024); pb[c] += db; }
         };
 
-        gload(nk > 1);
-        lstore(0);
-        __syncthreads();
-        rfrag(0, 0, 0);
-        gload(nk > 2);   // tile 1 travels in registers for a whole iteration (a harmless reload if nk == 1)
+        load_tile(0, nk > 1);
+        wait_all_and_barrier();
+        load_tile(1, nk > 2);            // tile 1 (tile 0 again when there is only one; never read then)
+        rfa(0, 0, 0, 0); rfb(0, 0, 0);
         for (int kt = 0; kt < nk - 1; ++kt) {
             const int cur = kt & 1;
-            lstore(cur ^ 1);          // tile kt+1; that stage was last read before the previous barrier
-            gload(kt + 3 < nk);       // tile kt+2 (re-reads the last tile when past the end)
             __builtin_amdgcn_sched_barrier(0);
-            rfrag(cur, 1, 1); mma(0, 0, MB); interleave();
-            __builtin_amdgcn_sched_barrier(0);
-            rfrag(cur, 2, 0); mma(1, 0, MB); interleave();
-            __builtin_amdgcn_sched_barrier(0);
-            rfrag(cur, 3, 1); mma(0, 0, MB); interleave();
-            __builtin_amdgcn_sched_barrier(0);
-            __syncthreads();          // tile kt+1 visible; nobody reads stage `cur` after this point
-            rfrag(cur ^ 1, 0, 0); mma(1, 0, MB); interleave();
-            __builtin_amdgcn_sched_barrier(0);
+            rfa(cur, 0, 1, 1);
+            mma(0, 0, 0); interleave(4);
+            rfa(cur, 1, 0, 0); rfb(cur, 1, 1);
+            mma(1, 1, 0); interleave(4 + NDSB);
+            rfa(cur, 1, 1, 1);
+            mma(0, 0, 1); interleave(4);
+            // tile kt+1 has landed in the other stage (this wave's share; the barrier covers the rest) and every
+            // wave has finished reading this stage, so tile kt+2 may overwrite it (the last tile again past the end)
+            wait_all_and_barrier();
+            load_tile(cur, kt + 3 < nk);
+            rfa(cur ^ 1, 0, 0, 0); rfb(cur ^ 1, 0, 0);
+            mma(1, 1, 1); interleave(4 + NDSB);
         }
         {
             const int cur = (nk - 1) & 1;
-            rfrag(cur, 1, 1); mma(0, 0, MB);
-            rfrag(cur, 2, 0); mma(1, 0, MB);
-            rfrag(cur, 3, 1); mma(0, 0, MB);
-            mma(1, 0, MB);
+            rfa(cur, 0, 1, 1); mma(0, 0, 0);
+            rfa(cur, 1, 0, 0); rfb(cur, 1, 1); mma(1, 1, 0);
+            rfa(cur, 1, 1, 1); mma(0, 0, 1);
+            mma(1, 1, 1);
         }
     }
 
-    // one masked pass: stage into buffer 0, then ceil(kc / 16) MFMA steps
+    // one masked pass: stage into buffer 0, then one or two 32-wide MFMA steps
     auto run_pass = [&](const PassDesc& d) {
+        wait_all_and_barrier();          // outstanding direct loads have landed; nobody reads the buffers any more
+        stage_pass<NN>(lds, d, m0, n0, g.Ncols, tid);
         __syncthreads();
-        stage_pass<NN>(lds, lds + A_TILE, d, m0, n0, g.Ncols, tid);
-        __syncthreads();
-        const int ksteps = (d.kc + 15) / 16;
+        const int ksteps = (d.kc + 31) / 32;
         for (int ks = 0; ks < ksteps; ++ks) {
-            rfrag(0, ks, 0);
-            mma(0, 0, MB);
+            rfa(0, ks, 0, 0); rfa(0, ks, 1, 1); rfb(0, ks, 0);
+            mma(0, 0, 0); mma(1, 1, 0);
         }
     };
 
@@ -288,20 +308,18 @@ __global__ __launch_bounds__(NTHR) void fused_gemm_kernel(GemmArgs g) {
     }
 
     // ---- epilogue: each wavefront transposes its own sub-tile through LDS; one rounding from fp32 ----
-    __syncthreads();
+    wait_all_and_barrier();
     {
-        u16* Es = lds + wave * (TM * E_LD);
+        u16* Es = reinterpret_cast<u16*>(lds) + wave * (TM * E_LD);
 #pragma unroll
-        for (int a = 0; a < MB; ++a)
+        for (int a = 0; a < 8; ++a)
 #pragma unroll
-            for (int b = 0; b < NB; ++b)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    uint2 v;
-                    v.x = pack2(acc[a][b][4 * q + 0], acc[a][b][4 * q + 1]);
-                    v.y = pack2(acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]);
-                    *reinterpret_cast<uint2*>(Es + (a * 32 + lm) * E_LD + b * 32 + q * 8 + h * 4) = v;
-                }
+            for (int b = 0; b < 4; ++b) {
+                uint2 v;
+                v.x = pack2(acc[a][b][0], acc[a][b][1]);
+                v.y = pack2(acc[a][b][2], acc[a][b][3]);
+                *reinterpret_cast<uint2*>(Es + (a * 16 + l16) * E_LD + b * 16 + g4 * 4) = v;
+            }
         // the same wavefront reads back what it wrote: only its own LDS writes must have landed
         __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0)
         constexpr int CPR = TN / 8;            // 16-byte chunks per row of the sub-tile
