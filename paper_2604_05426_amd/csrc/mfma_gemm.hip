@@ -52,8 +52,16 @@ __device__ __forceinline__ f32x4v mfma16(bf16x8 a, bf16x8 b, f32x4v c) {
 // (lds_base is wavefront-uniform).  Issued through inline assembly so that the compiler's wait-count
 // insertion does not serialise later LDS reads behind it; the caller waits with an explicit vmcnt and a
 // barrier before anybody reads the data.
-__device__ __forceinline__ void dma16(const void* gsrc, unsigned lds_base) {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gsrc), "s"(lds_base) : "memory", "m0");
+// The global address is a wavefront-uniform base pointer plus a 32-bit per-lane byte offset.
+__device__ __forceinline__ void dma16(unsigned voff, const void* sbase, unsigned lds_base) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_base) : "memory", "m0");
+}
+// two fp32 -> packed bf16 with the hardware conversion (round to nearest even)
+typedef __bf16 bf16x2v __attribute__((ext_vector_type(2)));
+typedef float f32x2v __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack2hw(float lo, float hi) {
+    const f32x2v f = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2v));
 }
 // all of this wavefront's direct loads and LDS accesses have completed; then the workgroup barrier
 __device__ __forceinline__ void wait_all_and_barrier() {
@@ -204,31 +212,33 @@ __global__ __launch_bounds__(NTHR) void fused_gemm_kernel(GemmArgs g) {
     // ---- contraction over the frozen weight: whole 64-wide tiles -------------------------------
     const int nk = g.skip_base ? 0 : g.Kdim / BK;
     if (nk > 0) {
-        // per-lane global pointers of the direct loads: 4 instructions per wave per operand, each fills 1 KB of LDS.
-        // Rows / columns past the edge are clamped to valid memory (they only feed outputs that are never stored).
-        const char* pa[4];
-        const char* pb[4];
+        // direct loads: 4 instructions per wave per operand, each fills 1 KB of LDS.  Address = uniform base (advances one
+        // tile per step) + constant per-lane byte offset.  Rows / columns past the edge are clamped to valid memory (they
+        // only feed outputs that are never stored).
+        unsigned oa[4], ob[4];
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             const int ii = wave * 4 + c;
             const int row = ii * 8 + (lane >> 3), ch = (lane & 7) ^ (lane >> 3);
-            pa[c] = reinterpret_cast<const char*>(g.Aop + (int64_t)min(m0 + row, g.M - 1) * g.lda + ch * 8);
+            oa[c] = (unsigned)((int64_t)(min(m0 + row, g.M - 1) - m0) * g.lda + ch * 8) * 2u;
             if (NN) {
                 const int k = ii * 2 + (lane >> 5);
                 const int chn = (lane & 31) ^ (nn_swz(k) << 1);
-                pb[c] = reinterpret_cast<const char*>(g.Bop + (int64_t)k * g.ldb + min(n0 + chn * 8, g.Ncols - 8));
+                ob[c] = (unsigned)((int64_t)k * g.ldb + min(n0 + chn * 8, g.Ncols - 8)) * 2u;
             } else {
-                pb[c] = reinterpret_cast<const char*>(g.Bop + (int64_t)min(n0 + row, g.Ncols - 1) * g.ldb + ch * 8);
+                ob[c] = (unsigned)((int64_t)(min(n0 + row, g.Ncols - 1) - n0) * g.ldb + ch * 8) * 2u;
             }
         }
+        const char* baseA = reinterpret_cast<const char*>(g.Aop + (int64_t)m0 * g.lda);
+        const char* baseB = NN ? reinterpret_cast<const char*>(g.Bop) : reinterpret_cast<const char*>(g.Bop + (int64_t)n0 * g.ldb);
         const int64_t astep = (int64_t)BK * 2, bstep = NN ? (int64_t)BK * g.ldb * 2 : (int64_t)BK * 2;
         auto load_tile = [&](int stage, bool advance) {
             const unsigned dst = (unsigned)(uintptr_t)lds + stage * STAGE_BYTES + wave * 4096;
-            const int64_t da = advance ? astep : 0, db = advance ? bstep : 0;
 #pragma unroll
-            for (int c = 0; c < 4; ++c) { dma16(pa[c], dst + c * 1024); pa[c] += da; }
+            for (int c = 0; c < 4; ++c) dma16(oa[c], baseA, dst + c * 1024);
 #pragma unroll
-            for (int c = 0; c < 4; ++c) { dma16(pb[c], dst + TILE_BYTES + c * 1024); pb[c] += db; }
+            for (int c = 0; c < 4; ++c) dma16(ob[c], baseB, dst + TILE_BYTES + c * 1024);
+            if (advance) { baseA += astep; baseB += bstep; }
         };
 
         load_tile(0, nk > 1);
@@ -316,8 +326,8 @@ __global__ __launch_bounds__(NTHR) void fused_gemm_kernel(GemmArgs g) {
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
                 uint2 v;
-                v.x = pack2(acc[a][b][0], acc[a][b][1]);
-                v.y = pack2(acc[a][b][2], acc[a][b][3]);
+                v.x = pack2hw(acc[a][b][0], acc[a][b][1]);
+                v.y = pack2hw(acc[a][b][2], acc[a][b][3]);
                 *reinterpret_cast<uint2*>(Es + (a * 16 + l16) * E_LD + b * 16 + g4 * 4) = v;
             }
         // the same wavefront reads back what it wrote: only its own LDS writes must have landed
@@ -349,6 +359,11 @@ __global__ __launch_bounds__(NTHR) void fused_gemm_kernel(GemmArgs g) {
 static int launch_gemm(mlora_plan* p, bool fwd, const void* Aop, const void* W, void* C, const void* E,
                        uint32_t flags, hipStream_t st) {
     if (p->T == 0) return MLORA_OK;
+    // the direct tile loads address a tile with 32-bit byte offsets from its first row: 256 rows of k or n elements
+    if (p->k > (int64_t(1) << 22) || p->n > (int64_t(1) << 22)) {
+        set_error("bf16 MFMA path supports k, n up to 4194304");
+        return MLORA_ERR_SHAPE;
+    }
     GemmArgs g{};
     g.Aop = (const u16*)Aop;
     g.Bop = (const u16*)W;
