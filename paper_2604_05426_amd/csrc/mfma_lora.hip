@@ -65,14 +65,14 @@ __global__ __launch_bounds__(64 * SNW) void shrink_kernel(ShrinkArgs g) {
 #pragma unroll
             for (int q = 0; q < 16; ++q) acc[mb][nb][q] = 0.f;
 
-    // this wavefront's slice of the contraction, in steps of 32
+    // this wavefront's share of the contraction: steps of 32, dealt round-robin to the wavefronts so that at any
+    // time the eight streams of a workgroup read neighbouring 64-byte pieces of the same rows
     const int steps = (g.Kdim + SKS - 1) / SKS;
-    const int per = (steps + SNW - 1) / SNW;
-    const int s_begin = wave * per, s_end = min(steps, s_begin + per);
+    const int s_begin = 0, s_end = wave < steps ? (steps - wave + SNW - 1) / SNW : 0;
 
     uint4 rx[DX][4], rf[DF][NF];
-    auto gloadX = [&](int step, int set) {
-        const int k0 = step * SKS;
+    auto gloadX = [&](int lstep, int set) {
+        const int k0 = (lstep * SNW + wave) * SKS;
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {
             const int row = (lane >> 2) + 16 * jj, gk = k0 + (lane & 3) * 8;
@@ -80,8 +80,8 @@ __global__ __launch_bounds__(64 * SNW) void shrink_kernel(ShrinkArgs g) {
                               ? *reinterpret_cast<const uint4*>(g.src + (int64_t)(row0 + row) * g.ld + gk) : zero4();
         }
     };
-    auto gloadF = [&](int step, int set) {
-        const int k0 = step * SKS;
+    auto gloadF = [&](int lstep, int set) {
+        const int k0 = (lstep * SNW + wave) * SKS;
 #pragma unroll
         for (int jj = 0; jj < NF; ++jj) {
             const int idx = lane + 64 * jj;
