@@ -143,6 +143,9 @@ int multi_lora_plan_dump(const mlora_plan* plan, int which, int32_t* entries, in
  *   Y  device [T,n] out (in/out with MLORA_FLAG_LORA_ONLY)
  *   S  device ragged [sum T_i r_i] out, unscaled X_i A_i
  *   workspace  device, multi_lora_workspace_bytes(plan) bytes
+ * The pointer arrays are copied into a device table owned by the plan; a call that passes the same
+ * pointers on the same stream as the previous call reuses the table without another launch.  One plan
+ * must not be used from two streams at once.
  */
 int multi_lora_fwd(mlora_plan* plan, const void* X, const void* W, const void* const* A,
                    const void* const* B, void* Y, void* S, void* workspace, uint32_t flags,

@@ -71,6 +71,10 @@ struct mlora_plan {
     size_t d_block_bytes = 0;
     mlora::PlanView view{};
     mlora::AdapterPtrs* d_ptrs = nullptr;
+    // host mirror of the device pointer table: a call whose pointers match what the same stream uploaded last skips the upload
+    std::vector<mlora::AdapterPtrs> ptr_mirror;
+    bool ptr_mirror_valid = false;
+    hipStream_t ptr_mirror_stream = nullptr;
     void* d_probs = nullptr;          // descriptor scratch of the FMA grouped GEMM
     void* d_adamw = nullptr;          // [N] optimizer entries (pointers + hyper-parameters), refreshed per call
     int64_t* d_part_off = nullptr;    // [N] float offset of each adapter's partial weight-gradient block

@@ -121,22 +121,44 @@ __global__ void upload_ptrs_kernel(AdapterPtrs* dst, PtrBatch batch, int32_t bas
     if (i < count) dst[base + i] = batch.p[i];
 }
 
+// Refreshes the device table of per-adapter pointers.  The forward passes no gradient pointers and leaves the ones in
+// the table alone.  The table is left as it is when the same stream already uploaded exactly these pointers (the usual
+// case: the same buffers every training step); a stream under graph capture always records the upload.
 int upload_ptrs(mlora_plan* p, const void* const* A, const void* const* B, void* const* dA,
                 void* const* dB, hipStream_t st) {
+    if (p->N == 0) return MLORA_OK;
+    const bool grads = dA != nullptr || dB != nullptr;
+    if (p->ptr_mirror.size() != (size_t)p->N) {
+        p->ptr_mirror.assign((size_t)p->N, AdapterPtrs{nullptr, nullptr, nullptr, nullptr});
+        p->ptr_mirror_valid = false;
+    }
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(st, &cap) != hipSuccess) { (void)hipGetLastError(); cap = hipStreamCaptureStatusNone; }
+    const bool capturing = cap != hipStreamCaptureStatusNone;
+    bool same = p->ptr_mirror_valid && p->ptr_mirror_stream == st && !capturing;
+    for (int32_t i = 0; i < p->N; ++i) {
+        AdapterPtrs& m = p->ptr_mirror[i];
+        const void* a = A ? A[i] : nullptr;
+        const void* b = B ? B[i] : nullptr;
+        if (m.A != a || m.B != b) { same = false; m.A = a; m.B = b; }
+        if (grads) {
+            void* da = dA ? dA[i] : nullptr;
+            void* db = dB ? dB[i] : nullptr;
+            if (m.dA != da || m.dB != db) { same = false; m.dA = da; m.dB = db; }
+        }
+    }
+    if (same) return MLORA_OK;
     for (int32_t base = 0; base < p->N; base += 32) {
         PtrBatch batch;
         std::memset(&batch, 0, sizeof(batch));
         const int32_t cnt = (p->N - base) < 32 ? (p->N - base) : 32;
-        for (int32_t j = 0; j < cnt; ++j) {
-            batch.p[j].A = A ? A[base + j] : nullptr;
-            batch.p[j].B = B ? B[base + j] : nullptr;
-            batch.p[j].dA = dA ? dA[base + j] : nullptr;
-            batch.p[j].dB = dB ? dB[base + j] : nullptr;
-        }
+        for (int32_t j = 0; j < cnt; ++j) batch.p[j] = p->ptr_mirror[base + j];
         ProfScope prof(p, MLORA_K_OTHER, st);
         hipLaunchKernelGGL(upload_ptrs_kernel, dim3(1), dim3(32), 0, st, p->d_ptrs, batch, base, cnt);
     }
     MLORA_HIP_TRY(hipGetLastError());
+    p->ptr_mirror_valid = !capturing;
+    p->ptr_mirror_stream = st;
     return MLORA_OK;
 }
 
