@@ -91,6 +91,16 @@ def test_bf16_ragged_small(seed, k, n, ranks, lens):
     check_full(w)
 
 
+@pytest.mark.parametrize("k,n", [(64, 128), (128, 64), (192, 256), (256, 192), (40, 72), (72, 40), (96, 520), (520, 96)])
+def test_bf16_contraction_lengths_around_the_two_stage_pipeline(k, n):
+    # the fused GEMM keeps two tiles in LDS and loads two tiles ahead: contractions of 0, 1, 2, 3, 4 and 8 whole
+    # 64-wide tiles, with and without a partial tile, exercise its prologue, steady state and drain (forward
+    # contracts over k, backward over n); 300 rows = one full 256-row tile and a partial one
+    w = wl.small_case(seed=70 + k % 7 + n % 5, dtype="bf16", k=k, n=n, ranks=(8, 40), seg_lens=(300, 45),
+                      scales=(2.0, 0.5), b_sigma=0.3)
+    check_full(w)
+
+
 def test_bf16_odd_widths_use_fma_kernels():
     w = wl.small_case(seed=35, dtype="bf16", k=100, n=52, ranks=(4, 7, 0, 16), seg_lens=(33, 64, 10, 70),
                       scales=(2.0, 0.5, 1.0, 1.5), b_sigma=0.3)
