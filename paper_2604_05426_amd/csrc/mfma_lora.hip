@@ -20,11 +20,7 @@ namespace mlora {
 // (deterministic) and rounded once.
 // =========================================================================================
 constexpr int SR = 64;             // rows per block == kBlockRows
-constexpr int SKS = 32;            // contraction elements per wavefront step
 constexpr int SNW = 8;             // wavefronts per workgroup
-constexpr int SX_LD = SKS + 8;     // X / dY tile [64][40]: 80-byte rows, conflict-free 128-bit reads
-constexpr int SX_TILE = SR * SX_LD;
-constexpr int S_RLD = 132;         // fp32 reduction tile row
 static_assert(kBlockRows == SR, "row-block table and shrink kernel must agree");
 
 struct ShrinkArgs {
@@ -35,15 +31,26 @@ struct ShrinkArgs {
 };
 
 // MAXNB: rank blocks of 32 the kernel is built for (2: every rank <= 64, 4: ranks up to 128).
+// SKS: contraction elements per wavefront step.  64 (ranks <= 64): every load instruction takes whole 128-byte lines,
+//      which halves the number of outstanding line requests per byte (the L1's pending-miss capacity is what limits this
+//      kernel); the X / dY tile is then unpadded and XOR-swizzled (chunk c of row r at c ^ ((r >> 1) & 7)), which keeps
+//      the private LDS of the eight wavefronts at exactly 160 KB.  32 (wide ranks): 80-byte padded rows.
 // DX / DF: register prefetch depth in steps for the streamed operand (X or dY, comes from HBM) and for
-// the adapter matrix (cache resident); the wide-rank build only has registers for DX = 2, DF = 1.
-template <bool FWD, int MAXNB, int DX, int DF>
+// the adapter matrix (cache resident).
+template <bool FWD, int MAXNB, int SKS, int DX, int DF>
 __global__ __launch_bounds__(64 * SNW) void shrink_kernel(ShrinkArgs g) {
-    constexpr int SBN_LD = MAXNB == 2 ? 96 : 160;                 // FWD small tile [32 contraction][LD] (192 / 320-byte rows)
-    constexpr int SB_TILE = (32 * SBN_LD > MAXNB * 32 * SX_LD) ? 32 * SBN_LD : MAXNB * 32 * SX_LD;
+    constexpr bool SWZ = SKS == 64;
+    constexpr int SX_LD = SWZ ? SKS : SKS + 8;                    // X / dY tile row (elements)
+    constexpr int SX_TILE = SR * SX_LD;
+    constexpr int SF_LD = SKS + 8;                                // !FWD small tile [rank][LD]: 80 / 144-byte rows
+    constexpr int SBN_LD = MAXNB == 2 ? 96 : 160;                 // FWD small tile [SKS contraction][LD] (192 / 320-byte rows)
+    constexpr int SB_TILE = (SKS * SBN_LD > MAXNB * 32 * SF_LD) ? SKS * SBN_LD : MAXNB * 32 * SF_LD;
     constexpr int S_WAVE = SX_TILE + SB_TILE;                     // per-wavefront private LDS (elements)
-    constexpr int NF = MAXNB * 2;                                 // small-tile chunks per lane per step
+    constexpr int XC = SKS / 8;                                   // 16-byte chunks per X row per step
+    constexpr int NX = SR * XC / 64;                              // X chunks per lane per step
+    constexpr int NF = MAXNB * 32 * XC / 64;                      // small-tile chunks per lane per step
     constexpr int CPRF = MAXNB * 4;                               // FWD: 16-byte chunks per small-tile row
+    static_assert(SNW * S_WAVE * 2 <= 163840, "private tiles fit in LDS");
     __shared__ __attribute__((aligned(16))) u16 lds[SNW * S_WAVE];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const Entry4 e = g.pv.row_blocks[blockIdx.x];
@@ -56,6 +63,8 @@ __global__ __launch_bounds__(64 * SNW) void shrink_kernel(ShrinkArgs g) {
     const float s = FWD ? 1.0f : g.pv.scale[i];
     u16* Xs = lds + wave * S_WAVE;
     u16* Fs = Xs + SX_TILE;
+    // element offset of 16-byte chunk c of row `row` in the X tile
+    auto xs_off = [&](int row, int c) { return SWZ ? row * SX_LD + ((c ^ ((row >> 1) & 7)) << 3) : row * SX_LD + c * 8; };
 
     f32x16 acc[2][MAXNB];
 #pragma unroll
@@ -65,17 +74,17 @@ __global__ __launch_bounds__(64 * SNW) void shrink_kernel(ShrinkArgs g) {
 #pragma unroll
             for (int q = 0; q < 16; ++q) acc[mb][nb][q] = 0.f;
 
-    // this wavefront's share of the contraction: steps of 32, dealt round-robin to the wavefronts so that at any
-    // time the eight streams of a workgroup read neighbouring 64-byte pieces of the same rows
+    // this wavefront's share of the contraction: steps of SKS, dealt round-robin to the wavefronts so that at any
+    // time the eight streams of a workgroup read neighbouring pieces of the same rows
     const int steps = (g.Kdim + SKS - 1) / SKS;
     const int s_begin = 0, s_end = wave < steps ? (steps - wave + SNW - 1) / SNW : 0;
 
-    uint4 rx[DX][4], rf[DF][NF];
+    uint4 rx[DX][NX], rf[DF][NF];
     auto gloadX = [&](int lstep, int set) {
         const int k0 = (lstep * SNW + wave) * SKS;
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
-            const int row = (lane >> 2) + 16 * jj, gk = k0 + (lane & 3) * 8;
+        for (int jj = 0; jj < NX; ++jj) {
+            const int row = (lane / XC) + (64 / XC) * jj, gk = k0 + (lane % XC) * 8;
             rx[set][jj] = (row < rows && gk < g.Kdim)
                               ? *reinterpret_cast<const uint4*>(g.src + (int64_t)(row0 + row) * g.ld + gk) : zero4();
         }
@@ -91,7 +100,7 @@ __global__ __launch_bounds__(64 * SNW) void shrink_kernel(ShrinkArgs g) {
                 if (cc * 8 < rpad && k0 + kr < g.Kdim)
                     rf[set][jj] = load_chunk(F + (int64_t)(k0 + kr) * r + cc * 8, min(8, r - cc * 8), f_vec);
             } else {     // B_i[rho][k0 + c * 8 ..]
-                const int rho = idx >> 2, gk = k0 + (idx & 3) * 8;
+                const int rho = idx / XC, gk = k0 + (idx % XC) * 8;
                 if (rho < r && gk < g.Kdim)
                     rf[set][jj] = *reinterpret_cast<const uint4*>(F + (int64_t)rho * g.ld + gk);
             }
@@ -99,9 +108,9 @@ __global__ __launch_bounds__(64 * SNW) void shrink_kernel(ShrinkArgs g) {
     };
     auto lstoreX = [&](int set) {
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
-            const int row = (lane >> 2) + 16 * jj;
-            *reinterpret_cast<uint4*>(Xs + row * SX_LD + (lane & 3) * 8) = rx[set][jj];
+        for (int jj = 0; jj < NX; ++jj) {
+            const int row = (lane / XC) + (64 / XC) * jj;
+            *reinterpret_cast<uint4*>(Xs + xs_off(row, lane % XC)) = rx[set][jj];
         }
     };
     auto lstoreF = [&](int set) {
@@ -112,8 +121,8 @@ __global__ __launch_bounds__(64 * SNW) void shrink_kernel(ShrinkArgs g) {
                 const int kr = idx / CPRF, cc = idx % CPRF;
                 if (cc * 8 < rpad) *reinterpret_cast<uint4*>(Fs + kr * SBN_LD + cc * 8) = rf[set][jj];
             } else {
-                const int rho = idx >> 2;
-                if (rho < rpad) *reinterpret_cast<uint4*>(Fs + rho * SX_LD + (idx & 3) * 8) = rf[set][jj];
+                const int rho = idx / XC;
+                if (rho < rpad) *reinterpret_cast<uint4*>(Fs + rho * SF_LD + (idx % XC) * 8) = rf[set][jj];
             }
         }
     };
@@ -123,7 +132,7 @@ __global__ __launch_bounds__(64 * SNW) void shrink_kernel(ShrinkArgs g) {
         for (int ks = 0; ks < SKS / 16; ++ks) {
             bf16x8 a[2];
 #pragma unroll
-            for (int mb = 0; mb < 2; ++mb) a[mb] = lds_read_frag(Xs + (mb * 32 + lm) * SX_LD + ks * 16 + h * 8);
+            for (int mb = 0; mb < 2; ++mb) a[mb] = lds_read_frag(Xs + xs_off(mb * 32 + lm, ks * 2 + h));
 #pragma unroll
             for (int nb = 0; nb < MAXNB; ++nb) {
                 if (nb < nblk) {
@@ -132,7 +141,7 @@ __global__ __launch_bounds__(64 * SNW) void shrink_kernel(ShrinkArgs g) {
                         const u16* p = Fs + (ks * 16 + 8 * (gq >> 1) + (j >> 2)) * SBN_LD + nb * 32 + 16 * (gq & 1) + 4 * (j & 3);
                         b = lds_read_frag_tr(p, p + 4 * SBN_LD);
                     } else {
-                        b = lds_read_frag(Fs + (nb * 32 + lm) * SX_LD + ks * 16 + h * 8);
+                        b = lds_read_frag(Fs + (nb * 32 + lm) * SF_LD + ks * 16 + h * 8);
                     }
 #pragma unroll
                     for (int mb = 0; mb < 2; ++mb) acc[mb][nb] = mfma32(a[mb], b, acc[mb][nb]);
@@ -204,9 +213,9 @@ __global__ __launch_bounds__(64 * SNW) void shrink_kernel(ShrinkArgs g) {
 template <bool FWD>
 static void launch_shrink(mlora_plan* p, const ShrinkArgs& a, hipStream_t st) {
     if (p->max_rank <= 64)
-        hipLaunchKernelGGL((shrink_kernel<FWD, 2, 2, 2>), dim3(p->n_row_blocks), dim3(64 * SNW), 0, st, a);
+        hipLaunchKernelGGL((shrink_kernel<FWD, 2, 64, 2, 1>), dim3(p->n_row_blocks), dim3(64 * SNW), 0, st, a);
     else
-        hipLaunchKernelGGL((shrink_kernel<FWD, 4, 2, 1>), dim3(p->n_row_blocks), dim3(64 * SNW), 0, st, a);
+        hipLaunchKernelGGL((shrink_kernel<FWD, 4, 32, 2, 1>), dim3(p->n_row_blocks), dim3(64 * SNW), 0, st, a);
 }
 
 // =========================================================================================
