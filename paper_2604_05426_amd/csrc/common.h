@@ -65,6 +65,11 @@ struct mlora_plan {
     int32_t n_row_blocks = 0, n_gemm_tiles = 0, n_wgrad_chunks = 0;
     int32_t max_rank = 0;
     int32_t max_chunks_per_adapter = 0;
+    // row blocks split by rank class (<= 64 / wider): indices into the row-block table, wide class first (its blocks run longest).  Plans that
+    // mix narrow and wide ranks run each class through the kernel build made for it.
+    std::vector<int32_t> block_lists;   // upload source
+    int32_t n_blocks_narrow = 0, n_blocks_wide = 0;
+    int32_t* d_block_lists = nullptr;
     int32_t wgrad_chunk_rows = 0;     // token chunk of the weight-gradient items (chosen per plan)
     // one device allocation carved into the tables below
     void* d_block = nullptr;

@@ -27,6 +27,7 @@ struct ShrinkArgs {
     const u16* src; int64_t ld;   // X (ld k) or dY (ld n)
     u16* out;                     // ragged S or dS
     int32_t Kdim;                 // k or n
+    const int32_t* list;          // row-block indices this launch covers (nullptr: all, in table order)
     PlanView pv;
 };
 
@@ -38,7 +39,7 @@ struct ShrinkArgs {
 // DX / DF: register prefetch depth in steps for the streamed operand (X or dY, comes from HBM) and for
 // the adapter matrix (cache resident).
 template <bool FWD, int MAXNB, int SKS, int DX, int DF>
-__global__ __launch_bounds__(64 * SNW) void shrink_kernel(ShrinkArgs g) {
+__device__ __forceinline__ void shrink_body(const ShrinkArgs& g, const Entry4 e, u16* lds) {
     constexpr bool SWZ = SKS == 64;
     constexpr int SX_LD = SWZ ? SKS : SKS + 8;                    // X / dY tile row (elements)
     constexpr int SX_TILE = SR * SX_LD;
@@ -51,9 +52,7 @@ __global__ __launch_bounds__(64 * SNW) void shrink_kernel(ShrinkArgs g) {
     constexpr int NF = MAXNB * 32 * XC / 64;                      // small-tile chunks per lane per step
     constexpr int CPRF = MAXNB * 4;                               // FWD: 16-byte chunks per small-tile row
     static_assert(SNW * S_WAVE * 2 <= 163840, "private tiles fit in LDS");
-    __shared__ __attribute__((aligned(16))) u16 lds[SNW * S_WAVE];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const Entry4 e = g.pv.row_blocks[blockIdx.x];
     const int i = e.a, row0 = e.c, rows = e.d;
     const int r = g.pv.rank[i];
     const int rpad = (r + 31) & ~31;
@@ -210,12 +209,26 @@ __global__ __launch_bounds__(64 * SNW) void shrink_kernel(ShrinkArgs g) {
     }
 }
 
+// WIDE: the launch may contain row blocks of adapters with ranks above 64; those take the wide-rank build, all others
+// the narrow one (the branch is uniform over the workgroup).  The list puts the wide blocks first: they run longest.
+template <bool FWD, bool WIDE>
+__global__ __launch_bounds__(64 * SNW) void shrink_kernel(ShrinkArgs g) {
+    __shared__ __attribute__((aligned(16))) u16 lds[163840 / 2];
+    const Entry4 e = g.pv.row_blocks[g.list ? g.list[blockIdx.x] : (int)blockIdx.x];
+    if (WIDE && g.pv.rank[e.a] > 64) shrink_body<FWD, 4, 32, 2, 1>(g, e, lds);
+    else shrink_body<FWD, 2, 64, 2, 1>(g, e, lds);
+}
+
 template <bool FWD>
-static void launch_shrink(mlora_plan* p, const ShrinkArgs& a, hipStream_t st) {
-    if (p->max_rank <= 64)
-        hipLaunchKernelGGL((shrink_kernel<FWD, 2, 64, 2, 1>), dim3(p->n_row_blocks), dim3(64 * SNW), 0, st, a);
-    else
-        hipLaunchKernelGGL((shrink_kernel<FWD, 4, 32, 2, 1>), dim3(p->n_row_blocks), dim3(64 * SNW), 0, st, a);
+static void launch_shrink(mlora_plan* p, ShrinkArgs a, hipStream_t st) {
+    const dim3 grid(p->n_row_blocks), block(64 * SNW);
+    if (p->n_blocks_wide == 0) {
+        a.list = nullptr;
+        hipLaunchKernelGGL((shrink_kernel<FWD, false>), grid, block, 0, st, a);
+    } else {
+        a.list = p->d_block_lists;
+        hipLaunchKernelGGL((shrink_kernel<FWD, true>), grid, block, 0, st, a);
+    }
 }
 
 // =========================================================================================
@@ -410,6 +423,7 @@ struct ExpandArgs {
     u16* C; int64_t ldc;     // Y [T,n] or dX [T,k]
     const u16* E;            // ragged S or dS
     int32_t Ncols, col_tiles;
+    const int32_t* list;     // row-block indices this launch covers (nullptr: all, in table order)
     PlanView pv;
 };
 
@@ -424,7 +438,8 @@ __global__ __launch_bounds__(256) void expand_add_kernel(ExpandArgs g) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int lm = lane & 31, h = lane >> 5, gq = lane >> 4, j = lane & 15;
     // row-block-major: consecutive workgroups cover adjacent column tiles of the same 64 rows
-    const Entry4 e = g.pv.row_blocks[blockIdx.x / g.col_tiles];
+    const int bsel = blockIdx.x / g.col_tiles;
+    const Entry4 e = g.pv.row_blocks[g.list ? g.list[bsel] : bsel];
     const int ct = blockIdx.x % g.col_tiles;
     const int i = e.a, row0 = e.c, rows = e.d;
     const int r = g.pv.rank[i];
@@ -572,13 +587,22 @@ static int launch_expand(mlora_plan* p, bool fwd, void* C, const void* E, hipStr
     a.Ncols = (int32_t)(fwd ? p->n : p->k);
     a.ldc = a.Ncols;
     a.col_tiles = (a.Ncols + XC - 1) / XC;
-    const int64_t grid = (int64_t)p->n_row_blocks * a.col_tiles;
     ProfScope prof(p, fwd ? MLORA_K_GEMM_FWD : MLORA_K_GEMM_BWD, st);
-    const bool small = p->max_rank <= 64;
-    if (fwd && small)       hipLaunchKernelGGL((expand_add_kernel<true, 4>), dim3((unsigned)grid), dim3(256), 0, st, a);
-    else if (fwd)           hipLaunchKernelGGL((expand_add_kernel<true, 8>), dim3((unsigned)grid), dim3(256), 0, st, a);
-    else if (small)         hipLaunchKernelGGL((expand_add_kernel<false, 4>), dim3((unsigned)grid), dim3(256), 0, st, a);
-    else                    hipLaunchKernelGGL((expand_add_kernel<false, 8>), dim3((unsigned)grid), dim3(256), 0, st, a);
+    auto go = [&](bool narrow, int32_t nblocks, const int32_t* list) {
+        if (nblocks <= 0) return;
+        a.list = list;
+        const dim3 grid((unsigned)((int64_t)nblocks * a.col_tiles));
+        if (fwd && narrow)      hipLaunchKernelGGL((expand_add_kernel<true, 4>), grid, dim3(256), 0, st, a);
+        else if (fwd)           hipLaunchKernelGGL((expand_add_kernel<true, 8>), grid, dim3(256), 0, st, a);
+        else if (narrow)        hipLaunchKernelGGL((expand_add_kernel<false, 4>), grid, dim3(256), 0, st, a);
+        else                    hipLaunchKernelGGL((expand_add_kernel<false, 8>), grid, dim3(256), 0, st, a);
+    };
+    if (p->n_blocks_wide == 0) {
+        go(true, p->n_row_blocks, nullptr);
+    } else {   // each rank class through the build made for it
+        go(false, p->n_blocks_wide, p->d_block_lists);
+        go(true, p->n_blocks_narrow, p->d_block_lists + p->n_blocks_wide);
+    }
     MLORA_HIP_TRY(hipGetLastError());
     return MLORA_OK;
 }

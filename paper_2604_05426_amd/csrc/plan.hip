@@ -287,6 +287,19 @@ extern "C" int multi_lora_plan_create(mlora_plan** out, int dtype, int64_t T, in
         }
         if (ranks[i] > p->max_rank) p->max_rank = ranks[i];
     }
+    {   // same enumeration as the device-built row-block table: adapters ascending, blocks ascending
+        std::vector<int32_t> narrow;
+        int32_t idx = 0;
+        for (int32_t i = 0; i < N; ++i) {
+            const int64_t Ti = p->off[i + 1] - p->off[i];
+            if (Ti <= 0 || ranks[i] <= 0) continue;
+            const int32_t nb = (int32_t)ceil_div(Ti, kBlockRows);
+            for (int32_t b = 0; b < nb; ++b, ++idx) (ranks[i] <= 64 ? narrow : p->block_lists).push_back(idx);
+        }
+        p->n_blocks_wide = (int32_t)p->block_lists.size();
+        p->n_blocks_narrow = (int32_t)narrow.size();
+        p->block_lists.insert(p->block_lists.end(), narrow.begin(), narrow.end());
+    }
     p->soff[N] = s;
     p->wchunk_start[N] = (int32_t)wc;
     p->R1 = s;
@@ -326,6 +339,7 @@ extern "C" int multi_lora_plan_create(mlora_plan** out, int dtype, int64_t T, in
     const size_t o_probs = take(128 * (size_t)(5 * N + 8));
     const size_t o_part = take(sizeof(int64_t) * (N + 1));
     const size_t o_adamw = take(96 * (size_t)(N + 1));
+    const size_t o_lists = take(sizeof(int32_t) * (size_t)(p->n_row_blocks + 1));
     p->d_block_bytes = o;
 
     if (e == hipSuccess) e = hipMalloc(&p->d_block, p->d_block_bytes);
@@ -347,6 +361,7 @@ extern "C" int multi_lora_plan_create(mlora_plan** out, int dtype, int64_t T, in
     p->d_probs = base + o_probs;
     p->d_part_off = (int64_t*)(base + o_part);
     p->d_adamw = base + o_adamw;
+    p->d_block_lists = (int32_t*)(base + o_lists);
 
     hipStream_t st = p->build_stream;
     std::vector<int32_t>& off32 = p->off32;
@@ -367,6 +382,10 @@ extern "C" int multi_lora_plan_create(mlora_plan** out, int dtype, int64_t T, in
     }
     if ((e = hipMemcpyAsync(p->d_part_off, part_off.data(), sizeof(int64_t) * (N + 1), hipMemcpyHostToDevice, st)) != hipSuccess)
         return fail(e, "hipMemcpyAsync(partial offsets)");
+    if (!p->block_lists.empty() &&
+        (e = hipMemcpyAsync(p->d_block_lists, p->block_lists.data(), sizeof(int32_t) * p->block_lists.size(),
+                            hipMemcpyHostToDevice, st)) != hipSuccess)
+        return fail(e, "hipMemcpyAsync(row-block classes)");
     hipLaunchKernelGGL(plan_scan_kernel, dim3(1), dim3(64), 0, st, N, d_off, d_rank, d_soff, d_rbs, d_wcs,
                        kBlockRows, p->wgrad_chunk_rows);
     if (p->n_row_blocks > 0)
