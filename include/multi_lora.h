@@ -66,6 +66,10 @@ typedef enum {
 #define MLORA_FLAG_LORA_ONLY 2u /* skip W: fwd Y += s S B in place (Y holds Y_base on entry, the
                                    paper's decoupled "fused GEMM-add", Sec. 5.1 / App. A.1);
                                    bwd dX += dS A^T in place; S, dA, dB as usual */
+#define MLORA_FLAG_ACCUM_GRADS 4u /* multi_lora_bwd only: dA_i, dB_i += this call's gradients instead of being
+                                   overwritten (gradient accumulation over micro-batches; the paper's runs use 1
+                                   accumulation step).  The sum is formed in fp32 from the stored value and the
+                                   fp32 result and rounded once to the plan dtype.  dX is not affected. */
 
 /* which table multi_lora_plan_dump copies out */
 typedef enum {

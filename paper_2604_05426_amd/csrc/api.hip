@@ -5,8 +5,8 @@ using namespace mlora;
 
 static inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
-static int check_flags(uint32_t flags) {
-    if (flags & ~(MLORA_FLAG_BASE_ONLY | MLORA_FLAG_LORA_ONLY)) {
+static int check_flags(uint32_t flags, bool backward) {
+    if (flags & ~(MLORA_FLAG_BASE_ONLY | MLORA_FLAG_LORA_ONLY | (backward ? MLORA_FLAG_ACCUM_GRADS : 0u))) {
         set_error("unknown flag bits");
         return MLORA_ERR_FLAGS;
     }
@@ -45,7 +45,7 @@ extern "C" int multi_lora_fwd(mlora_plan* plan, const void* X, const void* W, co
         set_error("plan is NULL");
         return MLORA_ERR_NULL;
     }
-    int rc = check_flags(flags);
+    int rc = check_flags(flags, false);
     if (rc != MLORA_OK) return rc;
     const bool lora = !(flags & MLORA_FLAG_BASE_ONLY) && plan->N > 0;
     const bool base = !(flags & MLORA_FLAG_LORA_ONLY);
@@ -79,7 +79,7 @@ extern "C" int multi_lora_bwd(mlora_plan* plan, const void* dY, const void* X, c
         set_error("plan is NULL");
         return MLORA_ERR_NULL;
     }
-    int rc = check_flags(flags);
+    int rc = check_flags(flags, true);
     if (rc != MLORA_OK) return rc;
     const bool lora = !(flags & MLORA_FLAG_BASE_ONLY) && plan->N > 0;
     const bool base = !(flags & MLORA_FLAG_LORA_ONLY);

@@ -34,6 +34,7 @@ struct FmaOperands {
     void* dX;
     void* S;   // S (fwd out / bwd in)
     void* dS;
+    int accum_grads;   // dA_i, dB_i += result
 };
 
 template <typename T> __device__ inline float ld(const T* p);
@@ -92,13 +93,13 @@ __global__ void fma_make_probs_kernel(PlanView pv, FmaOperands ops, int op, GPro
                 g.A = (const T*)ops.X + row0 * pv.k; g.lda = pv.k; g.transA = 1;
                 g.B = (const T*)ops.dS + so; g.ldb = r;
                 g.C = ap.dA; g.ldc = r;
-                g.M = (int32_t)pv.k; g.N = r; g.K = Ti;
+                g.M = (int32_t)pv.k; g.N = r; g.K = Ti; g.accumulate = ops.accum_grads;
                 break;
             case OP_WGRAD_B:
                 g.A = (const T*)ops.S + so; g.lda = r; g.transA = 1;
                 g.B = (const T*)ops.dY + row0 * pv.n; g.ldb = pv.n;
                 g.C = ap.dB; g.ldc = pv.n;
-                g.M = r; g.N = (int32_t)pv.n; g.K = Ti; g.alpha = s;
+                g.M = r; g.N = (int32_t)pv.n; g.K = Ti; g.alpha = s; g.accumulate = ops.accum_grads;
                 break;
         }
         if (r == 0) g.M = 0;   // rank-0 adapters have no LoRA work in any op
@@ -261,6 +262,7 @@ static int bwd_t(mlora_plan* p, const void* dY, const void* X, const void* W, co
                  uint32_t flags, hipStream_t st) {
     FmaOperands ops{};
     ops.X = X; ops.dY = dY; ops.dX = dX; ops.S = const_cast<void*>(S); ops.dS = dS;
+    ops.accum_grads = (flags & MLORA_FLAG_ACCUM_GRADS) ? 1 : 0;
     int rc;
     if (!(flags & MLORA_FLAG_BASE_ONLY))
         if ((rc = run_grouped<T>(p, ops, OP_DSHRINK, 0, st)) != MLORA_OK) return rc;

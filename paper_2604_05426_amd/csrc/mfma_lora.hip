@@ -252,6 +252,7 @@ struct WgradArgs {
     int32_t panels_k, panels_n;
     PlanView pv;
     const int64_t* part_off;   // [N] float offset of adapter i's partial block (chunks > 1 only)
+    int32_t accumulate;        // dA_i, dB_i += result (MLORA_FLAG_ACCUM_GRADS)
 };
 
 __global__ __launch_bounds__(256) void wgrad_kernel(WgradArgs g) {
@@ -365,7 +366,7 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradArgs g) {
             const int64_t idx = isA ? ((int64_t)c * r + rho) : ((int64_t)rho * nn + c);
             if (nchunks == 1) {
                 u16* out = (u16*)(isA ? g.pv.ptrs[i].dA : g.pv.ptrs[i].dB);
-                out[idx] = f2bf(s * acc[nb][q]);
+                out[idx] = f2bf(g.accumulate ? s * acc[nb][q] + bf2f(out[idx]) : s * acc[nb][q]);
             } else {
                 float* part = g.partials + g.part_off[i] + (int64_t)chunk * (kk + nn) * r + (isA ? 0 : kk * r);
                 part[idx] = s * acc[nb][q];
@@ -387,8 +388,8 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(WgradArgs g) {
     const float* part = g.partials + g.part_off[i] + idx;
     float v = 0.f;
     for (int c = 0; c < nchunks; ++c) v += part[(int64_t)c * per];
-    if (idx < kk * r) ((u16*)g.pv.ptrs[i].dA)[idx] = f2bf(v);
-    else ((u16*)g.pv.ptrs[i].dB)[idx - kk * r] = f2bf(v);
+    u16* out = idx < kk * r ? (u16*)g.pv.ptrs[i].dA + idx : (u16*)g.pv.ptrs[i].dB + (idx - kk * r);
+    *out = f2bf(g.accumulate ? v + bf2f(*out) : v);
 }
 
 // Zero-fills dA_i, dB_i of adapters that have a rank but no tokens (no work item reaches them).
@@ -640,6 +641,7 @@ int mfma_backward(mlora_plan* p, const void* dY, const void* X, const void* W, c
         w.panels_n = (int32_t)((p->n + WP - 1) / WP);
         w.pv = p->view;
         w.part_off = p->d_part_off;
+        w.accumulate = (flags & MLORA_FLAG_ACCUM_GRADS) ? 1 : 0;
         if (p->n_wgrad_chunks > 0) {
             const int64_t grid = (int64_t)p->n_wgrad_chunks * (w.panels_k + w.panels_n);
             {
@@ -652,7 +654,7 @@ int mfma_backward(mlora_plan* p, const void* dY, const void* X, const void* W, c
                 hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)((per + 255) / 256), p->N), dim3(256), 0, st, w);
             }
         }
-        if (p->has_empty_ranked) {
+        if (p->has_empty_ranked && !w.accumulate) {   // adapters without tokens add nothing when accumulating
             ProfScope prof(p, MLORA_K_OTHER, st);
             hipLaunchKernelGGL(wgrad_zero_empty_kernel, dim3(64, p->N), dim3(256), 0, st, p->view);
         }

@@ -157,6 +157,31 @@ def test_base_only_and_lora_only_modes(dtype, ranks):
     assert rel_fro(to_host(dl.Y), fw.Y) <= tol
 
 
+@pytest.mark.parametrize("dtype,lens", [("bf16", (300, 1200, 77, 0)), ("f32", (129, 70, 33, 0))])
+def test_gradient_accumulation_flag(dtype, lens):
+    # two backward calls with MLORA_FLAG_ACCUM_GRADS on zeroed gradients hold twice the oracle's dA_i, dB_i; dX is
+    # overwritten as usual; the 1200-token segment is split over several weight-gradient chunks in the bf16 plan
+    w = wl.small_case(seed=64, dtype=dtype, k=256, n=320, ranks=(8, 64, 100, 16), seg_lens=lens,
+                      scales=(2.0, 0.25, 1.0, 3.0), b_sigma=0.3)
+    bw = orc.backward(w.dY, w.X, w.W, w.A, w.B, w.scales, w.offsets)
+    dl = DeviceLayer(w)
+    dl.forward()
+    for t in dl.dA + dl.dB:
+        t.zero_()
+    dl.backward(ml.FLAG_ACCUM_GRADS); dl.backward(ml.FLAG_ACCUM_GRADS); dl.sync()
+    tol = TOL[dtype]
+    assert rel_fro(to_host(dl.dX), bw.dX) <= tol
+    for i in range(w.N):
+        assert rel_fro(to_host(dl.dA[i]), 2.0 * bw.dA[i]) <= tol, i
+        assert rel_fro(to_host(dl.dB[i]), 2.0 * bw.dB[i]) <= tol, i
+    dl.backward(); dl.sync()          # without the flag the gradients are overwritten again
+    for i in range(w.N):
+        assert rel_fro(to_host(dl.dA[i]), bw.dA[i]) <= tol and rel_fro(to_host(dl.dB[i]), bw.dB[i]) <= tol
+    with pytest.raises(ml.MultiLoraError) as e:   # the flag belongs to the backward
+        dl.forward(ml.FLAG_ACCUM_GRADS)
+    assert e.value.status == -9
+
+
 # ---- degenerate shapes ----------------------------------------------------------------------------
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_no_adapters_and_no_tokens(dtype):
