@@ -178,6 +178,26 @@ def main() -> int:
                             "frac_bf16_mfma_peak": flops_base / (ms_base * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS,
                             "fused_over_base": ms_step / ms_base}
 
+    if not args.no_extra and not args.fused_only:
+        # what this GPU sustains right now for the two resources the fractions above are priced against (the published
+        # peaks stay the denominators of `frac`): a register-only loop of the GEMM's 16x16x32 MFMAs on random operands
+        # (runs into the board power limit like the GEMM does) and on zeros (no throttling), and a streaming read
+        scratch = torch.zeros(4096, dtype=torch.uint8, device=dl.device)
+        buf = torch.zeros(1 << 30, dtype=torch.uint8, device=dl.device)
+        meas = {
+            "mfma_loop_random_tflops": ml.multi_lora_calib_mfma(True, scratch, dl.stream),
+            "mfma_loop_zeros_tflops": ml.multi_lora_calib_mfma(False, scratch, dl.stream),
+            "stream_read_gbs": ml.multi_lora_calib_read(buf, 1 << 30, scratch, dl.stream),
+        }
+        del buf
+        out["measured_ceilings"] = meas
+        if out.get("roofline", {}).get("bound") == "mfma":
+            out["roofline"]["frac_of_measured_mfma_loop"] = out["roofline"]["achieved"] / meas["mfma_loop_random_tflops"]
+        if "lora_path" in out:
+            out["lora_path"]["frac_of_measured_stream_read"] = (
+                (out["lora_path"]["fwd_gbs"] * out["lora_path"]["fwd_ms"] + out["lora_path"]["bwd_gbs"] * out["lora_path"]["bwd_ms"])
+                / (out["lora_path"]["fwd_ms"] + out["lora_path"]["bwd_ms"]) / meas["stream_read_gbs"])
+
     if args.calib_copy:
         src = torch.zeros(1 << 30, dtype=torch.uint8, device=dl.device)
         dst = torch.empty_like(src)

@@ -217,6 +217,17 @@ int multi_lora_adamw_step(mlora_plan* plan, void* const* A, void* const* B, cons
                           const void* const* dB, float* const* stateA, float* const* stateB,
                           const mlora_adamw_hparams* hp, void* stream);
 
+/*
+ * Measurement aids for benchmarks (no part of the layer; both synchronise the stream and take a few tens of ms).
+ * multi_lora_calib_mfma: TFLOP/s of a register-only loop of the 16x16x32 bf16 MFMAs the fused GEMM is built from,
+ *   8 wavefronts per CU; random_data != 0 uses random operands (the power draw of a real GEMM, under which the
+ *   board reaches its power limit and lowers the clock), 0 uses zeros (no throttling).
+ * multi_lora_calib_read: GB/s of a coalesced streaming read of `buffer` (device, 16-byte aligned, >= 1 MiB).
+ * scratch: device, at least 4096 bytes, never written in practice.  tflops / gbs: host, out.
+ */
+int multi_lora_calib_mfma(int32_t random_data, void* scratch, float* tflops, void* stream);
+int multi_lora_calib_read(const void* buffer, size_t bytes, void* scratch, float* gbs, void* stream);
+
 /* Thread-local text of the last error returned on this thread ("" if none). */
 const char* multi_lora_last_error(void);
 

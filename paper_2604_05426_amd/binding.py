@@ -30,7 +30,8 @@ EXPORTS = ["multi_lora_plan_create", "multi_lora_plan_destroy", "multi_lora_vali
            "multi_lora_workspace_bytes", "multi_lora_plan_geometry", "multi_lora_plan_dump",
            "multi_lora_fwd", "multi_lora_bwd", "multi_lora_last_error", "multi_lora_version",
            "multi_lora_profile_begin", "multi_lora_profile_end",
-           "multi_lora_adamw_init", "multi_lora_adamw_step"]
+           "multi_lora_adamw_init", "multi_lora_adamw_step",
+           "multi_lora_calib_mfma", "multi_lora_calib_read"]
 
 KERNEL_NAMES = {0: "shrink", 1: "gemm_fwd", 2: "dshrink", 3: "gemm_bwd", 4: "wgrad", 5: "wgrad_reduce", 6: "other",
                 7: "adamw"}
@@ -84,6 +85,10 @@ def lib() -> ctypes.CDLL:
         L.multi_lora_adamw_init.restype = ctypes.c_int
         L.multi_lora_adamw_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.multi_lora_adamw_step.restype = ctypes.c_int
+        L.multi_lora_calib_mfma.argtypes = [i32, vp, ctypes.POINTER(ctypes.c_float), vp]
+        L.multi_lora_calib_mfma.restype = ctypes.c_int
+        L.multi_lora_calib_read.argtypes = [vp, ctypes.c_size_t, vp, ctypes.POINTER(ctypes.c_float), vp]
+        L.multi_lora_calib_read.restype = ctypes.c_int
         L.multi_lora_last_error.restype = ctypes.c_char_p
         L.multi_lora_version.restype = ctypes.c_char_p
         _lib = L
@@ -221,3 +226,17 @@ def multi_lora_adamw_step(plan: Plan, A, B, dA, dB, stateA, stateB, hparams: Seq
     _check(lib().multi_lora_adamw_step(plan.handle, _ptr_array(A, n), _ptr_array(B, n), _ptr_array(dA, n),
                                        _ptr_array(dB, n), _ptr_array(stateA, n), _ptr_array(stateB, n), hp,
                                        ctypes.c_void_p(stream)))
+
+
+def multi_lora_calib_mfma(random_data: bool, scratch, stream: int = 0) -> float:
+    """TFLOP/s of the register-only MFMA loop (see include/multi_lora.h)."""
+    out = ctypes.c_float(0.0)
+    _check(lib().multi_lora_calib_mfma(1 if random_data else 0, _addr(scratch), ctypes.byref(out), ctypes.c_void_p(stream)))
+    return float(out.value)
+
+
+def multi_lora_calib_read(buffer, nbytes: int, scratch, stream: int = 0) -> float:
+    """GB/s of a coalesced streaming read of `buffer`."""
+    out = ctypes.c_float(0.0)
+    _check(lib().multi_lora_calib_read(_addr(buffer), nbytes, _addr(scratch), ctypes.byref(out), ctypes.c_void_p(stream)))
+    return float(out.value)
