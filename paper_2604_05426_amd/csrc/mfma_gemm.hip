@@ -13,8 +13,13 @@
 // other's MFMAs), each 128 x 64 = 8 x 4 blocks of 16x16x32 MFMAs with fp32 accumulators (on this chip a
 // GEMM of this size runs into the board power limit, and the 16x16x32 form needs measurably less energy
 // per FLOP than 32x32x16).  Operand tiles go from global memory straight into LDS (no staging registers,
-// no LDS store instructions); two 64 KB stages; the loads of tile t+2 are issued right after the barrier
-// that ends the reads of tile t, so they have a whole tile of MFMAs to land.  LDS tiles are unpadded and
+// no LDS store instructions).  The 160 KB of LDS hold five 32 KB tile buffers: two stages for the row
+// operand (X / dY), which runs one tile ahead, and three slots for the weight operand, which runs two
+// tiles ahead.  The eight direct loads a wavefront owes per tile are issued one at a time between groups
+// of 8 MFMAs: issued back to back after the barrier they fill the memory pipeline's queue and every
+// wavefront of the workgroup sits blocked on load issue, with no MFMA in flight, for ~20 % of the tile.
+// With the weight tile two tiles ahead, each barrier only waits for loads issued at least half a tile
+// earlier.  LDS tiles are unpadded and
 // XOR-swizzled so that both the 1 KB-contiguous direct loads and the fragment reads are conflict free:
 //   X / dY tile and the [col][contraction] weight tile: 256 rows of 128 bytes; the 16-byte chunk c of
 //     row r sits at chunk position c ^ (r & 7);
@@ -33,10 +38,11 @@ constexpr int WM = 2, WN = 4;                 // wavefront grid
 constexpr int NTHR = 64 * WM * WN;            // 512
 constexpr int TM = BM / WM, TN = BN / WN;     // 128 x 64 per wavefront
 constexpr int TILE_BYTES = 32768;             // one operand tile
-constexpr int STAGE_BYTES = 2 * TILE_BYTES;   // X tile + W tile
+constexpr int B_SLOT0 = 2;                    // tile buffers 0, 1: row-operand stages; 2, 3, 4: weight-operand slots
 constexpr int E_LD = TN + 8;                  // epilogue staging row (elements)
 constexpr int EPI_BYTES = WM * WN * TM * E_LD * 2;
-constexpr int LDS_BYTES = EPI_BYTES > 2 * STAGE_BYTES ? EPI_BYTES : 2 * STAGE_BYTES;
+constexpr int LDS_BYTES = 5 * TILE_BYTES;     // all of a CU's LDS
+static_assert(EPI_BYTES <= LDS_BYTES, "epilogue staging must fit the tile buffers");
 static_assert(kGemmTileRows == BM && kGemmTileCols == BN, "plan geometry and kernel tile must agree");
 
 typedef float f32x4v __attribute__((ext_vector_type(4)));
@@ -79,7 +85,7 @@ struct GemmArgs {
     PlanView pv;
 };
 
-// One masked operand pass staged into stage 0 of the tile buffers.  Used for the rank extension
+// One masked operand pass staged into the first row-operand stage and the first weight slot.  Used for the rank extension
 // (rows owned by one adapter, contraction = rank) and for the tail of a contraction that is not a
 // multiple of 64.  All arguments are uniform over the workgroup.
 struct PassDesc {
@@ -94,7 +100,7 @@ struct PassDesc {
 
 __device__ __forceinline__ int nn_swz(int k) { return (k & 3) | (((k >> 3) & 1) << 2); }
 
-// Writes the pass operands into stage 0 in the same swizzled layouts the main loop uses, zero-filled
+// Writes the pass operands into tile buffers 0 and B_SLOT0 in the same swizzled layouts the main loop uses, zero-filled
 // up to a multiple of 32 in the contraction and outside the rows / columns the pass owns.
 template <bool NN>
 __device__ __forceinline__ void stage_pass(unsigned char* lds, const PassDesc& d, int m0, int n0, int ncols, int tid) {
@@ -114,7 +120,7 @@ __device__ __forceinline__ void stage_pass(unsigned char* lds, const PassDesc& d
             *reinterpret_cast<uint4*>(lds + row * 128 + ((cc ^ (row & 7)) << 4)) = v;
         }
     }
-    unsigned char* Bs = lds + TILE_BYTES;
+    unsigned char* Bs = lds + B_SLOT0 * TILE_BYTES;
     if (NN) {
         const int nc = tid & 31;
         const int gcol = n0 + nc * 8;
@@ -174,24 +180,25 @@ __global__ __launch_bounds__(NTHR) void fused_gemm_kernel(GemmArgs g) {
     // ---- fragment reads (k32 = 32-wide half of the 64-wide tile, half = upper / lower 64 rows of the wave tile) ----
     const int a_off0 = (wm * TM + l16) * 128 + ((g4 ^ (l16 & 7)) << 4);
     const int a_off1 = (wm * TM + l16) * 128 + (((4 + g4) ^ (l16 & 7)) << 4);
-    const int bnt_off0 = TILE_BYTES + (wn * TN + l16) * 128 + ((g4 ^ (l16 & 7)) << 4);
-    const int bnt_off1 = TILE_BYTES + (wn * TN + l16) * 128 + (((4 + g4) ^ (l16 & 7)) << 4);
+    const int bnt_off0 = (wn * TN + l16) * 128 + ((g4 ^ (l16 & 7)) << 4);
+    const int bnt_off1 = (wn * TN + l16) * 128 + (((4 + g4) ^ (l16 & 7)) << 4);
     const int vq = ((l16 >> 2) & 3) | ((g4 & 1) << 2);    // nn_swz of the rows this lane reads
-    const int bnn_off = TILE_BYTES + (8 * g4 + (l16 >> 2)) * 512 + (l16 & 3) * 8;
+    const int bnn_off = (8 * g4 + (l16 >> 2)) * 512 + (l16 & 3) * 8;
     bf16x8 fa[2][4], fb[2][4];
     auto rfa = [&](int stage, int k32, int half, int buf) {
-        const unsigned char* base = lds + stage * STAGE_BYTES + (k32 ? a_off1 : a_off0);
+        const unsigned char* base = lds + stage * TILE_BYTES + (k32 ? a_off1 : a_off0);
 #pragma unroll
         for (int a = 0; a < 4; ++a) fa[buf][a] = lds_read_frag(reinterpret_cast<const u16*>(base + (half * 4 + a) * 16 * 128));
     };
-    auto rfb = [&](int stage, int k32, int buf) {
+    auto rfb = [&](int slot, int k32, int buf) {
+        const unsigned char* bbase = lds + (B_SLOT0 + slot) * TILE_BYTES;
 #pragma unroll
         for (int b = 0; b < 4; ++b) {
             if (NN) {
-                const unsigned char* p = lds + stage * STAGE_BYTES + bnn_off + k32 * 32 * 512 + (((wn * 4 + b) ^ vq) << 5);
+                const unsigned char* p = bbase + bnn_off + k32 * 32 * 512 + (((wn * 4 + b) ^ vq) << 5);
                 fb[buf][b] = lds_read_frag_tr(reinterpret_cast<const u16*>(p), reinterpret_cast<const u16*>(p + 4 * 512));
             } else {
-                fb[buf][b] = lds_read_frag(reinterpret_cast<const u16*>(lds + stage * STAGE_BYTES + (k32 ? bnt_off1 : bnt_off0) + b * 16 * 128));
+                fb[buf][b] = lds_read_frag(reinterpret_cast<const u16*>(bbase + (k32 ? bnt_off1 : bnt_off0) + b * 16 * 128));
             }
         }
     };
@@ -202,10 +209,18 @@ __global__ __launch_bounds__(NTHR) void fused_gemm_kernel(GemmArgs g) {
 #pragma unroll
             for (int b = 0; b < 4; ++b) acc[half * 4 + a][b] = mfma16(fb[bbuf][b], fa[abuf][a], acc[half * 4 + a][b]);
     };
-    // ask the scheduler to alternate LDS reads with MFMAs instead of issuing the reads in one burst
+    // two of the four 16-row blocks of one half: 8 MFMAs
+    auto mma8 = [&](int half, int abuf, int bbuf, int alo) {
+#pragma unroll
+        for (int a = alo; a < alo + 2; ++a)
+#pragma unroll
+            for (int b = 0; b < 4; ++b) acc[half * 4 + a][b] = mfma16(fb[bbuf][b], fa[abuf][a], acc[half * 4 + a][b]);
+    };
+    // ask the scheduler to spread nds LDS reads over the 8 MFMAs issued with them instead of one burst
     constexpr int NDSB = NN ? 8 : 4;
     auto interleave = [&](int nds) {
-        for (int i = 0; i < nds; ++i) { MLORA_SGB(0x008, 1); MLORA_SGB(0x100, 1); }
+        if (nds > 8) { for (int i = 0; i < 8; ++i) { MLORA_SGB(0x008, 1); if (2 * i < nds) MLORA_SGB(0x100, 2); } }
+        else { for (int i = 0; i < 8; ++i) { MLORA_SGB(0x008, 1); if (i < nds) MLORA_SGB(0x100, 1); } }
         __builtin_amdgcn_sched_barrier(0);
     };
 
@@ -232,45 +247,71 @@ __global__ __launch_bounds__(NTHR) void fused_gemm_kernel(GemmArgs g) {
         const char* baseA = reinterpret_cast<const char*>(g.Aop + (int64_t)m0 * g.lda);
         const char* baseB = NN ? reinterpret_cast<const char*>(g.Bop) : reinterpret_cast<const char*>(g.Bop + (int64_t)n0 * g.ldb);
         const int64_t astep = (int64_t)BK * 2, bstep = NN ? (int64_t)BK * g.ldb * 2 : (int64_t)BK * 2;
-        auto load_tile = [&](int stage, bool advance) {
-            const unsigned dst = (unsigned)(uintptr_t)lds + stage * STAGE_BYTES + wave * 4096;
-#pragma unroll
-            for (int c = 0; c < 4; ++c) dma16(oa[c], baseA, dst + c * 1024);
-#pragma unroll
-            for (int c = 0; c < 4; ++c) dma16(ob[c], baseB, dst + TILE_BYTES + c * 1024);
-            if (advance) { baseA += astep; baseB += bstep; }
-        };
+        const unsigned ldsw = (unsigned)(uintptr_t)lds + wave * 4096;
+        auto dmaA = [&](int stage, int c) { dma16(oa[c], baseA, ldsw + stage * TILE_BYTES + c * 1024); };
+        auto dmaB = [&](int slot, int c) { dma16(ob[c], baseB, ldsw + (B_SLOT0 + slot) * TILE_BYTES + c * 1024); };
 
-        load_tile(0, nk > 1);
+        // tile 0 of both operands, then the weight tile 1 and the first half of the row tile 1: from here on the
+        // order of this wavefront's loads is ... A(t+1) x4, B(t+2) x4, A(t+2) x4, B(t+3) x4 ...  Past the last tile the
+        // base pointers stop advancing and the loads fetch the last tile again into buffers nobody reads.
+#pragma unroll
+        for (int c = 0; c < 4; ++c) dmaA(0, c);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) dmaB(0, c);
+        if (nk > 1) { baseA += astep; baseB += bstep; }
         wait_all_and_barrier();
-        load_tile(1, nk > 2);            // tile 1 (tile 0 again when there is only one; never read then)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) dmaB(1, c);
+        if (nk > 2) baseB += bstep;
+        dmaA(1, 0); dmaA(1, 1);
         rfa(0, 0, 0, 0); rfb(0, 0, 0);
+        int bs = 0;                      // weight slot of tile kt
         for (int kt = 0; kt < nk - 1; ++kt) {
             const int cur = kt & 1;
+            const int bn = bs == 2 ? 0 : bs + 1, bp = bs == 0 ? 2 : bs - 1;
+            // Since the last barrier row stage cur^1 and weight slot bp are free.  Row tile kt+1 is completed here,
+            // the weight tile kt+2 follows; one load per 8 MFMAs.
             __builtin_amdgcn_sched_barrier(0);
-            rfa(cur, 0, 1, 1);
-            mma(0, 0, 0); interleave(4);
-            rfa(cur, 1, 0, 0); rfb(cur, 1, 1);
-            mma(1, 1, 0); interleave(4 + NDSB);
-            rfa(cur, 1, 1, 1);
-            mma(0, 0, 1); interleave(4);
-            // tile kt+1 has landed in the other stage (this wave's share; the barrier covers the rest) and every
-            // wave has finished reading this stage, so tile kt+2 may overwrite it (the last tile again past the end)
-            wait_all_and_barrier();
-            load_tile(cur, kt + 3 < nk);
-            rfa(cur ^ 1, 0, 0, 0); rfb(cur ^ 1, 0, 0);
-            mma(1, 1, 1); interleave(4 + NDSB);
+            dmaA(cur ^ 1, 2);
+            __builtin_amdgcn_sched_barrier(0);
+            rfa(cur, 0, 1, 1); mma8(0, 0, 0, 0); interleave(4);
+            dmaA(cur ^ 1, 3); baseA += (kt + 2 < nk) ? astep : 0;
+            __builtin_amdgcn_sched_barrier(0);
+            mma8(0, 0, 0, 2); __builtin_amdgcn_sched_barrier(0);
+            dmaB(bp, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            rfa(cur, 1, 0, 0); rfb(bs, 1, 1); mma8(1, 1, 0, 0); interleave(4 + NDSB);
+            dmaB(bp, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            mma8(1, 1, 0, 2); __builtin_amdgcn_sched_barrier(0);
+            dmaB(bp, 2);
+            __builtin_amdgcn_sched_barrier(0);
+            rfa(cur, 1, 1, 1); mma8(0, 0, 1, 0); interleave(4);
+            dmaB(bp, 3); baseB += (kt + 3 < nk) ? bstep : 0;
+            __builtin_amdgcn_sched_barrier(0);
+            mma8(0, 0, 1, 2); __builtin_amdgcn_sched_barrier(0);
+            // Everything but this iteration's four weight loads has landed: row tile kt+1 and weight tile kt+1 are
+            // complete (this wavefront's share; the barrier covers the rest), and every wavefront has finished reading
+            // row stage cur and weight slot bs, which the next loads overwrite.
+            asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            dmaA(cur, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            rfa(cur ^ 1, 0, 0, 0); rfb(bn, 0, 0); mma8(1, 1, 1, 0); interleave(4 + NDSB);
+            dmaA(cur, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            mma8(1, 1, 1, 2); __builtin_amdgcn_sched_barrier(0);
+            bs = bn;
         }
         {
             const int cur = (nk - 1) & 1;
             rfa(cur, 0, 1, 1); mma(0, 0, 0);
-            rfa(cur, 1, 0, 0); rfb(cur, 1, 1); mma(1, 1, 0);
+            rfa(cur, 1, 0, 0); rfb(bs, 1, 1); mma(1, 1, 0);
             rfa(cur, 1, 1, 1); mma(0, 0, 1);
             mma(1, 1, 1);
         }
     }
 
-    // one masked pass: stage into buffer 0, then one or two 32-wide MFMA steps
+    // one masked pass: stage into the first row stage and weight slot, then one or two 32-wide MFMA steps
     auto run_pass = [&](const PassDesc& d) {
         wait_all_and_barrier();          // outstanding direct loads have landed; nobody reads the buffers any more
         stage_pass<NN>(lds, d, m0, n0, g.Ncols, tid);
