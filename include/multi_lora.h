@@ -106,10 +106,12 @@ enum {
  * allocates the small device tables and builds them with a device kernel on `stream`.
  *   out          host, receives the plan
  *   T, k, n      token count (>= 0), input width (>= 1), output width (>= 1)
- *   N            number of adapters, 0..MLORA_MAX_ADAPTERS (0 = plain X W)
+ *   N            number of adapters, 0..MLORA_MAX_ADAPTERS.  With N = 0 all T rows are plain X W rows
+ *                (Y = X W, dX = dY W^T); ranks, scales and seg_offsets are then not read and may be NULL,
+ *                and the A / B / dA / dB pointer arrays of multi_lora_fwd / multi_lora_bwd may be NULL.
  *   ranks        host [N], each in [0, MLORA_MAX_RANK]; rank 0 = rows pass through as X W
  *   scales       host [N], finite
- *   seg_offsets  host [N+1], seg_offsets[0] = 0, non-decreasing, seg_offsets[N] = T
+ *   seg_offsets  host [N+1], seg_offsets[0] = 0, non-decreasing, seg_offsets[N] = T (N >= 1)
  * The only entry point that allocates device memory; freed by multi_lora_plan_destroy.
  */
 int multi_lora_plan_create(mlora_plan** out, int dtype, int64_t T, int64_t k, int64_t n,

@@ -144,7 +144,7 @@ class Plan:
     def __init__(self, dtype: int, T: int, k: int, n: int, ranks, scales, offsets, stream: int = 0):
         self.dtype, self.T, self.k, self.n = dtype, T, k, n
         self.N = len(ranks)
-        self.ranks, self.scales, self.offsets = list(ranks), list(scales), list(offsets)
+        self.ranks, self.scales, self.offsets = list(ranks), list(scales or []), list(offsets or [0])
         self._h = ctypes.c_void_p()
         r, s, o = _meta(self.N, ranks, scales, offsets)
         _check(lib().multi_lora_plan_create(ctypes.byref(self._h), dtype, T, k, n, self.N, r, s, o,

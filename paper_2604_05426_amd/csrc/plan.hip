@@ -188,11 +188,12 @@ extern "C" int multi_lora_validate(int dtype, int64_t T, int64_t k, int64_t n, i
         set_error("N must be in [0, MLORA_MAX_ADAPTERS]");
         return MLORA_ERR_SHAPE;
     }
+    if (N == 0) return MLORA_OK;   // no adapters: every row is a plain X W row; the metadata arrays are not read
     if (!seg_offsets) {
         set_error("seg_offsets is NULL");
         return MLORA_ERR_NULL;
     }
-    if (N > 0 && (!ranks || !scales)) {
+    if (!ranks || !scales) {
         set_error("ranks / scales is NULL");
         return MLORA_ERR_NULL;
     }
@@ -237,9 +238,13 @@ extern "C" int multi_lora_plan_create(mlora_plan** out, int dtype, int64_t T, in
     mlora_plan* p = new mlora_plan();
     p->dtype = dtype;
     p->T = T; p->k = k; p->n = n; p->N = N;
-    p->ranks.assign(ranks, ranks + N);
-    p->scales.assign(scales, scales + N);
-    p->off.assign(seg_offsets, seg_offsets + N + 1);
+    if (N > 0) {
+        p->ranks.assign(ranks, ranks + N);
+        p->scales.assign(scales, scales + N);
+        p->off.assign(seg_offsets, seg_offsets + N + 1);
+    } else {
+        p->off.assign(1, 0);
+    }
     p->soff.resize(N + 1);
     p->wchunk_start.resize(N + 1);
     p->build_stream = (hipStream_t)stream;

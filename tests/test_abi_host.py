@@ -35,6 +35,7 @@ V = ml.multi_lora_validate
 def test_validate_accepts_legal_inputs():
     assert V(ml.BF16, 10, 8, 8, 2, [4, 0], [1.0, 2.0], [0, 4, 10]) == 0
     assert V(ml.F32, 0, 1, 1, 0, [], [], [0]) == 0            # no tokens, no adapters
+    assert V(ml.BF16, 300, 8, 8, 0, None, None, None) == 0    # no adapters: all rows plain X W, metadata not read
     assert V(ml.F32, 5, 3, 7, 3, [1, 128, 2], [1, 1, 1], [0, 0, 5, 5]) == 0   # empty segments
 
 

@@ -9,7 +9,7 @@ from oracle import multilora_oracle as orc
 from oracle import tile_tables as tt
 from paper_2604_05426_amd import binding as ml
 from paper_2604_05426_amd import workloads as wl
-from paper_2604_05426_amd.harness import DeviceLayer, to_host
+from paper_2604_05426_amd.harness import DeviceLayer, to_device, to_host
 from util import rel_fro, sample_cols, sample_rows
 
 pytestmark = pytest.mark.gpu
@@ -193,6 +193,26 @@ def test_no_adapters_and_no_tokens(dtype):
     w = wl.make_workload("emptyseg", dtype, 128, 64, [8, 16], [0, 300], [1.0, 2.0], seed=52)
     dl, _, _ = check_full(w)                                                 # adapter 0 has a rank but no tokens
     assert torch.all(dl.dA[0] == 0) and torch.all(dl.dB[0] == 0)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_no_adapters_with_tokens(dtype):
+    """N = 0 with T > 0: every row is a plain X W row; the metadata and pointer arrays may be NULL."""
+    T, k, n = 300, 128, 192
+    ref = wl.make_workload("plain", dtype, k, n, [0], [T], [1.0], seed=54)     # same numbers through a rank-0 adapter
+    fw = orc.forward(ref.X, ref.W, ref.A, ref.B, ref.scales, ref.offsets)
+    bw = orc.backward(ref.dY, ref.X, ref.W, ref.A, ref.B, ref.scales, ref.offsets)
+    dev = torch.device("cuda:0")
+    X, W, dY = (to_device(a, dtype, dev) for a in (ref.X, ref.W, ref.dY))
+    Y = torch.full((T, n), float("nan"), dtype=X.dtype, device=dev)
+    dX = torch.full((T, k), float("nan"), dtype=X.dtype, device=dev)
+    plan = ml.Plan(ml.BF16 if dtype == "bf16" else ml.F32, T, k, n, [], None, None)
+    assert plan.workspace_bytes() == 0
+    ml.multi_lora_fwd(plan, X, W, None, None, Y, None, None)
+    ml.multi_lora_bwd(plan, dY, None, W, None, None, None, dX, None, None, None)
+    torch.cuda.synchronize()
+    assert rel_fro(to_host(Y), fw.Y) <= TOL[dtype] and rel_fro(to_host(dX), bw.dX) <= TOL[dtype]
+    plan.destroy()
 
 
 def test_single_token_segments():
