@@ -33,6 +33,26 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
+// v_mfma_f32_16x16x32_bf16:  C[16x16] += A[16x32] * B[32x16].
+// Lane l supplies A[row l%16][8*(l/16) .. +7] and B[8*(l/16) .. +7][col l%16];
+// it receives C[4*(l/16) + i][l%16] in c[i], i = 0..3.
+__device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+
+// two fp32 -> packed bf16 with the hardware conversion (round to nearest even)
+typedef __bf16 bf16x2v __attribute__((ext_vector_type(2)));
+typedef float f32x2v __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack2hw(float lo, float hi) {
+    const f32x2v f = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2v));
+}
+
+// Swizzle key of contraction row k of a [contraction][column] LDS tile that is read with the transposing load
+// for 16x16x32 MFMA operands: the eight rows one such read touches per half-wavefront (k, k+1, k+2, k+3 and the
+// same plus 8) get eight different keys; rows k and k+4 share one (they belong to different read instructions).
+__device__ __forceinline__ int nn_swz(int k) { return (k & 3) | (((k >> 3) & 1) << 2); }
+
 __device__ __forceinline__ bf16x8 lds_read_frag(const u16* p) {
     return *reinterpret_cast<const bf16x8*>(p);
 }

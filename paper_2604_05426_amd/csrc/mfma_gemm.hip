@@ -45,14 +45,7 @@ constexpr int LDS_BYTES = 5 * TILE_BYTES;     // all of a CU's LDS
 static_assert(EPI_BYTES <= LDS_BYTES, "epilogue staging must fit the tile buffers");
 static_assert(kGemmTileRows == BM && kGemmTileCols == BN, "plan geometry and kernel tile must agree");
 
-typedef float f32x4v __attribute__((ext_vector_type(4)));
-
-// v_mfma_f32_16x16x32_bf16:  C[16x16] += A[16x32] * B[32x16].
-// Lane l supplies A[row l%16][8*(l/16) .. +7] and B[8*(l/16) .. +7][col l%16];
-// it receives C[4*(l/16) + i][l%16] in c[i], i = 0..3.
-__device__ __forceinline__ f32x4v mfma16(bf16x8 a, bf16x8 b, f32x4v c) {
-    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
-}
+typedef f32x4 f32x4v;
 
 // Direct global -> LDS load of 16 bytes per lane: lane i's data lands at LDS byte address lds_base + 16 i
 // (lds_base is wavefront-uniform).  Issued through inline assembly so that the compiler's wait-count
@@ -61,13 +54,6 @@ __device__ __forceinline__ f32x4v mfma16(bf16x8 a, bf16x8 b, f32x4v c) {
 // The global address is a wavefront-uniform base pointer plus a 32-bit per-lane byte offset.
 __device__ __forceinline__ void dma16(unsigned voff, const void* sbase, unsigned lds_base) {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_base) : "memory", "m0");
-}
-// two fp32 -> packed bf16 with the hardware conversion (round to nearest even)
-typedef __bf16 bf16x2v __attribute__((ext_vector_type(2)));
-typedef float f32x2v __attribute__((ext_vector_type(2)));
-__device__ __forceinline__ uint32_t pack2hw(float lo, float hi) {
-    const f32x2v f = {lo, hi};
-    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2v));
 }
 // all of this wavefront's direct loads and LDS accesses have completed; then the workgroup barrier
 __device__ __forceinline__ void wait_all_and_barrier() {
@@ -97,8 +83,6 @@ struct PassDesc {
     bool b_vec;
     int kc;                            // valid contraction length, 1..64
 };
-
-__device__ __forceinline__ int nn_swz(int k) { return (k & 3) | (((k >> 3) & 1) << 2); }
 
 // Writes the pass operands into tile buffers 0 and B_SLOT0 in the same swizzled layouts the main loop uses, zero-filled
 // up to a multiple of 32 in the contraction and outside the rows / columns the pass owns.

@@ -406,19 +406,21 @@ __global__ void wgrad_zero_empty_kernel(PlanView pv) {
 }
 
 // =========================================================================================
-// Expand-add, the decoupled form (paper Sec. 5.1 / App. A.1 "fused base-output addition"):
-//   FWD:  Y_i  += s_i S_i B_i          (Y holds the base output on entry)
-//   !FWD: dX_i += dS_i A_i^T
-// Serves MLORA_FLAG_LORA_ONLY.  Memory bound (one read and one write of the output), so it
-// is built as a stream: work item = (64-row block of one adapter, 256 output columns), four
-// wavefronts with 64 columns each, no workgroup barrier.  Each wavefront issues the loads of
-// its old output tile first, multiplies from register-resident S fragments (B_i goes through
-// a small private LDS tile for the transposing read; A_i^T fragments come straight from
-// memory), transposes its result through private LDS and adds into the old tile with full
-// 128-byte row segments.
+// Expand-add (MLORA_FLAG_LORA_ONLY; the paper's decoupled "fused GEMM-add", Sec. 5.1 / App. A.1):
+//   fwd  Y_i  += s_i S_i B_i        bwd  dX_i += dS_i A_i^T        in place, one rounding.
+// A pure read-modify-write stream of the output with a small contraction on top.  Work item = (64-row block of
+// one adapter, 128 columns); 4 wavefronts (2 x 2), each 32 rows x 64 columns = 2 x 4 blocks of 16x16x32 MFMAs.
+// The old output tile is not added after the fact: it is loaded in 16-byte row chunks, which is exactly the MFMA
+// operand layout of a [row][32 columns] fragment, and multiplied by a constant identity operand into the fp32
+// accumulators (bf16 x 1.0 is exact), so the accumulators start as the old tile and the rank steps add on top.
+// That leaves no separate fp32 add, no second register copy of the tile and a bf16-only transpose in the
+// epilogue (operands are swapped so that a lane holds 4 consecutive columns, as in the fused GEMM).
+// fwd: B_i is [r][n] (contraction index outermost), so the work group stages its [r][128] tile in LDS once
+// (256-byte rows, 16-byte chunk c of row k at c ^ (nn_swz(k) << 1)) and reads it with the transposing load;
+// bwd: A_i is [k][r], contraction contiguous: operand fragments come straight from memory.
 // =========================================================================================
-constexpr int XC = 256;               // output columns per work item
-constexpr int X_BLD = 64 + 32;        // FWD B_i tile row: 192-byte rows for the transposing reads
+constexpr int XC = 128;               // output columns per work item
+constexpr int XE_LD = 64 + 8;         // epilogue staging row of one wavefront (elements)
 
 struct ExpandArgs {
     u16* C; int64_t ldc;     // Y [T,n] or dX [T,k]
@@ -428,151 +430,143 @@ struct ExpandArgs {
     PlanView pv;
 };
 
-// MAXKS: 16-wide rank steps the kernel is built for (4: every rank <= 64, 8: ranks up to 128).
+// MAXKS: 32-wide rank steps the kernel is built for (2: every rank <= 64, 4: ranks up to 128).
 // All loads of a work item (old output tile, S fragments, B_i / A_i^T operands) are issued before the
-// first MFMA, so a wavefront pays the memory latency once.
+// first MFMA, so a wavefront pays the memory latency once; many small work items per CU overlap each other.
 template <bool FWD, int MAXKS>
 __global__ __launch_bounds__(256) void expand_add_kernel(ExpandArgs g) {
-    constexpr int X_WAVE = 4 * 16 * X_BLD;       // private LDS per wavefront (elements): 64 rank rows of the B_i tile; >= 64 x 36 floats
-    static_assert(X_WAVE * 2 >= 64 * 36 * 4, "fp32 epilogue staging fits in the private region");
-    __shared__ __attribute__((aligned(16))) u16 lds[4 * X_WAVE];
+    constexpr int BT_BYTES = FWD ? MAXKS * 32 * 256 : 0;        // staged B_i tile
+    constexpr int EP_WAVE = 32 * XE_LD * 2;                      // bytes of epilogue staging per wavefront
+    __shared__ __attribute__((aligned(16))) unsigned char lds[BT_BYTES + 4 * EP_WAVE];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int lm = lane & 31, h = lane >> 5, gq = lane >> 4, j = lane & 15;
+    const int wr = wave >> 1, wc = wave & 1;
+    const int l16 = lane & 15, g4 = lane >> 4;
     // row-block-major: consecutive workgroups cover adjacent column tiles of the same 64 rows
     const int bsel = blockIdx.x / g.col_tiles;
     const Entry4 e = g.pv.row_blocks[g.list ? g.list[bsel] : bsel];
     const int ct = blockIdx.x % g.col_tiles;
     const int i = e.a, row0 = e.c, rows = e.d;
     const int r = g.pv.rank[i];
-    const int ksteps = (r + 15) / 16;
+    const int ksteps = (r + 31) / 32;
     const int64_t so = g.pv.soff[i];
     const int seg0 = g.pv.off[i];
     const float s = FWD ? g.pv.scale[i] : 1.0f;
     const u16* F = (const u16*)(FWD ? g.pv.ptrs[i].B : g.pv.ptrs[i].A);
-    const int col0 = ct * XC + wave * 64;
-    u16* Ws = lds + wave * X_WAVE;
-    if (col0 >= g.Ncols) return;   // whole wavefront beyond the edge (no workgroup barrier is used below)
+    const int colw = ct * XC + wc * 64;          // first column of this wavefront
 
-    // 1. old output tile: 64 rows x 64 columns per wavefront, 8 chunks per lane
-    uint4 old[8];
+    // 1. old output tile as MFMA operand fragments: [16 rows][32 columns], lane = (row l16, 8 columns at 8 g4)
+    uint4 old[2][2];
 #pragma unroll
-    for (int it = 0; it < 8; ++it) {
-        const int rr = it * 8 + (lane >> 3), c = lane & 7;
-        const int col = col0 + c * 8;
-        old[it] = (rr < rows && col < g.Ncols)
-                      ? *reinterpret_cast<const uint4*>(g.C + (int64_t)(row0 + rr) * g.ldc + col) : zero4();
-    }
-    // 2. operands for every rank step
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int kg = 0; kg < 2; ++kg) {
+            const int row = wr * 32 + rb * 16 + l16, col = colw + kg * 32 + g4 * 8;
+            old[rb][kg] = (row < rows && col < g.Ncols)
+                              ? *reinterpret_cast<const uint4*>(g.C + (int64_t)(row0 + row) * g.ldc + col) : zero4();
+        }
+    // 2. S / dS fragments: [16 rows][32 ranks]
     const bool e_vec = ((r & 7) == 0) && ((so & 7) == 0);
-    const bool f_vec = FWD ? true : ((r & 7) == 0);
-    uint4 av[2][MAXKS], bv[2][MAXKS];
+    uint4 sv[2][MAXKS];
+#pragma unroll
+    for (int ks = 0; ks < MAXKS; ++ks)
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) {
+            const int row = wr * 32 + rb * 16 + l16, rho = ks * 32 + g4 * 8;
+            sv[rb][ks] = zero4();
+            if (ks < ksteps && row < rows && rho < r)
+                sv[rb][ks] = load_chunk(g.E + so + (int64_t)(row0 + row - seg0) * r + rho, min(8, r - rho), e_vec);
+        }
+    // 3. the adapter matrix: fragments [16 columns][32 ranks], lane = (column l16, 8 ranks at 8 g4)
+    uint4 fv[4][MAXKS];
+    if (FWD) {
+        // the work group's [32 ksteps][128] piece of B_i -> LDS (each thread 2 * MAXKS chunks), then transposing reads
+        uint4 st[2 * MAXKS];
+#pragma unroll
+        for (int jj = 0; jj < 2 * MAXKS; ++jj) {
+            const int idx = tid + 256 * jj, kr = idx >> 4, c = idx & 15;
+            const int col = ct * XC + c * 8;
+            st[jj] = (kr < r && col < g.Ncols) ? *reinterpret_cast<const uint4*>(F + (int64_t)kr * g.Ncols + col) : zero4();
+        }
+#pragma unroll
+        for (int jj = 0; jj < 2 * MAXKS; ++jj) {
+            const int idx = tid + 256 * jj, kr = idx >> 4, c = idx & 15;
+            if (kr < ksteps * 32) *reinterpret_cast<uint4*>(lds + kr * 256 + ((c ^ (nn_swz(kr) << 1)) << 4)) = st[jj];
+        }
+        __syncthreads();
+        const int vq = ((l16 >> 2) & 3) | ((g4 & 1) << 2);   // nn_swz of the rows this lane reads
+#pragma unroll
+        for (int ks = 0; ks < MAXKS; ++ks)
+#pragma unroll
+            for (int cb = 0; cb < 4; ++cb) {
+                fv[cb][ks] = zero4();
+                if (ks < ksteps) {
+                    const unsigned char* p = lds + (ks * 32 + 8 * g4 + (l16 >> 2)) * 256 + (((wc * 4 + cb) ^ vq) << 5) + (l16 & 3) * 8;
+                    fv[cb][ks] = __builtin_bit_cast(uint4, lds_read_frag_tr(reinterpret_cast<const u16*>(p),
+                                                                            reinterpret_cast<const u16*>(p + 4 * 256)));
+                }
+            }
+    } else {
+        const bool f_vec = (r & 7) == 0;
+#pragma unroll
+        for (int ks = 0; ks < MAXKS; ++ks)
+#pragma unroll
+            for (int cb = 0; cb < 4; ++cb) {
+                const int col = colw + cb * 16 + l16, rho = ks * 32 + g4 * 8;
+                fv[cb][ks] = zero4();
+                if (ks < ksteps && col < g.Ncols && rho < r)
+                    fv[cb][ks] = load_chunk(F + (int64_t)col * r + rho, min(8, r - rho), f_vec);
+            }
+    }
+
+    // accumulators start as the old tile: identity operand I_j[m][k] = (k == 16 j + m), j = column block parity
+    f32x4 acc[2][4];
+    {
+        uint4 idn[2];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const uint32_t one = (g4 == 2 * j + (l16 >> 3)) ? (0x3f80u << (16 * (l16 & 1))) : 0u;
+            const int w = (l16 & 7) >> 1;
+            idn[j] = make_uint4(w == 0 ? one : 0u, w == 1 ? one : 0u, w == 2 ? one : 0u, w == 3 ? one : 0u);
+        }
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int cb = 0; cb < 4; ++cb) {
+                const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+                acc[rb][cb] = mfma16(__builtin_bit_cast(bf16x8, idn[cb & 1]), __builtin_bit_cast(bf16x8, old[rb][cb >> 1]), z);
+            }
+    }
 #pragma unroll
     for (int ks = 0; ks < MAXKS; ++ks) {
-        const int rho = ks * 16 + h * 8;
+        if (ks < ksteps) {
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb) {
-            const int rr = mb * 32 + lm;
-            av[mb][ks] = zero4();
-            if (ks < ksteps && rr < rows && rho < r)
-                av[mb][ks] = load_chunk(g.E + so + (int64_t)(row0 + rr - seg0) * r + rho, min(8, r - rho), e_vec);
-        }
-        if (FWD) {   // B_i rows ks*16 .. ks*16+15, this wavefront's 64 columns: 2 chunks per lane
+            for (int rb = 0; rb < 2; ++rb) {
+                const bf16x8 a = __builtin_bit_cast(bf16x8, s != 1.0f ? scale_chunk(sv[rb][ks], s) : sv[rb][ks]);
 #pragma unroll
-            for (int jj = 0; jj < 2; ++jj) {
-                const int kr = ks * 16 + (lane >> 3) + 8 * jj, c = lane & 7;
-                const int col = col0 + c * 8;
-                bv[jj][ks] = zero4();
-                if (ks < ksteps && kr < r && col < g.Ncols)
-                    bv[jj][ks] = *reinterpret_cast<const uint4*>(F + (int64_t)kr * g.Ncols + col);
-            }
-        } else {     // A_i rows = output columns, contraction contiguous: MFMA operand layout straight from memory
-#pragma unroll
-            for (int nb = 0; nb < 2; ++nb) {
-                const int col = col0 + nb * 32 + lm;
-                bv[nb][ks] = zero4();
-                if (ks < ksteps && col < g.Ncols && rho < r)
-                    bv[nb][ks] = load_chunk(F + (int64_t)col * r + rho, min(8, r - rho), f_vec);
-            }
-        }
-    }
-    f32x16 acc[2][2];
-#pragma unroll
-    for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-        for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-            for (int q = 0; q < 16; ++q) acc[mb][nb][q] = 0.f;
-    // the private B_i tile holds 64 rank rows at a time (LDS operations of one wavefront execute in order)
-#pragma unroll
-    for (int half = 0; half < MAXKS / 4; ++half) {
-        if (FWD) {
-#pragma unroll
-            for (int k4 = 0; k4 < 4; ++k4)
-#pragma unroll
-                for (int jj = 0; jj < 2; ++jj) {
-                    const int ks = half * 4 + k4;
-                    const int kr = k4 * 16 + (lane >> 3) + 8 * jj, c = lane & 7;
-                    if (ks < ksteps) *reinterpret_cast<uint4*>(Ws + kr * X_BLD + c * 8) = bv[jj][ks];
-                }
-        }
-#pragma unroll
-        for (int k4 = 0; k4 < 4; ++k4) {
-            const int ks = half * 4 + k4;
-            if (ks < ksteps) {
-                bf16x8 a[2], b[2];
-#pragma unroll
-                for (int mb = 0; mb < 2; ++mb)
-                    a[mb] = __builtin_bit_cast(bf16x8, s != 1.0f ? scale_chunk(av[mb][ks], s) : av[mb][ks]);
-#pragma unroll
-                for (int nb = 0; nb < 2; ++nb) {
-                    if (FWD) {
-                        const u16* p = Ws + (k4 * 16 + 8 * (gq >> 1) + (j >> 2)) * X_BLD + nb * 32 + 16 * (gq & 1) + 4 * (j & 3);
-                        b[nb] = lds_read_frag_tr(p, p + 4 * X_BLD);
-                    } else {
-                        b[nb] = __builtin_bit_cast(bf16x8, bv[nb][ks]);
-                    }
-                }
-#pragma unroll
-                for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-                    for (int nb = 0; nb < 2; ++nb) acc[mb][nb] = mfma32(b[nb], a[mb], acc[mb][nb]);   // transposed block
+                for (int cb = 0; cb < 4; ++cb)
+                    acc[rb][cb] = mfma16(__builtin_bit_cast(bf16x8, fv[cb][ks]), a, acc[rb][cb]);   // transposed block
             }
         }
     }
 
-    // 3. transpose through private LDS, add the old tile, one rounding, store
-    // fp32 staging: [64 rows][36 floats] per 32-column half, two passes
-    float* Fs = reinterpret_cast<float*>(Ws);   // X_WAVE * 2 bytes = 9216 B = 64 rows * 36 floats
-    constexpr int F_LD = 36;
+    // epilogue: one rounding, transpose through this wavefront's private LDS, 128-byte row segments
+    u16* Es = reinterpret_cast<u16*>(lds + BT_BYTES + wave * EP_WAVE);
 #pragma unroll
-    for (int nb = 0; nb < 2; ++nb) {
+    for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const float4 v = make_float4(acc[mb][nb][4 * q + 0], acc[mb][nb][4 * q + 1], acc[mb][nb][4 * q + 2],
-                                             acc[mb][nb][4 * q + 3]);
-                *reinterpret_cast<float4*>(Fs + (mb * 32 + lm) * F_LD + q * 8 + h * 4) = v;
-            }
-        // this half covers columns col0 + nb*32 .. +31 = chunks c = nb*4 .. nb*4+3 of every row
-#pragma unroll
-        for (int it = 0; it < 8; ++it) {
-            const int rr = it * 8 + (lane >> 3), c = lane & 7;
-            if ((c >> 2) != nb) continue;
-            const int col = col0 + c * 8;
-            if (rr >= rows || col >= g.Ncols) continue;
-            const float* src = Fs + rr * F_LD + (c & 3) * 8;
-            const float4 lo = *reinterpret_cast<const float4*>(src);
-            const float4 hi = *reinterpret_cast<const float4*>(src + 4);
-            const uint32_t ov[4] = {old[it].x, old[it].y, old[it].z, old[it].w};
-            const float nv[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-            uint32_t res[4];
-#pragma unroll
-            for (int p2 = 0; p2 < 4; ++p2)
-                res[p2] = pack2(nv[2 * p2] + __uint_as_float(ov[p2] << 16),
-                                nv[2 * p2 + 1] + __uint_as_float(ov[p2] & 0xffff0000u));
-            *reinterpret_cast<uint4*>(g.C + (int64_t)(row0 + rr) * g.ldc + col) = make_uint4(res[0], res[1], res[2], res[3]);
+        for (int cb = 0; cb < 4; ++cb) {
+            uint2 v;
+            v.x = pack2hw(acc[rb][cb][0], acc[rb][cb][1]);
+            v.y = pack2hw(acc[rb][cb][2], acc[rb][cb][3]);
+            *reinterpret_cast<uint2*>(Es + (rb * 16 + l16) * XE_LD + cb * 16 + g4 * 4) = v;
         }
+    __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): the same wavefront reads back what it wrote
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+        const int rr = it * 8 + (lane >> 3), c = lane & 7;
+        const int row = wr * 32 + rr, col = colw + c * 8;
+        if (row >= rows || col >= g.Ncols) continue;
+        *reinterpret_cast<uint4*>(g.C + (int64_t)(row0 + row) * g.ldc + col) = *reinterpret_cast<const uint4*>(Es + rr * XE_LD + c * 8);
     }
 }
 
@@ -593,10 +587,10 @@ static int launch_expand(mlora_plan* p, bool fwd, void* C, const void* E, hipStr
         if (nblocks <= 0) return;
         a.list = list;
         const dim3 grid((unsigned)((int64_t)nblocks * a.col_tiles));
-        if (fwd && narrow)      hipLaunchKernelGGL((expand_add_kernel<true, 4>), grid, dim3(256), 0, st, a);
-        else if (fwd)           hipLaunchKernelGGL((expand_add_kernel<true, 8>), grid, dim3(256), 0, st, a);
-        else if (narrow)        hipLaunchKernelGGL((expand_add_kernel<false, 4>), grid, dim3(256), 0, st, a);
-        else                    hipLaunchKernelGGL((expand_add_kernel<false, 8>), grid, dim3(256), 0, st, a);
+        if (fwd && narrow)      hipLaunchKernelGGL((expand_add_kernel<true, 2>), grid, dim3(256), 0, st, a);
+        else if (fwd)           hipLaunchKernelGGL((expand_add_kernel<true, 4>), grid, dim3(256), 0, st, a);
+        else if (narrow)        hipLaunchKernelGGL((expand_add_kernel<false, 2>), grid, dim3(256), 0, st, a);
+        else                    hipLaunchKernelGGL((expand_add_kernel<false, 4>), grid, dim3(256), 0, st, a);
     };
     if (p->n_blocks_wide == 0) {
         go(true, p->n_row_blocks, nullptr);
