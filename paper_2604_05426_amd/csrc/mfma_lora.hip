@@ -239,12 +239,16 @@ static void launch_shrink(mlora_plan* p, ShrinkArgs a, hipStream_t st) {
 // have the token index as the row index in memory, so both are read with transposing loads.
 // A chunk that covers its whole segment stores the result directly; otherwise fp32 partials go
 // to the workspace and a second kernel adds them in chunk order (no atomics, deterministic).
+// The kernel is a stream of X / dY, and what it sustains depends on the bytes a CU keeps in flight, i.e. on how
+// many workgroups fit a CU: it is built per rank class MAXNB (32-wide rank blocks: 1, 2 or 4, chosen per plan from
+// the largest rank), which sizes the accumulators, the prefetch registers and the S / dS tile.  LDS tiles are
+// unpadded and XOR-swizzled in 64-byte units so that the transposing reads (4 token rows x 64 bytes per half
+// wavefront) are conflict free: the panel tile [64 tokens][128] and a 128-wide S tile keep unit u of token row t at
+// u ^ (t & 3), a 64-wide S tile at u ^ ((t >> 1) & 1), a 32-wide one needs none.  Two stages: 40 / 48 / 64 KB.
 // =========================================================================================
 constexpr int WP = kWgradPanelCols;   // panel columns (128)
 constexpr int WT = 64;           // tokens per step
-constexpr int W_LD = 128 + 32;   // both tiles [64 tokens][160]
-constexpr int W_TILE = WT * W_LD;
-constexpr int W_STAGE = 2 * W_TILE;
+constexpr int WX_TILE = WT * 128;     // panel tile (elements)
 
 struct WgradArgs {
     const u16* X; const u16* dY; const u16* S; const u16* dS;
@@ -255,8 +259,19 @@ struct WgradArgs {
     int32_t accumulate;        // dA_i, dB_i += result (MLORA_FLAG_ACCUM_GRADS)
 };
 
+template <int MAXNB>
 __global__ __launch_bounds__(256) void wgrad_kernel(WgradArgs g) {
+    constexpr int SW = MAXNB * 32;                 // S / dS tile width (elements)
+    constexpr int CPRS = SW / 8;                   // 16-byte chunks per S tile row
+    constexpr int W_STAGE = WX_TILE + WT * SW;     // elements per stage
     __shared__ __attribute__((aligned(16))) u16 lds[2 * W_STAGE];
+    // byte offset of element column c (multiple of 4) of token row t
+    auto x_off = [](int t, int c) { return t * 256 + ((((c >> 5) ^ (t & 3)) << 6) | ((c & 31) << 1)); };
+    auto s_off = [](int t, int c) {
+        const int u = c >> 5;
+        const int us = MAXNB == 4 ? (u ^ (t & 3)) : MAXNB == 2 ? (u ^ ((t >> 1) & 1)) : u;
+        return t * (SW * 2) + ((us << 6) | ((c & 31) << 1));
+    };
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int panels = g.panels_k + g.panels_n;
     const int ce = blockIdx.x / panels;
@@ -276,53 +291,60 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradArgs g) {
     const int col0 = panel * WP;
     const bool s_vec = ((r & 7) == 0) && ((so & 7) == 0);
 
-    f32x16 acc[4];
+    f32x16 acc[MAXNB];
 #pragma unroll
-    for (int nb = 0; nb < 4; ++nb)
+    for (int nb = 0; nb < MAXNB; ++nb)
 #pragma unroll
         for (int q = 0; q < 16; ++q) acc[nb][q] = 0.f;
 
     const int nt = (rows + WT - 1) / WT;
-    uint4 ra[2][4], rb[2][4];   // two register sets: tiles of even / odd index, two steps of loads in flight
+    uint4 ra[2][4], rb[2][MAXNB];   // two register sets: tiles of even / odd index, two steps of loads in flight
     auto gload = [&](int tt, int set) {
         const int t0 = tt * WT;
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {
             const int trow = (tid >> 4) + 16 * jj, cc = tid & 15;
             const int col = col0 + cc * 8;
-            const bool ok = (t0 + trow < rows);
-            ra[set][jj] = (ok && col < width)
+            ra[set][jj] = (t0 + trow < rows && col < width)
                               ? *reinterpret_cast<const uint4*>(big + (int64_t)(row0 + t0 + trow) * width + col) : zero4();
+        }
+#pragma unroll
+        for (int jj = 0; jj < MAXNB; ++jj) {
+            const int idx = tid + 256 * jj, trow = idx / CPRS, cc = idx % CPRS;
             rb[set][jj] = zero4();
-            if (ok && cc * 8 < rpad)
+            if (t0 + trow < rows && cc * 8 < r)
                 rb[set][jj] = load_chunk(small + (int64_t)(t0 + trow) * r + cc * 8, min(8, r - cc * 8), s_vec);
         }
     };
     auto lstore = [&](int stage, int set) {
-        u16* Xs = lds + stage * W_STAGE;
-        u16* Ss = Xs + W_TILE;
+        unsigned char* Xs = reinterpret_cast<unsigned char*>(lds + stage * W_STAGE);
+        unsigned char* Ss = Xs + WX_TILE * 2;
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {
             const int trow = (tid >> 4) + 16 * jj, cc = tid & 15;
-            *reinterpret_cast<uint4*>(Xs + trow * W_LD + cc * 8) = ra[set][jj];
-            *reinterpret_cast<uint4*>(Ss + trow * W_LD + cc * 8) = rb[set][jj];
+            *reinterpret_cast<uint4*>(Xs + x_off(trow, cc * 8)) = ra[set][jj];
+        }
+#pragma unroll
+        for (int jj = 0; jj < MAXNB; ++jj) {
+            const int idx = tid + 256 * jj, trow = idx / CPRS, cc = idx % CPRS;
+            *reinterpret_cast<uint4*>(Ss + s_off(trow, cc * 8)) = rb[set][jj];
         }
     };
     const int lm = lane & 31, h = lane >> 5, gq = lane >> 4, j = lane & 15;
     auto compute = [&](int stage) {
-        const u16* Xs = lds + stage * W_STAGE;
-        const u16* Ss = Xs + W_TILE;
+        const unsigned char* Xs = reinterpret_cast<const unsigned char*>(lds + stage * W_STAGE);
+        const unsigned char* Ss = Xs + WX_TILE * 2;
 #pragma unroll
         for (int ks = 0; ks < WT / 16; ++ks) {
-            const int trow = ks * 16 + 8 * (gq >> 1) + (j >> 2);
+            const int trow = ks * 16 + 8 * (gq >> 1) + (j >> 2);    // token rows trow and trow + 4 share their swizzle keys
             const int coff = 16 * (gq & 1) + 4 * (j & 3);
-            const u16* pa = Xs + trow * W_LD + wave * 32 + coff;
-            const bf16x8 a = lds_read_frag_tr(pa, pa + 4 * W_LD);
+            const unsigned char* pa = Xs + x_off(trow, wave * 32 + coff);
+            const bf16x8 a = lds_read_frag_tr(reinterpret_cast<const u16*>(pa), reinterpret_cast<const u16*>(pa + 4 * 256));
 #pragma unroll
-            for (int nb = 0; nb < 4; ++nb) {
+            for (int nb = 0; nb < MAXNB; ++nb) {
                 if (nb < nblk) {
-                    const u16* pb = Ss + trow * W_LD + nb * 32 + coff;
-                    const bf16x8 b = lds_read_frag_tr(pb, pb + 4 * W_LD);
+                    const unsigned char* pb = Ss + s_off(trow, nb * 32 + coff);
+                    const bf16x8 b = lds_read_frag_tr(reinterpret_cast<const u16*>(pb), reinterpret_cast<const u16*>(pb + 4 * SW * 2));
                     acc[nb] = mfma32(a, b, acc[nb]);
                 }
             }
@@ -355,7 +377,7 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradArgs g) {
     const float s = isA ? 1.0f : g.pv.scale[i];
     const int64_t kk = g.pv.k, nn = g.pv.n;
 #pragma unroll
-    for (int nb = 0; nb < 4; ++nb) {
+    for (int nb = 0; nb < MAXNB; ++nb) {
         if (nb >= nblk) continue;
         const int rho = nb * 32 + lm;
         if (rho >= r) continue;
@@ -640,7 +662,9 @@ int mfma_backward(mlora_plan* p, const void* dY, const void* X, const void* W, c
             const int64_t grid = (int64_t)p->n_wgrad_chunks * (w.panels_k + w.panels_n);
             {
                 ProfScope prof(p, MLORA_K_WGRAD, st);
-                hipLaunchKernelGGL(wgrad_kernel, dim3((unsigned)grid), dim3(256), 0, st, w);
+                if (p->max_rank <= 32)      hipLaunchKernelGGL(wgrad_kernel<1>, dim3((unsigned)grid), dim3(256), 0, st, w);
+                else if (p->max_rank <= 64) hipLaunchKernelGGL(wgrad_kernel<2>, dim3((unsigned)grid), dim3(256), 0, st, w);
+                else                        hipLaunchKernelGGL(wgrad_kernel<4>, dim3((unsigned)grid), dim3(256), 0, st, w);
             }
             if (p->max_chunks_per_adapter > 1) {
                 const int64_t per = (p->k + p->n) * (int64_t)p->max_rank;
