@@ -118,6 +118,16 @@ int multi_lora_plan_create(mlora_plan** out, int dtype, int64_t T, int64_t k, in
                            int32_t N, const int32_t* ranks, const float* scales,
                            const int64_t* seg_offsets, void* stream);
 
+/*
+ * A plan for another layer shape (k, n) over the segmentation of `base` (same T, adapters, ranks, scales and
+ * offsets): App. A.1 builds the schedule table once per step and every layer of the step uses it.  The new plan
+ * uses the device tables of `base` in place (row blocks, row tiles, offsets, ranks, scales; the weight-gradient
+ * item table too when both shapes chunk the tokens alike) and builds only what depends on the layer: its pointer
+ * table and workspace layout.  `stream` must be the stream `base` was created on.  The two plans are independent
+ * afterwards: either may be destroyed first, and each is used by one stream at a time as usual.
+ */
+int multi_lora_plan_create_like(mlora_plan** out, const mlora_plan* base, int64_t k, int64_t n, void* stream);
+
 /* Frees the plan's device tables (synchronises with nothing: destroy a plan only after
  * the work that uses it has finished).  NULL is accepted. */
 int multi_lora_plan_destroy(mlora_plan* plan);

@@ -26,7 +26,7 @@ STATUS_NAMES = {0: "MLORA_OK", -1: "MLORA_ERR_NULL", -2: "MLORA_ERR_SHAPE", -3: 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmultilora.so")
 
 # every symbol include/multi_lora.h declares
-EXPORTS = ["multi_lora_plan_create", "multi_lora_plan_destroy", "multi_lora_validate",
+EXPORTS = ["multi_lora_plan_create", "multi_lora_plan_create_like", "multi_lora_plan_destroy", "multi_lora_validate",
            "multi_lora_workspace_bytes", "multi_lora_plan_geometry", "multi_lora_plan_dump",
            "multi_lora_fwd", "multi_lora_bwd", "multi_lora_last_error", "multi_lora_version",
            "multi_lora_profile_begin", "multi_lora_profile_end",
@@ -63,6 +63,8 @@ def lib() -> ctypes.CDLL:
         i32, i64, vp, u32 = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p, ctypes.c_uint32
         L.multi_lora_plan_create.argtypes = [ctypes.POINTER(vp), ctypes.c_int, i64, i64, i64, i32, vp, vp, vp, vp]
         L.multi_lora_plan_create.restype = ctypes.c_int
+        L.multi_lora_plan_create_like.argtypes = [ctypes.POINTER(vp), vp, i64, i64, vp]
+        L.multi_lora_plan_create_like.restype = ctypes.c_int
         L.multi_lora_plan_destroy.argtypes = [vp]
         L.multi_lora_plan_destroy.restype = ctypes.c_int
         L.multi_lora_validate.argtypes = [ctypes.c_int, i64, i64, i64, i32, vp, vp, vp]
@@ -149,6 +151,16 @@ class Plan:
         r, s, o = _meta(self.N, ranks, scales, offsets)
         _check(lib().multi_lora_plan_create(ctypes.byref(self._h), dtype, T, k, n, self.N, r, s, o,
                                             ctypes.c_void_p(stream)))
+
+    @classmethod
+    def like(cls, base: "Plan", k: int, n: int, stream: int = 0) -> "Plan":
+        """multi_lora_plan_create_like: another layer shape over the segmentation tables of `base`."""
+        self = cls.__new__(cls)
+        self.dtype, self.T, self.k, self.n, self.N = base.dtype, base.T, k, n, base.N
+        self.ranks, self.scales, self.offsets = list(base.ranks), list(base.scales), list(base.offsets)
+        self._h = ctypes.c_void_p()
+        _check(lib().multi_lora_plan_create_like(ctypes.byref(self._h), base.handle, k, n, ctypes.c_void_p(stream)))
+        return self
 
     @property
     def handle(self):

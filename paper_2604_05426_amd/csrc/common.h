@@ -5,6 +5,7 @@
 #include <stdint.h>
 
 #include <string>
+#include <memory>
 #include <vector>
 
 #include "multi_lora.h"
@@ -30,6 +31,14 @@ struct AdapterPtrs {
     const void* B;
     void* dA;
     void* dB;
+};
+
+// Owner of one hipMalloc'd block.
+struct DeviceBlock {
+    void* ptr = nullptr;
+    ~DeviceBlock() {
+        if (ptr) (void)hipFree(ptr);
+    }
 };
 
 // Device-resident view of a plan, passed by value to kernels.
@@ -71,9 +80,11 @@ struct mlora_plan {
     int32_t n_blocks_narrow = 0, n_blocks_wide = 0;
     int32_t* d_block_lists = nullptr;
     int32_t wgrad_chunk_rows = 0;     // token chunk of the weight-gradient items (chosen per plan)
-    // one device allocation carved into the tables below
-    void* d_block = nullptr;
+    // one device allocation carved into the tables below; a plan made by multi_lora_plan_create_like also holds the
+    // allocation of the plan whose segmentation tables it uses, so the two may be destroyed in any order
+    std::shared_ptr<mlora::DeviceBlock> d_block, d_shared_block;
     size_t d_block_bytes = 0;
+    bool shares_tables = false, shares_wgrad_table = false;
     mlora::PlanView view{};
     mlora::AdapterPtrs* d_ptrs = nullptr;
     // host mirror of the device pointer table: a call whose pointers match what the same stream uploaded last skips the upload

@@ -25,7 +25,7 @@ static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 // ---- device kernels -----------------------------------------------------------------
 
-// Sequential prefix sums over the adapters (N <= 4096, done by one thread).
+// Sequential prefix sums over the adapters (N <= 4096, done by one thread).  soff / rb_start may be NULL (not wanted).
 __global__ void plan_scan_kernel(int32_t N, const int32_t* off, const int32_t* rank, int64_t* soff,
                                  int32_t* rb_start, int32_t* wc_start, int block_rows,
                                  int chunk_rows) {
@@ -33,8 +33,8 @@ __global__ void plan_scan_kernel(int32_t N, const int32_t* off, const int32_t* r
     int64_t s = 0;
     int32_t rb = 0, wc = 0;
     for (int32_t i = 0; i < N; ++i) {
-        soff[i] = s;
-        rb_start[i] = rb;
+        if (soff) soff[i] = s;
+        if (rb_start) rb_start[i] = rb;
         wc_start[i] = wc;
         const int32_t Ti = off[i + 1] - off[i];
         const int32_t r = rank[i];
@@ -44,8 +44,8 @@ __global__ void plan_scan_kernel(int32_t N, const int32_t* off, const int32_t* r
             wc += (Ti + chunk_rows - 1) / chunk_rows;
         }
     }
-    soff[N] = s;
-    rb_start[N] = rb;
+    if (soff) soff[N] = s;
+    if (rb_start) rb_start[N] = rb;
     wc_start[N] = wc;
 }
 
@@ -224,9 +224,11 @@ extern "C" int multi_lora_validate(int dtype, int64_t T, int64_t k, int64_t n, i
     return MLORA_OK;
 }
 
-extern "C" int multi_lora_plan_create(mlora_plan** out, int dtype, int64_t T, int64_t k, int64_t n,
-                                      int32_t N, const int32_t* ranks, const float* scales,
-                                      const int64_t* seg_offsets, void* stream) {
+// `like`: a plan over the same segmentation (same T, N, ranks, scales, offsets) whose device tables the new plan
+// uses instead of building its own; only what depends on the layer shape or on the caller's buffers is new.
+static int plan_create_impl(mlora_plan** out, int dtype, int64_t T, int64_t k, int64_t n,
+                            int32_t N, const int32_t* ranks, const float* scales,
+                            const int64_t* seg_offsets, void* stream, const mlora_plan* like) {
     if (!out) {
         set_error("out is NULL");
         return MLORA_ERR_NULL;
@@ -275,6 +277,9 @@ extern "C" int multi_lora_plan_create(mlora_plan** out, int dtype, int64_t T, in
         }
         p->wgrad_chunk_rows = (int32_t)chunk;
     }
+    p->shares_tables = like != nullptr;
+    // the weight-gradient item table depends on the layer shape only through the token chunk
+    p->shares_wgrad_table = like != nullptr && like->wgrad_chunk_rows == p->wgrad_chunk_rows;
 
     // host-side sizes (the device rebuilds the same numbers; multi_lora_plan_dump exposes them)
     int64_t s = 0;
@@ -330,56 +335,59 @@ extern "C" int multi_lora_plan_create(mlora_plan** out, int dtype, int64_t T, in
     // carve one device allocation
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t r = o; o += up256(bytes); return r; };
-    const size_t o_off = take(sizeof(int32_t) * (N + 1));
-    const size_t o_rank = take(sizeof(int32_t) * (N + 1));
-    const size_t o_scale = take(sizeof(float) * (N + 1));
-    const size_t o_soff = take(sizeof(int64_t) * (N + 1));
-    const size_t o_rbs = take(sizeof(int32_t) * (N + 1));
-    const size_t o_wcs = take(sizeof(int32_t) * (N + 1));
+    const bool own_seg = !p->shares_tables, own_wc = !p->shares_wgrad_table;
+    const size_t o_off = take(own_seg ? sizeof(int32_t) * (N + 1) : 0);
+    const size_t o_rank = take(own_seg ? sizeof(int32_t) * (N + 1) : 0);
+    const size_t o_scale = take(own_seg ? sizeof(float) * (N + 1) : 0);
+    const size_t o_soff = take(own_seg ? sizeof(int64_t) * (N + 1) : 0);
+    const size_t o_rbs = take(own_seg ? sizeof(int32_t) * (N + 1) : 0);
+    const size_t o_wcs = take(own_wc ? sizeof(int32_t) * (N + 1) : 0);
     const size_t o_ptrs = take(sizeof(AdapterPtrs) * (N + 1));
-    const size_t o_rb = take(sizeof(Entry4) * (size_t)(p->n_row_blocks + 1));
-    const size_t o_gt = take(sizeof(Entry4) * (size_t)(p->n_gemm_tiles + 1));
-    const size_t o_wc = take(sizeof(Entry4) * (size_t)(p->n_wgrad_chunks + 1));
-    const size_t o_wc_tmp = take(sizeof(Entry4) * (size_t)(p->n_wgrad_chunks + 1));
+    const size_t o_rb = take(own_seg ? sizeof(Entry4) * (size_t)(p->n_row_blocks + 1) : 0);
+    const size_t o_gt = take(own_seg ? sizeof(Entry4) * (size_t)(p->n_gemm_tiles + 1) : 0);
+    const size_t o_wc = take(own_wc ? sizeof(Entry4) * (size_t)(p->n_wgrad_chunks + 1) : 0);
+    const size_t o_wc_tmp = take(own_wc ? sizeof(Entry4) * (size_t)(p->n_wgrad_chunks + 1) : 0);
     const size_t o_probs = take(128 * (size_t)(5 * N + 8));
     const size_t o_part = take(sizeof(int64_t) * (N + 1));
     const size_t o_adamw = take(96 * (size_t)(N + 1));
-    const size_t o_lists = take(sizeof(int32_t) * (size_t)(p->n_row_blocks + 1));
+    const size_t o_lists = take(own_seg ? sizeof(int32_t) * (size_t)(p->n_row_blocks + 1) : 0);
     p->d_block_bytes = o;
 
-    if (e == hipSuccess) e = hipMalloc(&p->d_block, p->d_block_bytes);
+    p->d_block = std::make_shared<DeviceBlock>();
+    if (e == hipSuccess) e = hipMalloc(&p->d_block->ptr, p->d_block_bytes);
     if (e != hipSuccess) {
         delete p;
         return hip_fail(e, "hipMalloc(plan tables)");
     }
-    char* base = (char*)p->d_block;
-    int32_t* d_off = (int32_t*)(base + o_off);
-    int32_t* d_rank = (int32_t*)(base + o_rank);
-    float* d_scale = (float*)(base + o_scale);
-    int64_t* d_soff = (int64_t*)(base + o_soff);
-    int32_t* d_rbs = (int32_t*)(base + o_rbs);
-    int32_t* d_wcs = (int32_t*)(base + o_wcs);
+    if (like) p->d_shared_block = like->d_block;      // keeps the shared tables alive
+    char* base = (char*)p->d_block->ptr;
+    const PlanView* lv = like ? &like->view : nullptr;
+    int32_t* d_off = own_seg ? (int32_t*)(base + o_off) : const_cast<int32_t*>(lv->off);
+    int32_t* d_rank = own_seg ? (int32_t*)(base + o_rank) : const_cast<int32_t*>(lv->rank);
+    float* d_scale = own_seg ? (float*)(base + o_scale) : const_cast<float*>(lv->scale);
+    int64_t* d_soff = own_seg ? (int64_t*)(base + o_soff) : const_cast<int64_t*>(lv->soff);
+    int32_t* d_rbs = own_seg ? (int32_t*)(base + o_rbs) : nullptr;
+    int32_t* d_wcs = own_wc ? (int32_t*)(base + o_wcs) : const_cast<int32_t*>(lv->wgrad_chunk_start);
     p->d_ptrs = (AdapterPtrs*)(base + o_ptrs);
-    Entry4* d_rb = (Entry4*)(base + o_rb);
-    Entry4* d_gt = (Entry4*)(base + o_gt);
-    Entry4* d_wc = (Entry4*)(base + o_wc);
+    Entry4* d_rb = own_seg ? (Entry4*)(base + o_rb) : const_cast<Entry4*>(lv->row_blocks);
+    Entry4* d_gt = own_seg ? (Entry4*)(base + o_gt) : const_cast<Entry4*>(lv->gemm_tiles);
+    Entry4* d_wc = own_wc ? (Entry4*)(base + o_wc) : const_cast<Entry4*>(lv->wgrad_chunks);
     p->d_probs = base + o_probs;
     p->d_part_off = (int64_t*)(base + o_part);
     p->d_adamw = base + o_adamw;
-    p->d_block_lists = (int32_t*)(base + o_lists);
+    p->d_block_lists = own_seg ? (int32_t*)(base + o_lists) : like->d_block_lists;
 
     hipStream_t st = p->build_stream;
     std::vector<int32_t>& off32 = p->off32;
     off32.resize(N + 1);
     for (int32_t i = 0; i <= N; ++i) off32[i] = (int32_t)p->off[i];
     auto fail = [&](hipError_t err, const char* what) {
-        (void)hipFree(p->d_block);
         delete p;
         return hip_fail(err, what);
     };
-    if ((e = hipMemcpyAsync(d_off, off32.data(), sizeof(int32_t) * (N + 1), hipMemcpyHostToDevice, st)) != hipSuccess)
+    if (own_seg && (e = hipMemcpyAsync(d_off, off32.data(), sizeof(int32_t) * (N + 1), hipMemcpyHostToDevice, st)) != hipSuccess)
         return fail(e, "hipMemcpyAsync(offsets)");
-    if (N > 0) {
+    if (own_seg && N > 0) {
         if ((e = hipMemcpyAsync(d_rank, p->ranks.data(), sizeof(int32_t) * N, hipMemcpyHostToDevice, st)) != hipSuccess)
             return fail(e, "hipMemcpyAsync(ranks)");
         if ((e = hipMemcpyAsync(d_scale, p->scales.data(), sizeof(float) * N, hipMemcpyHostToDevice, st)) != hipSuccess)
@@ -387,16 +395,21 @@ extern "C" int multi_lora_plan_create(mlora_plan** out, int dtype, int64_t T, in
     }
     if ((e = hipMemcpyAsync(p->d_part_off, part_off.data(), sizeof(int64_t) * (N + 1), hipMemcpyHostToDevice, st)) != hipSuccess)
         return fail(e, "hipMemcpyAsync(partial offsets)");
-    if (!p->block_lists.empty() &&
+    if (own_seg && !p->block_lists.empty() &&
         (e = hipMemcpyAsync(p->d_block_lists, p->block_lists.data(), sizeof(int32_t) * p->block_lists.size(),
                             hipMemcpyHostToDevice, st)) != hipSuccess)
         return fail(e, "hipMemcpyAsync(row-block classes)");
-    hipLaunchKernelGGL(plan_scan_kernel, dim3(1), dim3(64), 0, st, N, d_off, d_rank, d_soff, d_rbs, d_wcs,
-                       kBlockRows, p->wgrad_chunk_rows);
-    if (p->n_row_blocks > 0)
+    // (a plan that shares the segmentation tables but chunks the tokens differently scans again for its chunk starts)
+    if (own_seg)
+        hipLaunchKernelGGL(plan_scan_kernel, dim3(1), dim3(64), 0, st, N, d_off, d_rank, d_soff, d_rbs, d_wcs,
+                           kBlockRows, p->wgrad_chunk_rows);
+    else if (own_wc)
+        hipLaunchKernelGGL(plan_scan_kernel, dim3(1), dim3(64), 0, st, N, d_off, d_rank, (int64_t*)nullptr,
+                           (int32_t*)nullptr, d_wcs, kBlockRows, p->wgrad_chunk_rows);
+    if (own_seg && p->n_row_blocks > 0)
         hipLaunchKernelGGL(plan_fill_blocks_kernel, dim3((p->n_row_blocks + 255) / 256), dim3(256), 0, st, N,
                            d_off, d_rbs, kBlockRows, d_rb, p->n_row_blocks);
-    if (p->n_wgrad_chunks > 0) {
+    if (own_wc && p->n_wgrad_chunks > 0) {
         Entry4* d_wc_tmp = (Entry4*)(base + o_wc_tmp);
         const unsigned blocks = (unsigned)((p->n_wgrad_chunks + 255) / 256);
         if (p->n_wgrad_chunks <= kMaxSortedChunks) {   // canonical table, then reordered by cost
@@ -409,7 +422,7 @@ extern "C" int multi_lora_plan_create(mlora_plan** out, int dtype, int64_t T, in
                                p->wgrad_chunk_rows, d_wc, p->n_wgrad_chunks);
         }
     }
-    if (p->n_gemm_tiles > 0)
+    if (own_seg && p->n_gemm_tiles > 0)
         hipLaunchKernelGGL(plan_fill_gemm_tiles_kernel, dim3((p->n_gemm_tiles + 255) / 256), dim3(256), 0, st, N,
                            d_off, (int32_t)T, kGemmTileRows, d_gt, p->n_gemm_tiles);
     if ((e = hipGetLastError()) != hipSuccess) return fail(e, "plan build kernels");
@@ -423,6 +436,32 @@ extern "C" int multi_lora_plan_create(mlora_plan** out, int dtype, int64_t T, in
     v.wgrad_chunk_start = d_wcs;
     *out = p;
     return MLORA_OK;
+}
+
+extern "C" int multi_lora_plan_create(mlora_plan** out, int dtype, int64_t T, int64_t k, int64_t n,
+                                      int32_t N, const int32_t* ranks, const float* scales,
+                                      const int64_t* seg_offsets, void* stream) {
+    return plan_create_impl(out, dtype, T, k, n, N, ranks, scales, seg_offsets, stream, nullptr);
+}
+
+extern "C" int multi_lora_plan_create_like(mlora_plan** out, const mlora_plan* base, int64_t k, int64_t n,
+                                           void* stream) {
+    if (!out) {
+        set_error("out is NULL");
+        return MLORA_ERR_NULL;
+    }
+    *out = nullptr;
+    if (!base) {
+        set_error("base plan is NULL");
+        return MLORA_ERR_NULL;
+    }
+    // the tables of `base` are built on its own stream: a different stream must see them finished
+    if ((hipStream_t)stream != base->build_stream) {
+        set_error("multi_lora_plan_create_like: pass the stream the base plan was created on");
+        return MLORA_ERR_SHAPE;
+    }
+    return plan_create_impl(out, base->dtype, base->T, k, n, base->N, base->ranks.data(), base->scales.data(),
+                            base->off.data(), stream, base);
 }
 
 static void free_events(mlora_plan* plan) {
@@ -495,10 +534,7 @@ extern "C" int multi_lora_profile_end(mlora_plan* plan, int32_t* kernel_ids, flo
 extern "C" int multi_lora_plan_destroy(mlora_plan* plan) {
     if (!plan) return MLORA_OK;
     free_events(plan);
-    hipError_t e = hipSuccess;
-    if (plan->d_block) e = hipFree(plan->d_block);
-    delete plan;
-    if (e != hipSuccess) return hip_fail(e, "hipFree(plan tables)");
+    delete plan;      // frees the device block unless another plan still shares it
     return MLORA_OK;
 }
 

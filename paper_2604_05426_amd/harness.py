@@ -28,7 +28,8 @@ def to_host(t: torch.Tensor) -> np.ndarray:
 class DeviceLayer:
     """One multi-LoRA layer resident on the GPU: inputs, outputs, plan and workspace."""
 
-    def __init__(self, w: Workload, device: str = "cuda:0", canary: Optional[float] = None):
+    def __init__(self, w: Workload, device: str = "cuda:0", canary: Optional[float] = None,
+                 like: Optional["ml.Plan"] = None):
         if not torch.cuda.is_available():
             raise RuntimeError("DeviceLayer needs a GPU; there is no CPU fallback")
         self.w = w
@@ -49,7 +50,10 @@ class DeviceLayer:
         self.dA = [out(w.k, r) for r in w.ranks]
         self.dB = [out(r, w.n) for r in w.ranks]
         self.stream = torch.cuda.current_stream(dev).cuda_stream
-        self.plan = ml.Plan(self.mdtype, w.T, w.k, w.n, w.ranks, w.scales, w.offsets, stream=self.stream)
+        if like is None:
+            self.plan = ml.Plan(self.mdtype, w.T, w.k, w.n, w.ranks, w.scales, w.offsets, stream=self.stream)
+        else:      # another layer shape over the segmentation tables of an existing plan
+            self.plan = ml.Plan.like(like, w.k, w.n, stream=self.stream)
         self.ws_bytes = self.plan.workspace_bytes()
         self.workspace = torch.zeros(max(self.ws_bytes, 256), dtype=torch.uint8, device=dev)
 
@@ -82,3 +86,38 @@ class DeviceLayer:
             out.append(s[o:o + t * r].reshape(t, r))
             o += t * r
         return out
+
+
+class DeviceBlock:
+    """The LoRA'd linear layers of one transformer block over one segmentation: the first layer's plan is built from
+    the metadata, every other layer's plan with multi_lora_plan_create_like on it.  `step` runs every forward, every
+    backward (reverse order) and, when optimizer state was set up, the grouped AdamW update of every layer."""
+
+    def __init__(self, layers: List[Workload], device: str = "cuda:0", canary: Optional[float] = None,
+                 share_tables: bool = True):
+        self.layers: List[DeviceLayer] = []
+        for w in layers:
+            base = self.layers[0].plan if (self.layers and share_tables) else None
+            self.layers.append(DeviceLayer(w, device, canary, like=base))
+        self.state = None
+
+    def init_adamw(self) -> None:
+        dev = self.layers[0].device
+        self.state = []
+        for dl in self.layers:
+            sA = [torch.empty(3 * a.numel(), dtype=torch.float32, device=dev) for a in dl.A]
+            sB = [torch.empty(3 * b.numel(), dtype=torch.float32, device=dev) for b in dl.B]
+            ml.multi_lora_adamw_init(dl.plan, dl.A, dl.B, sA, sB, dl.stream)
+            self.state.append((sA, sB))
+
+    def step(self, hparams=None) -> None:
+        for dl in self.layers:
+            dl.forward()
+        for dl in reversed(self.layers):
+            dl.backward()
+        if self.state is not None and hparams is not None:
+            for dl, (sA, sB) in zip(self.layers, self.state):
+                ml.multi_lora_adamw_step(dl.plan, dl.A, dl.B, dl.dA, dl.dB, sA, sB, hparams, dl.stream)
+
+    def sync(self) -> None:
+        self.layers[0].sync()

@@ -103,6 +103,20 @@ def make_workload(name: str, dtype: str, k: int, n: int, ranks: Sequence[int],
                     dY=dY, seed=seed)
 
 
+# (name, input width, output width) of the seven LoRA'd projections of one Llama-3.1-8B block (paper App. B: LoRA on
+# all linear layers of attention and MLP; hidden 4096, 8 KV heads of 128, MLP width 14336)
+LLAMA8B_BLOCK = [("q_proj", 4096, 4096), ("k_proj", 4096, 1024), ("v_proj", 4096, 1024), ("o_proj", 4096, 4096),
+                 ("gate_proj", 4096, 14336), ("up_proj", 4096, 14336), ("down_proj", 14336, 4096)]
+
+
+def block_workloads(dtype: str, shapes: Sequence, ranks: Sequence[int], seg_lens: Sequence[int],
+                    scales: Sequence[float], seed: int, b_sigma: float = 0.02) -> List[Workload]:
+    """One Workload per (name, k, n) in ``shapes``, all over the same segmentation (each adapter has one rank and
+    one scale for every projection it is attached to); layer l draws from seed + l."""
+    return [make_workload(name, dtype, k, n, ranks, seg_lens, scales, seed + l, b_sigma=b_sigma)
+            for l, (name, k, n) in enumerate(shapes)]
+
+
 CONFIG_NAMES = ["tiny_fp32", "llama8b_qproj", "hetero_lengths", "llama8b_mlp_up", "llama70b_mlp"]
 
 
