@@ -26,6 +26,86 @@ PEAK_BF16_MFMA_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak
 PEAK_HBM_GBS = 8000.0            # MI355X HBM3E
 
 
+def bench_block(args, np, torch, ml, wl) -> int:
+    """One step = forward of the seven projections, backward of the seven (reverse order), grouped AdamW of every
+    adapter of every projection.  The plans of projections 2..7 reuse the first plan's segmentation tables."""
+    from paper_2604_05426_amd.harness import DeviceBlock
+    _, _, _, ranks, lens, scales, seed, _ = wl.config_shape(1)
+    T, N = sum(lens), len(ranks)
+    shapes = wl.LLAMA8B_BLOCK
+    # plan construction: the first plan builds the segmentation tables, the others reuse them
+    torch.cuda.synchronize()
+    off = [0]
+    for t in lens:
+        off.append(off[-1] + t)
+    t0 = time.perf_counter()
+    base = ml.Plan(ml.BF16, T, shapes[0][1], shapes[0][2], ranks, scales, off)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    likes = [ml.Plan.like(base, k, n) for _, k, n in shapes[1:]]
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    owns = [ml.Plan(ml.BF16, T, k, n, ranks, scales, off) for _, k, n in shapes[1:]]
+    torch.cuda.synchronize()
+    t3 = time.perf_counter()
+    for pl in likes + owns + [base]:
+        pl.destroy()
+
+    blk = DeviceBlock.synthetic("bf16", shapes, ranks, lens, scales, seed=100)
+    blk.init_adamw()
+    K, W = args.steps, args.warmup
+    step_no = [0]
+
+    def step():
+        step_no[0] += 1
+        blk.step([(1e-4, 0.9, 0.999, 1e-8, 0.0, step_no[0])] * N)
+
+    for _ in range(W):
+        step()
+    torch.cuda.synchronize()
+    t_settle, extra = time.perf_counter(), 0
+    while time.perf_counter() - t_settle < 0.2 and extra < 200:     # clocks settle under load (see main)
+        step(); step()
+        torch.cuda.synchronize()
+        extra += 2
+    start, end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    start.record()
+    for _ in range(K):
+        step()
+    end.record()
+    torch.cuda.synchronize()
+    ms = start.elapsed_time(end) / K
+    # launches per step, from one event-profiled step
+    launches = {}
+    for dl in blk.layers:
+        dl.plan.profile_begin(64)
+    step()
+    torch.cuda.synchronize()
+    per_layer = {}
+    for dl in blk.layers:
+        recs = dl.plan.profile_end(64)
+        per_layer[dl.w.name] = {"k": dl.w.k, "n": dl.w.n, "launches": len(recs), "ms": float(sum(m for _, m in recs))}
+        for kid, _ in recs:
+            launches[ml.KERNEL_NAMES[kid]] = launches.get(ml.KERNEL_NAMES[kid], 0) + 1
+    R1 = sum(t * r for t, r in zip(lens, ranks))
+    flops = sum(4.0 * T * k * n + 6.0 * R1 * (k + n) for _, k, n in shapes)
+    out = {
+        "metric": "multi-LoRA Llama-3.1-8B block (7 projections) fwd+bwd+AdamW tokens/s", "value": T / (ms * 1e-3),
+        "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W, "warmup_clock_settle_steps": extra, "ms_per_step": ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "llama8b_block: q,k,v,o,gate,up,down over config 2's segmentation", "T": T, "adapters": N,
+                   "ranks": ranks, "tokens_per_adapter": lens, "mode": "fused fwd+bwd per projection, grouped AdamW"},
+        "tflops": flops / (ms * 1e-3) / 1e12,
+        "frac_bf16_mfma_peak_whole_step": flops / (ms * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS,
+        "launches_per_step": launches, "launches_per_step_total": sum(launches.values()),
+        "per_projection": per_layer,
+        "plan_build_ms": {"first_plan": (t1 - t0) * 1e3, "six_more_sharing_its_tables": (t2 - t1) * 1e3,
+                          "six_more_built_independently": (t3 - t2) * 1e3},
+    }
+    print(json.dumps(out))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -36,6 +116,9 @@ def main() -> int:
     ap.add_argument("--no-extra", action="store_true", help="skip the per-kernel / LoRA-only passes")
     ap.add_argument("--fused-only", action="store_true",
                     help="skip the LoRA-only and base-only passes (every launch is then the fused-mode one; used under rocprofv3)")
+    ap.add_argument("--block", action="store_true",
+                    help="time a whole LoRA'd Llama-3.1-8B block instead of one layer: the seven projections over one "
+                         "segmentation (config 2's adapters), fwd, bwd and the grouped AdamW update")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 1 GiB device copy 3 times (calibrates FETCH_SIZE / WRITE_SIZE under rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -54,6 +137,9 @@ def main() -> int:
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         return 3
     ml.lib()   # fail loudly if the extension is missing
+
+    if args.block:
+        return bench_block(args, np, torch, ml, wl)
 
     index = args.config - 1
     w = wl.config(index)

@@ -57,6 +57,45 @@ class DeviceLayer:
         self.ws_bytes = self.plan.workspace_bytes()
         self.workspace = torch.zeros(max(self.ws_bytes, 256), dtype=torch.uint8, device=dev)
 
+    @classmethod
+    def synthetic(cls, name: str, dtype: str, k: int, n: int, ranks, seg_lens, scales, seed: int,
+                  device: str = "cuda:0", like: Optional["ml.Plan"] = None) -> "DeviceLayer":
+        """Same shapes and value distributions as workloads.make_workload, drawn on the GPU (no host copy, hence
+        nothing an oracle could be run on): for timing layers too large to generate on the host in reasonable time."""
+        if not torch.cuda.is_available():
+            raise RuntimeError("DeviceLayer needs a GPU; there is no CPU fallback")
+        self = cls.__new__(cls)
+        off = [0]
+        for t in seg_lens:
+            off.append(off[-1] + int(t))
+        T = off[-1]
+        self.w = Workload(name=name, dtype=dtype, T=T, k=k, n=n, ranks=[int(r) for r in ranks],
+                          scales=[float(x) for x in scales], offsets=off, X=None, W=None, A=[], B=[], dY=None, seed=seed)
+        self.device = torch.device(device)
+        self.tdtype = torch.bfloat16 if dtype == "bf16" else torch.float32
+        self.mdtype = ml.BF16 if dtype == "bf16" else ml.F32
+        gen = torch.Generator(device=self.device).manual_seed(seed)
+
+        def draw(shape, sigma):
+            return (torch.randn(shape, generator=gen, device=self.device, dtype=torch.float32) * sigma).to(self.tdtype)
+
+        self.X, self.W, self.dY = draw((T, k), 1.0), draw((k, n), 0.02), draw((T, n), 1.0)
+        self.A = [draw((k, r), 1.0 / np.sqrt(k)) for r in self.w.ranks]
+        self.B = [draw((r, n), 0.02) for r in self.w.ranks]
+        self.Y = torch.zeros((T, n), dtype=self.tdtype, device=self.device)
+        self.dX = torch.zeros((T, k), dtype=self.tdtype, device=self.device)
+        self.S = torch.zeros(max(self.w.R1, 1), dtype=self.tdtype, device=self.device)
+        self.dA = [torch.zeros((k, r), dtype=self.tdtype, device=self.device) for r in self.w.ranks]
+        self.dB = [torch.zeros((r, n), dtype=self.tdtype, device=self.device) for r in self.w.ranks]
+        self.stream = torch.cuda.current_stream(self.device).cuda_stream
+        if like is None:
+            self.plan = ml.Plan(self.mdtype, T, k, n, self.w.ranks, self.w.scales, off, stream=self.stream)
+        else:
+            self.plan = ml.Plan.like(like, k, n, stream=self.stream)
+        self.ws_bytes = self.plan.workspace_bytes()
+        self.workspace = torch.zeros(max(self.ws_bytes, 256), dtype=torch.uint8, device=self.device)
+        return self
+
     def forward(self, flags: int = 0) -> None:
         ml.multi_lora_fwd(self.plan, self.X, self.W, self.A, self.B, self.Y, self.S, self.workspace,
                           flags, self.stream)
@@ -100,6 +139,16 @@ class DeviceBlock:
             base = self.layers[0].plan if (self.layers and share_tables) else None
             self.layers.append(DeviceLayer(w, device, canary, like=base))
         self.state = None
+
+    @classmethod
+    def synthetic(cls, dtype: str, shapes, ranks, seg_lens, scales, seed: int, device: str = "cuda:0") -> "DeviceBlock":
+        """Layers drawn on the GPU (timing only), plans shared as in __init__."""
+        self = cls.__new__(cls)
+        self.layers, self.state = [], None
+        for l, (name, k, n) in enumerate(shapes):
+            base = self.layers[0].plan if self.layers else None
+            self.layers.append(DeviceLayer.synthetic(name, dtype, k, n, ranks, seg_lens, scales, seed + l, device, like=base))
+        return self
 
     def init_adamw(self) -> None:
         dev = self.layers[0].device
