@@ -106,6 +106,76 @@ def bench_block(args, np, torch, ml, wl) -> int:
     return 0
 
 
+def bench_kernel_table(args, np, torch, ml, wl) -> int:
+    """Grouped execution against launching the same kernels once per adapter, on the shape of the paper's kernel
+    microbenchmark.  Three ways to run one fwd+bwd of a 2048 x 2048 projection for 32 co-resident adapters:
+      grouped      one plan over all adapters, fused step (this library's default);
+      back_to_back the frozen-weight GEMMs once over the whole batch (MLORA_FLAG_BASE_ONLY), then every adapter's LoRA
+                   terms on its own rows through its own single-adapter plan (MLORA_FLAG_LORA_ONLY), one after another;
+      sequential   every adapter alone: its own fused step on its own rows, frozen-weight GEMM included."""
+    from paper_2604_05426_amd.harness import DeviceLayer
+    k = n = 2048
+    N, seq = 32, 256
+    ranks = [[16, 32, 64][i % 3] for i in range(N)]
+    scales = [2.0] * N            # alpha = 2r (the paper's training setting)
+    K, W = args.steps, args.warmup
+    rows = []
+
+    def timed(fn):
+        for _ in range(W):
+            fn()
+        torch.cuda.synchronize()
+        t_settle = time.perf_counter()
+        while time.perf_counter() - t_settle < 0.1:
+            fn()
+            torch.cuda.synchronize()
+        start, end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        start.record()
+        for _ in range(K):
+            fn()
+        end.record()
+        torch.cuda.synchronize()
+        return start.elapsed_time(end) / K
+
+    for bs in (1, 2, 4):
+        lens = [bs * seq] * N
+        dl = DeviceLayer.synthetic(f"bs{bs}", "bf16", k, n, ranks, lens, scales, seed=200 + bs)
+        off = dl.w.offsets
+        singles = []
+        for i in range(N):
+            pl = ml.Plan(ml.BF16, lens[i], k, n, [ranks[i]], [scales[i]], [0, lens[i]], stream=dl.stream)
+            ws = torch.zeros(max(pl.workspace_bytes(), 256), dtype=torch.uint8, device=dl.device)
+            Si = torch.zeros(max(lens[i] * ranks[i], 1), dtype=dl.tdtype, device=dl.device)
+            singles.append((pl, ws, Si, slice(off[i], off[i + 1])))
+
+        def grouped():
+            dl.forward(); dl.backward()
+
+        def per_adapter(flags):
+            for i, (pl, ws, Si, sl) in enumerate(singles):
+                ml.multi_lora_fwd(pl, dl.X[sl], dl.W, [dl.A[i]], [dl.B[i]], dl.Y[sl], Si, ws, flags, dl.stream)
+                ml.multi_lora_bwd(pl, dl.dY[sl], dl.X[sl], dl.W, [dl.A[i]], [dl.B[i]], Si, dl.dX[sl], [dl.dA[i]], [dl.dB[i]],
+                                  ws, flags, dl.stream)
+
+        def back_to_back():
+            dl.forward(ml.FLAG_BASE_ONLY); dl.backward(ml.FLAG_BASE_ONLY)
+            per_adapter(ml.FLAG_LORA_ONLY)
+
+        t_g, t_b, t_s = timed(grouped), timed(back_to_back), timed(lambda: per_adapter(0))
+        rows.append({"per_adapter_batch": bs, "tokens": sum(lens), "grouped_ms": t_g, "back_to_back_ms": t_b, "sequential_ms": t_s,
+                     "grouped_over_back_to_back": t_b / t_g, "grouped_over_sequential": t_s / t_g})
+        for pl, _, _, _ in singles:
+            pl.destroy()
+        dl.plan.destroy()
+    out = {"metric": "grouped multi-LoRA layer fwd+bwd against per-adapter launches (speed-up)", "value": rows[0]["grouped_over_back_to_back"],
+           "unit": "x", "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": rows[0]["grouped_ms"], "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": "kernel_table: 32 adapters, ranks 16/32/64 mixed, k = n = 2048, 256-token sequences", "adapters": N,
+                      "ranks": ranks}, "table": rows}
+    print(json.dumps(out))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -119,6 +189,10 @@ def main() -> int:
     ap.add_argument("--block", action="store_true",
                     help="time a whole LoRA'd Llama-3.1-8B block instead of one layer: the seven projections over one "
                          "segmentation (config 2's adapters), fwd, bwd and the grouped AdamW update")
+    ap.add_argument("--kernel-table", action="store_true",
+                    help="the paper's kernel microbenchmark shape (Sec. 8.3 ablation, kernel table): 32 adapters, ranks "
+                         "16/32/64 equally mixed, Llama-3.2-1B width, per-adapter batch 1/2/4 x 256 tokens; grouped launch "
+                         "against per-adapter launches of the same kernels")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 1 GiB device copy 3 times (calibrates FETCH_SIZE / WRITE_SIZE under rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -140,6 +214,8 @@ def main() -> int:
 
     if args.block:
         return bench_block(args, np, torch, ml, wl)
+    if args.kernel_table:
+        return bench_kernel_table(args, np, torch, ml, wl)
 
     index = args.config - 1
     w = wl.config(index)
