@@ -246,6 +246,48 @@ const char* multi_lora_last_error(void);
 /* Library version, "major.minor". */
 const char* multi_lora_version(void);
 
+/* ---------------------------------------------------------------------------------------------
+ * Loss-aware early exit (Sec. 4.1, Algorithm "Loss-Aware Pattern Detection"; Sec. 4.2).  Host only, no GPU work.
+ * One monitor tracks n adapters.  Report every training loss with multi_lora_monitor_train_loss (it feeds the
+ * exponential moving average lhat <- alpha l + (1 - alpha) lhat, seeded with the first loss) and every validation
+ * loss with multi_lora_monitor_val_loss, which appends (lhat, val) to the adapter's histories and applies
+ *   divergence:  once `window` evaluations exist, the least-squares slopes of the last `window` values of both
+ *                histories; both >= tau_slope for patience_div evaluations in a row -> MLORA_EXIT_DIVERGING;
+ *   overfitting: (val - lhat) / lhat > tau_gap for patience_ovf evaluations in a row -> MLORA_EXIT_OVERFITTING
+ *                (multi_lora_monitor_state names the evaluation step with the best validation loss to restore);
+ * divergence is tested first.  A decision is final: later reports for that adapter return it again.
+ * multi_lora_monitor_warmup_select is the warmup boundary: the surviving adapters are ranked by their latest
+ * validation loss (ascending, ties in adapter order, never-evaluated last) and all but the best
+ * ceil(ratio x survivors) become MLORA_EXIT_UNDERPERFORMING; `status` (host, [n]) receives every adapter's status.
+ * Errors: MLORA_ERR_NULL, MLORA_ERR_SHAPE (index or parameter out of range, validation before any training loss).
+ * A monitor is not thread safe.
+ */
+typedef struct mlora_monitor mlora_monitor;
+typedef struct {
+    double ema_alpha;       /* weight of the newest training loss, (0, 1] */
+    int32_t window;         /* w >= 2, in evaluation steps */
+    int32_t patience_div;   /* p_div >= 1 */
+    int32_t patience_ovf;   /* p_ovf >= 1 */
+    double tau_slope;
+    double tau_gap;
+} mlora_monitor_params;
+typedef struct {
+    double ema_train_loss;  /* NaN before the first training loss */
+    double best_val_loss;   /* +inf before the first evaluation */
+    int32_t best_eval_step; /* 0-based index of that evaluation, -1 before the first */
+    int32_t evaluations;
+    int32_t count_diverging, count_overfitting;
+    int32_t status;         /* MLORA_EXIT_* */
+} mlora_monitor_state;
+enum { MLORA_EXIT_CONTINUE = 0, MLORA_EXIT_DIVERGING = 1, MLORA_EXIT_OVERFITTING = 2, MLORA_EXIT_UNDERPERFORMING = 3 };
+
+int multi_lora_monitor_create(mlora_monitor** out, int32_t n_adapters, const mlora_monitor_params* params);
+int multi_lora_monitor_destroy(mlora_monitor* monitor);
+int multi_lora_monitor_train_loss(mlora_monitor* monitor, int32_t adapter, double loss);
+int multi_lora_monitor_val_loss(mlora_monitor* monitor, int32_t adapter, double val_loss, int32_t* decision);
+int multi_lora_monitor_warmup_select(mlora_monitor* monitor, double ratio, int32_t* status);
+int multi_lora_monitor_state(const mlora_monitor* monitor, int32_t adapter, mlora_monitor_state* out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -31,10 +31,27 @@ EXPORTS = ["multi_lora_plan_create", "multi_lora_plan_create_like", "multi_lora_
            "multi_lora_fwd", "multi_lora_bwd", "multi_lora_last_error", "multi_lora_version",
            "multi_lora_profile_begin", "multi_lora_profile_end",
            "multi_lora_adamw_init", "multi_lora_adamw_step",
-           "multi_lora_calib_mfma", "multi_lora_calib_read"]
+           "multi_lora_calib_mfma", "multi_lora_calib_read",
+           "multi_lora_monitor_create", "multi_lora_monitor_destroy", "multi_lora_monitor_train_loss",
+           "multi_lora_monitor_val_loss", "multi_lora_monitor_warmup_select", "multi_lora_monitor_state"]
+
+EXIT_CONTINUE, EXIT_DIVERGING, EXIT_OVERFITTING, EXIT_UNDERPERFORMING = 0, 1, 2, 3
 
 KERNEL_NAMES = {0: "shrink", 1: "gemm_fwd", 2: "dshrink", 3: "gemm_bwd", 4: "wgrad", 5: "wgrad_reduce", 6: "other",
                 7: "adamw"}
+
+
+class MonitorParams(ctypes.Structure):
+    """mlora_monitor_params"""
+    _fields_ = [("ema_alpha", ctypes.c_double), ("window", ctypes.c_int32), ("patience_div", ctypes.c_int32),
+                ("patience_ovf", ctypes.c_int32), ("tau_slope", ctypes.c_double), ("tau_gap", ctypes.c_double)]
+
+
+class MonitorState(ctypes.Structure):
+    """mlora_monitor_state"""
+    _fields_ = [("ema_train_loss", ctypes.c_double), ("best_val_loss", ctypes.c_double), ("best_eval_step", ctypes.c_int32),
+                ("evaluations", ctypes.c_int32), ("count_diverging", ctypes.c_int32), ("count_overfitting", ctypes.c_int32),
+                ("status", ctypes.c_int32)]
 
 
 class AdamwHparams(ctypes.Structure):
@@ -91,6 +108,18 @@ def lib() -> ctypes.CDLL:
         L.multi_lora_calib_mfma.restype = ctypes.c_int
         L.multi_lora_calib_read.argtypes = [vp, ctypes.c_size_t, vp, ctypes.POINTER(ctypes.c_float), vp]
         L.multi_lora_calib_read.restype = ctypes.c_int
+        L.multi_lora_monitor_create.argtypes = [ctypes.POINTER(vp), i32, ctypes.POINTER(MonitorParams)]
+        L.multi_lora_monitor_create.restype = ctypes.c_int
+        L.multi_lora_monitor_destroy.argtypes = [vp]
+        L.multi_lora_monitor_destroy.restype = ctypes.c_int
+        L.multi_lora_monitor_train_loss.argtypes = [vp, i32, ctypes.c_double]
+        L.multi_lora_monitor_train_loss.restype = ctypes.c_int
+        L.multi_lora_monitor_val_loss.argtypes = [vp, i32, ctypes.c_double, ctypes.POINTER(i32)]
+        L.multi_lora_monitor_val_loss.restype = ctypes.c_int
+        L.multi_lora_monitor_warmup_select.argtypes = [vp, ctypes.c_double, vp]
+        L.multi_lora_monitor_warmup_select.restype = ctypes.c_int
+        L.multi_lora_monitor_state.argtypes = [vp, i32, ctypes.POINTER(MonitorState)]
+        L.multi_lora_monitor_state.restype = ctypes.c_int
         L.multi_lora_last_error.restype = ctypes.c_char_p
         L.multi_lora_version.restype = ctypes.c_char_p
         _lib = L
@@ -252,3 +281,43 @@ def multi_lora_calib_read(buffer, nbytes: int, scratch, stream: int = 0) -> floa
     out = ctypes.c_float(0.0)
     _check(lib().multi_lora_calib_read(_addr(buffer), nbytes, _addr(scratch), ctypes.byref(out), ctypes.c_void_p(stream)))
     return float(out.value)
+
+
+class Monitor:
+    """Owns one mlora_monitor (loss-aware early exit; host only)."""
+
+    def __init__(self, n: int, ema_alpha: float, window: int, tau_slope: float, tau_gap: float, patience_div: int,
+                 patience_ovf: int):
+        self.n = n
+        self._h = ctypes.c_void_p()
+        p = MonitorParams(ema_alpha, window, patience_div, patience_ovf, tau_slope, tau_gap)
+        _check(lib().multi_lora_monitor_create(ctypes.byref(self._h), n, ctypes.byref(p)))
+
+    def train_loss(self, adapter: int, loss: float) -> None:
+        _check(lib().multi_lora_monitor_train_loss(self._h, adapter, float(loss)))
+
+    def val_loss(self, adapter: int, val: float) -> int:
+        d = ctypes.c_int32(-1)
+        _check(lib().multi_lora_monitor_val_loss(self._h, adapter, float(val), ctypes.byref(d)))
+        return d.value
+
+    def warmup_select(self, ratio: float) -> List[int]:
+        out = (ctypes.c_int32 * max(self.n, 1))()
+        _check(lib().multi_lora_monitor_warmup_select(self._h, float(ratio), out))
+        return list(out)[: self.n]
+
+    def state(self, adapter: int) -> MonitorState:
+        st = MonitorState()
+        _check(lib().multi_lora_monitor_state(self._h, adapter, ctypes.byref(st)))
+        return st
+
+    def destroy(self) -> None:
+        if self._h:
+            lib().multi_lora_monitor_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
