@@ -80,6 +80,13 @@ struct mlora_plan {
     int32_t n_blocks_narrow = 0, n_blocks_wide = 0;
     int32_t* d_block_lists = nullptr;
     int32_t wgrad_chunk_rows = 0;     // token chunk of the weight-gradient items (chosen per plan)
+    // Plans that mix ranks <= 64 and wider ones run the weight-gradient items of the two classes as two launches that
+    // overlap (the wide class on aux_stream, forked from and joined to the caller's stream with the two events), each
+    // through the kernel build - and so at the workgroups per CU - its class allows.
+    int32_t max_rank_narrow = 0;      // largest rank <= 64 among adapters with tokens
+    bool wgrad_two_classes = false;
+    hipStream_t aux_stream = nullptr;
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     // one device allocation carved into the tables below; a plan made by multi_lora_plan_create_like also holds the
     // allocation of the plan whose segmentation tables it uses, so the two may be destroyed in any order
     std::shared_ptr<mlora::DeviceBlock> d_block, d_shared_block;

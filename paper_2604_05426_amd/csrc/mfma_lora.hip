@@ -257,6 +257,7 @@ struct WgradArgs {
     PlanView pv;
     const int64_t* part_off;   // [N] float offset of adapter i's partial block (chunks > 1 only)
     int32_t accumulate;        // dA_i, dB_i += result (MLORA_FLAG_ACCUM_GRADS)
+    int32_t rank_class;        // 0: every item; 1: only adapters with rank <= 64; 2: only wider ones
 };
 
 template <int MAXNB>
@@ -281,6 +282,7 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradArgs g) {
     const bool isA = panel < g.panels_k;
     if (!isA) panel -= g.panels_k;
     const int r = g.pv.rank[i];
+    if ((g.rank_class == 1 && r > 64) || (g.rank_class == 2 && r <= 64)) return;   // the other launch's item (uniform)
     const int rpad = (r + 31) & ~31;
     const int nblk = rpad / 32;
     const int64_t so = g.pv.soff[i];
@@ -662,9 +664,26 @@ int mfma_backward(mlora_plan* p, const void* dY, const void* X, const void* W, c
             const int64_t grid = (int64_t)p->n_wgrad_chunks * (w.panels_k + w.panels_n);
             {
                 ProfScope prof(p, MLORA_K_WGRAD, st);
-                if (p->max_rank <= 32)      hipLaunchKernelGGL(wgrad_kernel<1>, dim3((unsigned)grid), dim3(256), 0, st, w);
-                else if (p->max_rank <= 64) hipLaunchKernelGGL(wgrad_kernel<2>, dim3((unsigned)grid), dim3(256), 0, st, w);
-                else                        hipLaunchKernelGGL(wgrad_kernel<4>, dim3((unsigned)grid), dim3(256), 0, st, w);
+                auto narrow = [&](int32_t max_rank, hipStream_t s) {
+                    if (max_rank <= 32) hipLaunchKernelGGL(wgrad_kernel<1>, dim3((unsigned)grid), dim3(256), 0, s, w);
+                    else                hipLaunchKernelGGL(wgrad_kernel<2>, dim3((unsigned)grid), dim3(256), 0, s, w);
+                };
+                if (p->wgrad_two_classes) {
+                    // fork: the wide class on the plan's own stream, overlapping the narrow class; join before anything else
+                    MLORA_HIP_TRY(hipEventRecord(p->ev_fork, st));
+                    MLORA_HIP_TRY(hipStreamWaitEvent(p->aux_stream, p->ev_fork, 0));
+                    w.rank_class = 2;
+                    hipLaunchKernelGGL(wgrad_kernel<4>, dim3((unsigned)grid), dim3(256), 0, p->aux_stream, w);
+                    w.rank_class = 1;
+                    narrow(p->max_rank_narrow, st);
+                    w.rank_class = 0;
+                    MLORA_HIP_TRY(hipEventRecord(p->ev_join, p->aux_stream));
+                    MLORA_HIP_TRY(hipStreamWaitEvent(st, p->ev_join, 0));
+                } else if (p->max_rank <= 64) {
+                    narrow(p->max_rank, st);
+                } else {
+                    hipLaunchKernelGGL(wgrad_kernel<4>, dim3((unsigned)grid), dim3(256), 0, st, w);
+                }
             }
             if (p->max_chunks_per_adapter > 1) {
                 const int64_t per = (p->k + p->n) * (int64_t)p->max_rank;

@@ -297,6 +297,15 @@ static int plan_create_impl(mlora_plan** out, int dtype, int64_t T, int64_t k, i
         }
         if (ranks[i] > p->max_rank) p->max_rank = ranks[i];
     }
+    {
+        bool wide = false;
+        for (int32_t i = 0; i < N; ++i) {
+            if (p->off[i + 1] == p->off[i] || ranks[i] == 0) continue;
+            if (ranks[i] > 64) wide = true;
+            else if (ranks[i] > p->max_rank_narrow) p->max_rank_narrow = ranks[i];
+        }
+        p->wgrad_two_classes = wide && p->max_rank_narrow > 0;
+    }
     {   // same enumeration as the device-built row-block table: adapters ascending, blocks ascending
         std::vector<int32_t> narrow;
         int32_t idx = 0;
@@ -382,6 +391,9 @@ static int plan_create_impl(mlora_plan** out, int dtype, int64_t T, int64_t k, i
     off32.resize(N + 1);
     for (int32_t i = 0; i <= N; ++i) off32[i] = (int32_t)p->off[i];
     auto fail = [&](hipError_t err, const char* what) {
+        if (p->ev_fork) (void)hipEventDestroy(p->ev_fork);
+        if (p->ev_join) (void)hipEventDestroy(p->ev_join);
+        if (p->aux_stream) (void)hipStreamDestroy(p->aux_stream);
         delete p;
         return hip_fail(err, what);
     };
@@ -434,6 +446,11 @@ static int plan_create_impl(mlora_plan** out, int dtype, int64_t T, int64_t k, i
     v.gemm_tiles = d_gt; v.n_gemm_tiles = p->n_gemm_tiles;
     v.wgrad_chunks = d_wc; v.n_wgrad_chunks = p->n_wgrad_chunks;
     v.wgrad_chunk_start = d_wcs;
+    if (p->wgrad_two_classes && p->use_mfma) {
+        if ((e = hipStreamCreateWithFlags(&p->aux_stream, hipStreamNonBlocking)) != hipSuccess) return fail(e, "hipStreamCreateWithFlags");
+        if ((e = hipEventCreateWithFlags(&p->ev_fork, hipEventDisableTiming)) != hipSuccess) return fail(e, "hipEventCreateWithFlags");
+        if ((e = hipEventCreateWithFlags(&p->ev_join, hipEventDisableTiming)) != hipSuccess) return fail(e, "hipEventCreateWithFlags");
+    }
     *out = p;
     return MLORA_OK;
 }
@@ -534,6 +551,9 @@ extern "C" int multi_lora_profile_end(mlora_plan* plan, int32_t* kernel_ids, flo
 extern "C" int multi_lora_plan_destroy(mlora_plan* plan) {
     if (!plan) return MLORA_OK;
     free_events(plan);
+    if (plan->ev_fork) (void)hipEventDestroy(plan->ev_fork);
+    if (plan->ev_join) (void)hipEventDestroy(plan->ev_join);
+    if (plan->aux_stream) (void)hipStreamDestroy(plan->aux_stream);
     delete plan;      // frees the device block unless another plan still shares it
     return MLORA_OK;
 }
