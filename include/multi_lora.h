@@ -288,6 +288,38 @@ int multi_lora_monitor_val_loss(mlora_monitor* monitor, int32_t adapter, double 
 int multi_lora_monitor_warmup_select(mlora_monitor* monitor, double ratio, int32_t* status);
 int multi_lora_monitor_state(const mlora_monitor* monitor, int32_t adapter, mlora_monitor_state* out);
 
+/* ---------------------------------------------------------------------------------------------
+ * Online greedy intra-task scheduling (Sec. 6.1; App. "Intra-Task Scheduling Details").  Host only, no GPU work.
+ * multi_lora_memory_model_fit fits the profiled points (total batch x sequence length, peak bytes) to
+ * Mhat(B) = k0 + k1 B L by least squares.  A scheduler keeps pending jobs (submission order) and running jobs (admission
+ * order); a job fits while  k0 + k1 (B_running + b) L <= safety_margin x capacity_bytes.
+ *   _submit   adds a pending job with its per-adapter batch size (ids are the caller's, unique among live jobs);
+ *   _fill     greedy pass: pending jobs in decreasing batch size (submission order within a size), every job that fits
+ *             is admitted, one that does not is skipped; `admitted` (host, cap entries) receives the ids in order;
+ *   _exit     a running job leaves (early exit or completion): the oldest pending job of the same batch size takes the
+ *             slot if it fits, then the greedy pass runs over what is still pending; `admitted` as above;
+ *   _running  the co-located set in admission order = the adapter order of the next step's batch.
+ * If an output array is too small the call returns MLORA_ERR_SHAPE with *count set; the scheduler state has changed.
+ * Errors: MLORA_ERR_NULL, MLORA_ERR_SHAPE (bad parameter, duplicate id, job not running).  Not thread safe.
+ */
+typedef struct mlora_admission mlora_admission;
+typedef struct {
+    double k0, k1;           /* bytes, bytes per (sample x token) */
+    double capacity_bytes;   /* HBM capacity the executor may use */
+    double safety_margin;    /* usable fraction of the capacity, (0, 1] */
+    int64_t seq_len;         /* L */
+} mlora_admission_params;
+
+int multi_lora_memory_model_fit(int32_t n_points, const double* batch_times_seq, const double* peak_bytes,
+                                double* k0, double* k1);
+int multi_lora_admission_create(mlora_admission** out, const mlora_admission_params* params);
+int multi_lora_admission_destroy(mlora_admission* scheduler);
+int multi_lora_admission_submit(mlora_admission* scheduler, int32_t job_id, int32_t batch_size);
+int multi_lora_admission_fill(mlora_admission* scheduler, int32_t* admitted, int32_t cap, int32_t* count);
+int multi_lora_admission_exit(mlora_admission* scheduler, int32_t job_id, int32_t* admitted, int32_t cap, int32_t* count);
+int multi_lora_admission_running(const mlora_admission* scheduler, int32_t* job_ids, int32_t* batch_sizes, int32_t cap,
+                                 int32_t* count);
+
 #ifdef __cplusplus
 }
 #endif

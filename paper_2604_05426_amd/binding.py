@@ -33,7 +33,10 @@ EXPORTS = ["multi_lora_plan_create", "multi_lora_plan_create_like", "multi_lora_
            "multi_lora_adamw_init", "multi_lora_adamw_step",
            "multi_lora_calib_mfma", "multi_lora_calib_read",
            "multi_lora_monitor_create", "multi_lora_monitor_destroy", "multi_lora_monitor_train_loss",
-           "multi_lora_monitor_val_loss", "multi_lora_monitor_warmup_select", "multi_lora_monitor_state"]
+           "multi_lora_monitor_val_loss", "multi_lora_monitor_warmup_select", "multi_lora_monitor_state",
+           "multi_lora_memory_model_fit", "multi_lora_admission_create", "multi_lora_admission_destroy",
+           "multi_lora_admission_submit", "multi_lora_admission_fill", "multi_lora_admission_exit",
+           "multi_lora_admission_running"]
 
 EXIT_CONTINUE, EXIT_DIVERGING, EXIT_OVERFITTING, EXIT_UNDERPERFORMING = 0, 1, 2, 3
 
@@ -52,6 +55,12 @@ class MonitorState(ctypes.Structure):
     _fields_ = [("ema_train_loss", ctypes.c_double), ("best_val_loss", ctypes.c_double), ("best_eval_step", ctypes.c_int32),
                 ("evaluations", ctypes.c_int32), ("count_diverging", ctypes.c_int32), ("count_overfitting", ctypes.c_int32),
                 ("status", ctypes.c_int32)]
+
+
+class AdmissionParams(ctypes.Structure):
+    """mlora_admission_params"""
+    _fields_ = [("k0", ctypes.c_double), ("k1", ctypes.c_double), ("capacity_bytes", ctypes.c_double),
+                ("safety_margin", ctypes.c_double), ("seq_len", ctypes.c_int64)]
 
 
 class AdamwHparams(ctypes.Structure):
@@ -120,6 +129,21 @@ def lib() -> ctypes.CDLL:
         L.multi_lora_monitor_warmup_select.restype = ctypes.c_int
         L.multi_lora_monitor_state.argtypes = [vp, i32, ctypes.POINTER(MonitorState)]
         L.multi_lora_monitor_state.restype = ctypes.c_int
+        dp = ctypes.POINTER(ctypes.c_double)
+        L.multi_lora_memory_model_fit.argtypes = [i32, dp, dp, dp, dp]
+        L.multi_lora_memory_model_fit.restype = ctypes.c_int
+        L.multi_lora_admission_create.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(AdmissionParams)]
+        L.multi_lora_admission_create.restype = ctypes.c_int
+        L.multi_lora_admission_destroy.argtypes = [vp]
+        L.multi_lora_admission_destroy.restype = ctypes.c_int
+        L.multi_lora_admission_submit.argtypes = [vp, i32, i32]
+        L.multi_lora_admission_submit.restype = ctypes.c_int
+        L.multi_lora_admission_fill.argtypes = [vp, vp, i32, ctypes.POINTER(i32)]
+        L.multi_lora_admission_fill.restype = ctypes.c_int
+        L.multi_lora_admission_exit.argtypes = [vp, i32, vp, i32, ctypes.POINTER(i32)]
+        L.multi_lora_admission_exit.restype = ctypes.c_int
+        L.multi_lora_admission_running.argtypes = [vp, vp, vp, i32, ctypes.POINTER(i32)]
+        L.multi_lora_admission_running.restype = ctypes.c_int
         L.multi_lora_last_error.restype = ctypes.c_char_p
         L.multi_lora_version.restype = ctypes.c_char_p
         _lib = L
@@ -314,6 +338,55 @@ class Monitor:
     def destroy(self) -> None:
         if self._h:
             lib().multi_lora_monitor_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def memory_model_fit(batch_times_seq: Sequence[float], peak_bytes: Sequence[float]):
+    """multi_lora_memory_model_fit -> (k0, k1)"""
+    n = len(batch_times_seq)
+    x = (ctypes.c_double * max(n, 1))(*[float(v) for v in batch_times_seq])
+    y = (ctypes.c_double * max(n, 1))(*[float(v) for v in peak_bytes])
+    k0, k1 = ctypes.c_double(), ctypes.c_double()
+    _check(lib().multi_lora_memory_model_fit(n, x, y, ctypes.byref(k0), ctypes.byref(k1)))
+    return k0.value, k1.value
+
+
+class Admission:
+    """Owns one mlora_admission (online greedy intra-task scheduler; host only)."""
+    CAP = 4096
+
+    def __init__(self, k0: float, k1: float, capacity_bytes: float, safety_margin: float, seq_len: int):
+        self._h = ctypes.c_void_p()
+        p = AdmissionParams(k0, k1, capacity_bytes, safety_margin, seq_len)
+        _check(lib().multi_lora_admission_create(ctypes.byref(self._h), ctypes.byref(p)))
+
+    def submit(self, job: int, batch: int) -> None:
+        _check(lib().multi_lora_admission_submit(self._h, job, batch))
+
+    def fill(self) -> List[int]:
+        out, cnt = (ctypes.c_int32 * self.CAP)(), ctypes.c_int32(0)
+        _check(lib().multi_lora_admission_fill(self._h, out, self.CAP, ctypes.byref(cnt)))
+        return list(out[: cnt.value])
+
+    def exit(self, job: int) -> List[int]:
+        out, cnt = (ctypes.c_int32 * self.CAP)(), ctypes.c_int32(0)
+        _check(lib().multi_lora_admission_exit(self._h, job, out, self.CAP, ctypes.byref(cnt)))
+        return list(out[: cnt.value])
+
+    def running(self) -> List[tuple]:
+        ids, bs, cnt = (ctypes.c_int32 * self.CAP)(), (ctypes.c_int32 * self.CAP)(), ctypes.c_int32(0)
+        _check(lib().multi_lora_admission_running(self._h, ids, bs, self.CAP, ctypes.byref(cnt)))
+        return [(ids[i], bs[i]) for i in range(cnt.value)]
+
+    def destroy(self) -> None:
+        if self._h:
+            lib().multi_lora_admission_destroy(self._h)
             self._h = ctypes.c_void_p()
 
     def __del__(self):
