@@ -113,6 +113,9 @@ enum {
  *   scales       host [N], finite
  *   seg_offsets  host [N+1], seg_offsets[0] = 0, non-decreasing, seg_offsets[N] = T (N >= 1)
  * The only entry point that allocates device memory; freed by multi_lora_plan_destroy.
+ * A bf16 plan whose adapters mix ranks <= 64 with wider ones also owns one HIP stream (default priority) and two events:
+ * multi_lora_bwd runs the weight gradients of the two rank classes as two overlapping launches, the second on that
+ * stream, forked from and joined back to the caller's stream with the events (legal under stream capture).
  */
 int multi_lora_plan_create(mlora_plan** out, int dtype, int64_t T, int64_t k, int64_t n,
                            int32_t N, const int32_t* ranks, const float* scales,
