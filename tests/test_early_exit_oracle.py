@@ -109,3 +109,34 @@ def test_warmup_selection_ranks_survivors_only():
     assert m.a[4].status == ee.OVERFITTING               # exited during warmup: not ranked
     st = m.warmup_select(0.25)                           # 5 survivors -> keep ceil(1.25) = 2: adapters 1 and 3 (tie, in order)
     assert st == [ee.UNDERPERFORMING, ee.CONTINUE, ee.UNDERPERFORMING, ee.CONTINUE, ee.OVERFITTING, ee.UNDERPERFORMING]
+
+
+def _paper_settings():
+    import os
+    vals, keeps = {}, []
+    with open(os.path.join(os.path.dirname(__file__), "golden", "early_exit_paper_settings.txt")) as f:
+        for line in f:
+            parts = line.split()
+            if not parts or parts[0].startswith("#"):
+                continue
+            if parts[0] == "keep":
+                keeps.append((int(parts[1]), int(parts[2])))
+            else:
+                vals[parts[0]] = float(parts[1])
+    return vals, keeps
+
+
+def test_paper_detector_settings_and_sweep_sizes():
+    v, keeps = _paper_settings()
+    for n, k in keeps:                                    # 25 % of the paper's sweep sizes
+        assert ee.keep_count(v["select_ratio"], n) == k
+    # with the paper's settings a job whose two curves rise by more than tau_slope per evaluation leaves at the
+    # third evaluation (two windows of two values), one whose validation loss sits 11 % above training at the second
+    p = ee.Params(alpha=1.0, w=int(v["window"]), tau_slope=v["tau_slope"], tau_gap=v["tau_gap"],
+                  p_div=int(v["patience_div"]), p_ovf=int(v["patience_ovf"]))
+    st, _ = _run([1.000, 1.002, 1.004], [1.000, 1.002, 1.004], p)
+    assert st == [ee.CONTINUE, ee.CONTINUE, ee.DIVERGING]
+    st, _ = _run([1.0, 1.0], [1.11, 1.11], p)
+    assert st == [ee.CONTINUE, ee.OVERFITTING]
+    st, _ = _run([1.0, 1.0, 1.0], [1.09, 1.09, 1.09], p)
+    assert st == [0, 0, 0]
