@@ -215,6 +215,22 @@ def test_no_adapters_with_tokens(dtype):
     plan.destroy()
 
 
+def test_tall_and_thin_layer():
+    """200 000 rows through 64 x 72: many row tiles and row blocks, a single partial column tile, one segment of 150 000
+    tokens (its weight gradients are reduced from several chunks), an odd rank and the widest one."""
+    w = wl.make_workload("tall", "bf16", 64, 72, [8, 128, 3, 0], [150_000, 30_000, 19_999, 1], [2.0, 0.125, 1.0, 1.0],
+                         seed=55, b_sigma=0.3)
+    dl, _, _ = check_full(w)
+    assert dl.plan.geometry()[ml.GEO_USES_MFMA] == 1
+
+
+def test_few_tokens_through_a_large_weight():
+    """5 tokens through 8192 x 4096 (decode-like shape): one partial row tile, long contraction, 64 weight-gradient panels
+    of a 3-token and a 2-token segment."""
+    w = wl.make_workload("flat", "bf16", 8192, 4096, [16, 64], [3, 2], [1.0, 0.25], seed=56, b_sigma=0.3)
+    check_full(w)
+
+
 def test_single_token_segments():
     w = wl.make_workload("ones", "bf16", 256, 256, [4, 8, 16, 32, 5], [1, 1, 1, 1, 1],
                          [1.0, 2.0, 0.5, 0.25, 3.0], seed=53, b_sigma=0.3)
