@@ -77,6 +77,17 @@ __device__ __forceinline__ bf16x8 lds_read_frag_tr(const u16* p_lo, const u16* p
 
 __device__ __forceinline__ uint4 zero4() { return make_uint4(0u, 0u, 0u, 0u); }
 
+// 16-byte store / load with the non-temporal hint (data that is written once, or read once, by the kernel)
+typedef unsigned int u32x4v __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void store_streaming(void* dst, uint4 v) {
+    const u32x4v vv = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(vv, reinterpret_cast<u32x4v*>(dst));
+}
+__device__ __forceinline__ uint4 load_streaming(const void* src) {
+    const u32x4v v = __builtin_nontemporal_load(reinterpret_cast<const u32x4v*>(src));
+    return make_uint4(v[0], v[1], v[2], v[3]);
+}
+
 // 8 consecutive bf16 starting at p; the first `valid` (0..8) are read, the rest are zero.
 // `vec_ok` says p is 16-byte aligned (then a full chunk is one 128-bit load).
 __device__ __forceinline__ uint4 load_chunk(const u16* p, int valid, bool vec_ok) {

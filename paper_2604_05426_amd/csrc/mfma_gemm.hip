@@ -376,7 +376,10 @@ __global__ __launch_bounds__(NTHR) void fused_gemm_kernel(GemmArgs g) {
                                    __uint_as_float(nv[e] & 0xffff0000u) + __uint_as_float(ov[e] & 0xffff0000u));
                 v = make_uint4(res[0], res[1], res[2], res[3]);
             }
-            *reinterpret_cast<uint4*>(dst) = v;
+            // streaming store: the output is not read again by this kernel, and lines left dirty in the caches would be
+            // written back underneath the next, memory-bound kernel (dShrink after the forward, the weight gradients after
+            // the backward ran up to a third slower behind ordinary stores)
+            store_streaming(dst, v);
         }
     }
 }

@@ -308,7 +308,7 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradArgs g) {
             const int trow = (tid >> 4) + 16 * jj, cc = tid & 15;
             const int col = col0 + cc * 8;
             ra[set][jj] = (t0 + trow < rows && col < width)
-                              ? *reinterpret_cast<const uint4*>(big + (int64_t)(row0 + t0 + trow) * width + col) : zero4();
+                              ? load_streaming(big + (int64_t)(row0 + t0 + trow) * width + col) : zero4();
         }
 #pragma unroll
         for (int jj = 0; jj < MAXNB; ++jj) {
@@ -590,7 +590,7 @@ __global__ __launch_bounds__(256) void expand_add_kernel(ExpandArgs g) {
         const int rr = it * 8 + (lane >> 3), c = lane & 7;
         const int row = wr * 32 + rr, col = colw + c * 8;
         if (row >= rows || col >= g.Ncols) continue;
-        *reinterpret_cast<uint4*>(g.C + (int64_t)(row0 + row) * g.ldc + col) = *reinterpret_cast<const uint4*>(Es + rr * XE_LD + c * 8);
+        store_streaming(g.C + (int64_t)(row0 + row) * g.ldc + col, *reinterpret_cast<const uint4*>(Es + rr * XE_LD + c * 8));
     }
 }
 
