@@ -450,6 +450,7 @@ struct ExpandArgs {
     u16* C; int64_t ldc;     // Y [T,n] or dX [T,k]
     const u16* E;            // ragged S or dS
     int32_t Ncols, col_tiles;
+    int32_t stream_out;      // streaming stores for the output (outputs up to about the Infinity Cache size)
     const int32_t* list;     // row-block indices this launch covers (nullptr: all, in table order)
     PlanView pv;
 };
@@ -590,7 +591,10 @@ __global__ __launch_bounds__(256) void expand_add_kernel(ExpandArgs g) {
         const int rr = it * 8 + (lane >> 3), c = lane & 7;
         const int row = wr * 32 + rr, col = colw + c * 8;
         if (row >= rows || col >= g.Ncols) continue;
-        store_streaming(g.C + (int64_t)(row0 + row) * g.ldc + col, *reinterpret_cast<const uint4*>(Es + rr * XE_LD + c * 8));
+        const uint4 v = *reinterpret_cast<const uint4*>(Es + rr * XE_LD + c * 8);
+        u16* dst = g.C + (int64_t)(row0 + row) * g.ldc + col;
+        if (g.stream_out) store_streaming(dst, v);
+        else *reinterpret_cast<uint4*>(dst) = v;
     }
 }
 
@@ -606,6 +610,7 @@ static int launch_expand(mlora_plan* p, bool fwd, void* C, const void* E, hipStr
     a.Ncols = (int32_t)(fwd ? p->n : p->k);
     a.ldc = a.Ncols;
     a.col_tiles = (a.Ncols + XC - 1) / XC;
+    a.stream_out = (p->T * (int64_t)a.Ncols * 2 <= kStreamingStoreMaxBytes) ? 1 : 0;
     ProfScope prof(p, fwd ? MLORA_K_GEMM_FWD : MLORA_K_GEMM_BWD, st);
     auto go = [&](bool narrow, int32_t nblocks, const int32_t* list) {
         if (nblocks <= 0) return;
