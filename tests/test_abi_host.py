@@ -71,3 +71,20 @@ def test_plan_create_reports_errors_before_touching_the_gpu():
     assert L.multi_lora_workspace_bytes(None) == 0
     assert L.multi_lora_fwd(None, None, None, None, None, None, None, None, 0, None) == -1
     assert L.multi_lora_bwd(None, None, None, None, None, None, None, None, None, None, None, 0, None) == -1
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/multi_lora.h is a C header: it must compile as C99 on its own, with warnings as errors."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "multi_lora.h"\n'
+                   'int main(void) { mlora_monitor_params p; mlora_admission_params q; (void)p; (void)q;\n'
+                   '                 return multi_lora_plan_destroy(0) == MLORA_OK ? 0 : 1; }\n')
+    inc = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include")
+    r = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only", "-I", inc, str(src)],
+                       capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
