@@ -101,6 +101,26 @@ __device__ __forceinline__ uint4 load_chunk(const u16* p, int valid, bool vec_ok
     return make_uint4(w[0], w[1], w[2], w[3]);
 }
 
+// Same, with 64-bit pieces when p is 8-byte aligned (ranks that are multiples of 4 but not of 8).  For kernels that load a
+// chunk once per work item; the extra paths cost registers in a kernel that loads chunks in its inner loop.
+__device__ __forceinline__ uint4 load_chunk_a8(const u16* p, int valid, bool vec_ok) {
+    if (valid >= 8 && vec_ok) return *reinterpret_cast<const uint4*>(p);
+    if ((reinterpret_cast<uintptr_t>(p) & 7) != 0) return load_chunk(p, valid, false);
+    uint32_t w[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        if (valid >= 4 * h + 4) {
+            const uint2 v = *reinterpret_cast<const uint2*>(p + 4 * h);
+            w[2 * h] = v.x; w[2 * h + 1] = v.y;
+        } else {
+#pragma unroll
+            for (int e = 4 * h; e < 4 * h + 4; ++e)
+                if (e < valid) w[e >> 1] |= ((uint32_t)p[e]) << ((e & 1) * 16);
+        }
+    }
+    return make_uint4(w[0], w[1], w[2], w[3]);
+}
+
 __device__ __forceinline__ uint4 scale_chunk(uint4 v, float s) {
     uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll

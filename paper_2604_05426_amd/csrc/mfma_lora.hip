@@ -499,7 +499,7 @@ __global__ __launch_bounds__(256) void expand_add_kernel(ExpandArgs g) {
             const int row = wr * 32 + rb * 16 + l16, rho = ks * 32 + g4 * 8;
             sv[rb][ks] = zero4();
             if (ks < ksteps && row < rows && rho < r)
-                sv[rb][ks] = load_chunk(g.E + so + (int64_t)(row0 + row - seg0) * r + rho, min(8, r - rho), e_vec);
+                sv[rb][ks] = load_chunk_a8(g.E + so + (int64_t)(row0 + row - seg0) * r + rho, min(8, r - rho), e_vec);
         }
     // 3. the adapter matrix: fragments [16 columns][32 ranks], lane = (column l16, 8 ranks at 8 g4)
     uint4 fv[4][MAXKS];
@@ -539,7 +539,7 @@ __global__ __launch_bounds__(256) void expand_add_kernel(ExpandArgs g) {
                 const int col = colw + cb * 16 + l16, rho = ks * 32 + g4 * 8;
                 fv[cb][ks] = zero4();
                 if (ks < ksteps && col < g.Ncols && rho < r)
-                    fv[cb][ks] = load_chunk(F + (int64_t)col * r + rho, min(8, r - rho), f_vec);
+                    fv[cb][ks] = load_chunk_a8(F + (int64_t)col * r + rho, min(8, r - rho), f_vec);
             }
     }
 
