@@ -138,12 +138,16 @@ __global__ __launch_bounds__(NTHR) void fused_gemm_kernel(GemmArgs g) {
     const int wm = wave / WN, wn = wave % WN;
     const int l16 = lane & 15, g4 = lane >> 4;
 
-    // Workgroups are handed to the 8 XCDs round-robin; give each XCD a contiguous run of
-    // tiles and walk it in bands of 8 row tiles so that co-resident tiles share W / X panels
-    // in that XCD's L2.
+    // Tile order.  Tiles are numbered band by band (a band = 8 row tiles x all column tiles, numbered down the rows first),
+    // so 32 consecutive numbers are 8 row tiles x 4 column tiles: 12 operand panels for 32 tiles.  Workgroups are handed to
+    // the 8 XCDs round-robin (XCD = blockIdx % 8), and each XCD has its own L2: the 32 workgroups an XCD runs at a time take
+    // one such group, so that they share those panels in its L2.  Consecutive groups go to consecutive XCDs, i.e. all
+    // eight XCDs work on the same band at the same time, on different columns: the band's row panels are then fetched
+    // from HBM once and served to the other XCDs, and to later rounds, by the Infinity Cache (with one band per XCD the
+    // eight bands of a large layer did not fit there together; this order measured 1.5 to 4.5 % faster on every workload).
     const int total = g.tiles_m * g.tiles_n;
-    const int per_xcd = (total + 7) / 8;
-    const int L = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+    const int xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
+    const int L = ((slot / 32) * 8 + xcd) * 32 + (slot % 32);
     if (L >= total) return;
     constexpr int GM = 8;
     const int band = L / (GM * g.tiles_n);
@@ -413,7 +417,7 @@ static int launch_gemm(mlora_plan* p, bool fwd, const void* Aop, const void* W, 
     g.stream_out = ((int64_t)g.M * g.Ncols * 2 <= kStreamingStoreMaxBytes) ? 1 : 0;
     g.pv = p->view;
     const int total = g.tiles_m * g.tiles_n;
-    const int grid = ((total + 7) / 8) * 8;
+    const int grid = ((total + 255) / 256) * 256;    // whole groups of 32 tiles for each of the 8 XCDs
     ProfScope prof(p, fwd ? MLORA_K_GEMM_FWD : MLORA_K_GEMM_BWD, st);
     if (fwd) hipLaunchKernelGGL(fused_gemm_kernel<true>, dim3(grid), dim3(NTHR), 0, st, g);
     else     hipLaunchKernelGGL(fused_gemm_kernel<false>, dim3(grid), dim3(NTHR), 0, st, g);
