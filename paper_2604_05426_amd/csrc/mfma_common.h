@@ -77,8 +77,6 @@ __device__ __forceinline__ bf16x8 lds_read_frag_tr(const u16* p_lo, const u16* p
 
 __device__ __forceinline__ uint4 zero4() { return make_uint4(0u, 0u, 0u, 0u); }
 
-constexpr int64_t kStreamingStoreMaxBytes = (int64_t)384 << 20;   // outputs up to this size are written with streaming stores
-
 // 16-byte store / load with the non-temporal hint (data that is written once, or read once, by the kernel)
 typedef unsigned int u32x4v __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ void store_streaming(void* dst, uint4 v) {

@@ -409,12 +409,10 @@ static int launch_gemm(mlora_plan* p, bool fwd, const void* Aop, const void* W, 
     g.skip_base = (flags & MLORA_FLAG_LORA_ONLY) ? 1 : 0;
     g.skip_lora = ((flags & MLORA_FLAG_BASE_ONLY) || p->N == 0) ? 1 : 0;
     g.accumulate = g.skip_base;
-    // Streaming stores for outputs up to about the size of the 256 MB Infinity Cache: such an output would otherwise sit
-    // dirty in the caches when the kernel ends and be written back underneath the next kernel, which is always a
-    // memory-bound one (dShrink after the forward and the weight gradients after the backward ran up to a third slower).
-    // Larger outputs are written back during the GEMM anyway, and a GEMM whose operands stream from HBM measures up to
-    // 5 % slower with streaming stores, so those keep ordinary ones.
-    g.stream_out = ((int64_t)g.M * g.Ncols * 2 <= kStreamingStoreMaxBytes) ? 1 : 0;
+    // Streaming stores: an output written with ordinary stores sits dirty in the caches when the kernel ends and is
+    // written back underneath the next kernel, which is always a memory-bound one (dShrink after the forward and the
+    // weight gradients after the backward ran up to a third slower).
+    g.stream_out = 1;
     g.pv = p->view;
     const int total = g.tiles_m * g.tiles_n;
     const int grid = ((total + 255) / 256) * 256;    // whole groups of 32 tiles for each of the 8 XCDs

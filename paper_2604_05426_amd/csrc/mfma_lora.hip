@@ -450,7 +450,7 @@ struct ExpandArgs {
     u16* C; int64_t ldc;     // Y [T,n] or dX [T,k]
     const u16* E;            // ragged S or dS
     int32_t Ncols, col_tiles;
-    int32_t stream_out;      // streaming stores for the output (outputs up to about the Infinity Cache size)
+    int32_t stream_out;      // streaming stores for the output
     const int32_t* list;     // row-block indices this launch covers (nullptr: all, in table order)
     PlanView pv;
 };
@@ -610,7 +610,7 @@ static int launch_expand(mlora_plan* p, bool fwd, void* C, const void* E, hipStr
     a.Ncols = (int32_t)(fwd ? p->n : p->k);
     a.ldc = a.Ncols;
     a.col_tiles = (a.Ncols + XC - 1) / XC;
-    a.stream_out = (p->T * (int64_t)a.Ncols * 2 <= kStreamingStoreMaxBytes) ? 1 : 0;
+    a.stream_out = 1;
     ProfScope prof(p, fwd ? MLORA_K_GEMM_FWD : MLORA_K_GEMM_BWD, st);
     auto go = [&](bool narrow, int32_t nblocks, const int32_t* list) {
         if (nblocks <= 0) return;
