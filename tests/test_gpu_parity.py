@@ -231,6 +231,37 @@ def test_few_tokens_through_a_large_weight():
     check_full(w)
 
 
+def test_rank_padded_stacked_adapters_equal_true_rank_adapters():
+    """The paper's stacked layout (App. A.1: adapters of different ranks zero-padded to r_max in one [Z, k, r_max] /
+    [Z, r_max, n] pair of tensors) is served by declaring every adapter with rank r_max and pointing into the stacks: the
+    padding columns / rows are zero, so Y and dX equal the true-rank run, the gradients of the real entries equal the
+    true-rank gradients and the gradients of the padding of A are exactly zero where B's padding rows are zero."""
+    ranks, lens, scales = [8, 24, 64], [200, 77, 300], [2.0, 0.5, 1.0]
+    k, n, rmax = 256, 320, 64
+    w = wl.make_workload("true_rank", "bf16", k, n, ranks, lens, scales, seed=57, b_sigma=0.3)
+    ref = DeviceLayer(w); ref.forward(); ref.backward(); ref.sync()
+    dev = ref.device
+    A_stack = torch.zeros((3, k, rmax), dtype=torch.bfloat16, device=dev)
+    B_stack = torch.zeros((3, rmax, n), dtype=torch.bfloat16, device=dev)
+    for i, r in enumerate(ranks):
+        A_stack[i, :, :r] = ref.A[i]
+        B_stack[i, :r, :] = ref.B[i]
+    dA_stack, dB_stack = torch.full_like(A_stack, float("nan")), torch.full_like(B_stack, float("nan"))
+    plan = ml.Plan(ml.BF16, w.T, k, n, [rmax] * 3, scales, w.offsets)
+    Y, dX = torch.empty_like(ref.Y), torch.empty_like(ref.dX)
+    S = torch.empty(w.T * rmax, dtype=torch.bfloat16, device=dev)
+    ws = torch.zeros(max(plan.workspace_bytes(), 256), dtype=torch.uint8, device=dev)
+    A, B = [A_stack[i] for i in range(3)], [B_stack[i] for i in range(3)]
+    ml.multi_lora_fwd(plan, ref.X, ref.W, A, B, Y, S, ws)
+    ml.multi_lora_bwd(plan, ref.dY, ref.X, ref.W, A, B, S, dX, [dA_stack[i] for i in range(3)], [dB_stack[i] for i in range(3)], ws)
+    torch.cuda.synchronize()
+    assert torch.equal(Y, ref.Y) and torch.equal(dX, ref.dX)            # zero padding adds exact zeros
+    for i, r in enumerate(ranks):
+        assert torch.equal(dA_stack[i, :, :r], ref.dA[i]) and torch.equal(dB_stack[i, :r, :], ref.dB[i])
+        assert torch.all(dA_stack[i, :, r:] == 0)                        # dA = X^T (dY B^T): zero rows of B give zero columns
+    plan.destroy()
+
+
 def test_single_token_segments():
     w = wl.make_workload("ones", "bf16", 256, 256, [4, 8, 16, 32, 5], [1, 1, 1, 1, 1],
                          [1.0, 2.0, 0.5, 0.25, 3.0], seed=53, b_sigma=0.3)
