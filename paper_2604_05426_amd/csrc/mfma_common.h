@@ -48,6 +48,15 @@ __device__ __forceinline__ uint32_t pack2hw(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2v));
 }
 
+// Direct global -> LDS load of 16 bytes per lane: lane i's data lands at LDS byte address lds_base + 16 i
+// (lds_base is wavefront-uniform).  Issued through inline assembly so that the compiler's wait-count
+// insertion does not serialise later LDS reads behind it; the caller waits with an explicit vmcnt and a
+// barrier before anybody reads the data.
+// The global address is a wavefront-uniform base pointer plus a 32-bit per-lane byte offset.
+__device__ __forceinline__ void dma16(unsigned voff, const void* sbase, unsigned lds_base) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_base) : "memory", "m0");
+}
+
 // Swizzle key of contraction row k of a [contraction][column] LDS tile that is read with the transposing load
 // for 16x16x32 MFMA operands: the eight rows one such read touches per half-wavefront (k, k+1, k+2, k+3 and the
 // same plus 8) get eight different keys; rows k and k+4 share one (they belong to different read instructions).

@@ -47,14 +47,6 @@ static_assert(kGemmTileRows == BM && kGemmTileCols == BN, "plan geometry and ker
 
 typedef f32x4 f32x4v;
 
-// Direct global -> LDS load of 16 bytes per lane: lane i's data lands at LDS byte address lds_base + 16 i
-// (lds_base is wavefront-uniform).  Issued through inline assembly so that the compiler's wait-count
-// insertion does not serialise later LDS reads behind it; the caller waits with an explicit vmcnt and a
-// barrier before anybody reads the data.
-// The global address is a wavefront-uniform base pointer plus a 32-bit per-lane byte offset.
-__device__ __forceinline__ void dma16(unsigned voff, const void* sbase, unsigned lds_base) {
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_base) : "memory", "m0");
-}
 // all of this wavefront's direct loads and LDS accesses have completed; then the workgroup barrier
 __device__ __forceinline__ void wait_all_and_barrier() {
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");

@@ -219,12 +219,134 @@ __global__ __launch_bounds__(64 * SNW) void shrink_kernel(ShrinkArgs g) {
     else shrink_body<FWD, 2, 64, 2, 1>(g, e, lds);
 }
 
+// Wide ranks (65..128, multiples of 8; contraction a multiple of 64): for these rows the adapter matrix is the larger
+// stream (64 contraction steps x 128 ranks = 16 KB from L2 per 8 KB of X from HBM), and the build above, in which every
+// wavefront stages its own slice of it through registers, runs at half the narrow build's rate.  This kernel is tiled like
+// a GEMM instead: per 64-wide contraction step the work group shares one X / dY tile [64 rows][64] and one adapter tile
+// ([64][128] of A_i, read with the transposing load, or [128][64] of B_i), both brought in by direct global -> LDS loads
+// into a ring of six 24 KB stages (five steps of loads in flight, no staging registers, no LDS stores), one barrier per
+// step.  Wavefront w owns row block w & 3 and the rank half w >> 2 (four 16x16 accumulators) over the whole contraction,
+// so there is no cross-wavefront reduction and the result is deterministic.  Tiles are unpadded and XOR-swizzled as in the
+// fused GEMM: 128-byte rows keep chunk c of row t at c ^ (t & 7), the 256-byte rows of the A_i tile at c ^ (nn_swz(k) << 1).
+// Rows past the block and ranks past r_i are clamped to valid addresses; they only feed outputs that are not stored.
+constexpr int SW_NST = 6;
+constexpr int SW_XT = 8192, SW_STAGE = SW_XT + 16384;
+
+template <bool FWD>
+__global__ __launch_bounds__(64 * SNW) void shrink_wide_kernel(ShrinkArgs g) {
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[SW_NST * SW_STAGE];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l16 = lane & 15, g4 = lane >> 4;
+    const Entry4 e = g.pv.row_blocks[g.list[blockIdx.x]];
+    const int i = e.a, row0 = e.c, rows = e.d;
+    const int r = g.pv.rank[i];
+    const u16* F = (const u16*)(FWD ? g.pv.ptrs[i].A : g.pv.ptrs[i].B);
+    const float s = FWD ? 1.0f : g.pv.scale[i];
+
+    // per-lane byte offsets of the three direct loads this wavefront issues per step
+    unsigned voffX, voffF[2];
+    {
+        const int row = 8 * wave + (lane >> 3);
+        voffX = (unsigned)(((int64_t)min(row, rows - 1) * g.ld + (((lane & 7) ^ (lane >> 3)) << 3)) * 2);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            if (FWD) {     // A_i rows k0 + krow, 16 chunks of 8 ranks
+                const int krow = 4 * (2 * wave + j) + (lane >> 4);
+                const int chunk = min((lane & 15) ^ (nn_swz(krow) << 1), r / 8 - 1);
+                voffF[j] = (unsigned)((krow * r + chunk * 8) * 2);
+            } else {       // B_i rows rho, 8 chunks of 8 contraction elements
+                const int rho = 8 * (2 * wave + j) + (lane >> 3);
+                voffF[j] = (unsigned)(((int64_t)min(rho, r - 1) * g.ld + (((lane & 7) ^ (lane >> 3)) << 3)) * 2);
+            }
+        }
+    }
+    const int steps = g.Kdim / 64;
+    const char* baseX = reinterpret_cast<const char*>(g.src + (int64_t)row0 * g.ld);
+    const char* baseF = reinterpret_cast<const char*>(F);
+    const int64_t stepF = FWD ? (int64_t)64 * r * 2 : 128;
+    const unsigned lds0 = (unsigned)(uintptr_t)lds;
+    int issued = 0, slot_in = 0;          // next step to load and the ring slot it goes to
+    auto issue = [&]() {                  // past the last step the last one is loaded again (keeps the wait counts uniform)
+        const int t = min(issued, steps - 1);
+        const unsigned dst = lds0 + slot_in * SW_STAGE;
+        dma16(voffX, baseX + (int64_t)t * 128, dst + wave * 1024);
+        dma16(voffF[0], baseF + t * stepF, dst + SW_XT + (2 * wave) * 1024);
+        dma16(voffF[1], baseF + t * stepF, dst + SW_XT + (2 * wave + 1) * 1024);
+        ++issued;
+        slot_in = slot_in == SW_NST - 1 ? 0 : slot_in + 1;
+    };
+
+    const int rb = wave & 3, ch = wave >> 2;
+    f32x4 acc[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const int xrow = 16 * rb + l16;
+    const int vq = ((l16 >> 2) & 3) | ((g4 & 1) << 2);     // nn_swz of the A_i tile rows this lane reads
+    auto compute = [&](int slot) {
+        const unsigned char* Xs = lds + slot * SW_STAGE;
+        const unsigned char* Fs = Xs + SW_XT;
+#pragma unroll
+        for (int k32 = 0; k32 < 2; ++k32) {
+            const bf16x8 a = lds_read_frag(reinterpret_cast<const u16*>(Xs + xrow * 128 + (((k32 * 4 + g4) ^ (l16 & 7)) << 4)));
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int cb = ch * 4 + j;
+                if (cb * 16 >= r) continue;
+                bf16x8 b;
+                if (FWD) {
+                    const unsigned char* p = Fs + (k32 * 32 + 8 * g4 + (l16 >> 2)) * 256 + ((cb ^ vq) << 5) + (l16 & 3) * 8;
+                    b = lds_read_frag_tr(reinterpret_cast<const u16*>(p), reinterpret_cast<const u16*>(p + 4 * 256));
+                } else {
+                    const int rho = 16 * cb + l16;
+                    b = lds_read_frag(reinterpret_cast<const u16*>(Fs + rho * 128 + (((k32 * 4 + g4) ^ (l16 & 7)) << 4)));
+                }
+                acc[j] = mfma16(a, b, acc[j]);
+            }
+        }
+    };
+
+    for (int t = 0; t < SW_NST - 1; ++t) issue();
+    int slot = 0;
+    for (int t = 0; t < steps; ++t) {
+        // step t has landed (only the loads of the SW_NST - 2 later steps may be in flight) and every wavefront is past
+        // step t-1, whose slot the next load overwrites
+        asm volatile("s_waitcnt vmcnt(12)\n\ts_barrier" ::: "memory");
+        static_assert(3 * (SW_NST - 2) == 12, "wait count = loads of the steps that may still be in flight");
+        issue();
+        compute(slot);
+        slot = slot == SW_NST - 1 ? 0 : slot + 1;
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // no load may still be writing LDS when the work group ends
+
+    // lane (l16, g4) holds rows 16 rb + 4 g4 + i, rank 16 cb + l16
+    const int64_t so = g.pv.soff[i];
+    const int seg0 = g.pv.off[i];
+    u16* out = g.out + so + (int64_t)(row0 - seg0) * r;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int rank = 16 * (ch * 4 + j) + l16;
+        if (rank >= r) continue;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int row = 16 * rb + 4 * g4 + q;
+            if (row < rows) out[(int64_t)row * r + rank] = f2bf(s * acc[j][q]);
+        }
+    }
+}
+
 template <bool FWD>
 static void launch_shrink(mlora_plan* p, ShrinkArgs a, hipStream_t st) {
     const dim3 grid(p->n_row_blocks), block(64 * SNW);
     if (p->n_blocks_wide == 0) {
         a.list = nullptr;
         hipLaunchKernelGGL((shrink_kernel<FWD, false>), grid, block, 0, st, a);
+    } else if (p->n_blocks_narrow == 0 && p->wide_ranks_mult8 && a.Kdim >= 64 && a.Kdim % 64 == 0 && a.ld <= ((int64_t)1 << 22)) {
+        // every row block is a wide one: the tiled kernel (32-bit lane offsets: rows of at most 2^22 elements).  Plans that
+        // mix the classes keep the single launch below: two launches of kernels that each want a whole CU's LDS measured
+        // slower there, overlapped or not.
+        a.list = p->d_block_lists;
+        hipLaunchKernelGGL((shrink_wide_kernel<FWD>), dim3(p->n_blocks_wide), block, 0, st, a);
     } else {
         a.list = p->d_block_lists;
         hipLaunchKernelGGL((shrink_kernel<FWD, true>), grid, block, 0, st, a);

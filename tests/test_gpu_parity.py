@@ -262,6 +262,15 @@ def test_rank_padded_stacked_adapters_equal_true_rank_adapters():
     plan.destroy()
 
 
+@pytest.mark.parametrize("ranks,lens,k,n", [((128, 72, 96), (300, 64, 131), 256, 320), ((80,), (1,), 64, 64),
+                                             ((128, 128), (700, 65), 1024, 192)])
+def test_plans_with_only_wide_ranks(ranks, lens, k, n):
+    """All ranks in 65..128 and multiples of 8, widths multiples of 64: the shrink kernels take the GEMM-tiled build
+    (shared X / adapter tiles in a ring of direct global -> LDS loads); partial row blocks, ranks below 128."""
+    w = wl.make_workload("wide_only", "bf16", k, n, list(ranks), list(lens), [0.5] * len(ranks), seed=58, b_sigma=0.3)
+    check_full(w)
+
+
 def test_single_token_segments():
     w = wl.make_workload("ones", "bf16", 256, 256, [4, 8, 16, 32, 5], [1, 1, 1, 1, 1],
                          [1.0, 2.0, 0.5, 0.25, 3.0], seed=53, b_sigma=0.3)
