@@ -84,7 +84,7 @@ struct mlora_plan {
     // overlap (the wide class on aux_stream, forked from and joined to the caller's stream with the two events), each
     // through the kernel build - and so at the workgroups per CU - its class allows.
     int32_t max_rank_narrow = 0;      // largest rank <= 64 among adapters with tokens
-    bool wide_ranks_mult8 = true;     // every rank > 64 of an adapter with tokens is a multiple of 8
+    bool ranks_mult8 = true;          // every rank of an adapter with tokens is a multiple of 8
     bool wgrad_two_classes = false;
     hipStream_t aux_stream = nullptr;
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;

@@ -48,6 +48,13 @@ __device__ __forceinline__ uint32_t pack2hw(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2v));
 }
 
+// A pointer the compiler may keep in vector registers although it is the same in every lane, moved to scalar registers.
+__device__ __forceinline__ const char* uniform_ptr(const void* p) {
+    const uint64_t v = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return reinterpret_cast<const char*>(((uint64_t)hi << 32) | lo);
+}
+
 // Direct global -> LDS load of 16 bytes per lane: lane i's data lands at LDS byte address lds_base + 16 i
 // (lds_base is wavefront-uniform).  Issued through inline assembly so that the compiler's wait-count
 // insertion does not serialise later LDS reads behind it; the caller waits with an explicit vmcnt and a

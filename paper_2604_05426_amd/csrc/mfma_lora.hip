@@ -219,84 +219,95 @@ __global__ __launch_bounds__(64 * SNW) void shrink_kernel(ShrinkArgs g) {
     else shrink_body<FWD, 2, 64, 2, 1>(g, e, lds);
 }
 
-// Wide ranks (65..128, multiples of 8; contraction a multiple of 64): for these rows the adapter matrix is the larger
-// stream (64 contraction steps x 128 ranks = 16 KB from L2 per 8 KB of X from HBM), and the build above, in which every
-// wavefront stages its own slice of it through registers, runs at half the narrow build's rate.  This kernel is tiled like
-// a GEMM instead: per 64-wide contraction step the work group shares one X / dY tile [64 rows][64] and one adapter tile
-// ([64][128] of A_i, read with the transposing load, or [128][64] of B_i), both brought in by direct global -> LDS loads
-// into a ring of six 24 KB stages (five steps of loads in flight, no staging registers, no LDS stores), one barrier per
-// step.  Wavefront w owns row block w & 3 and the rank half w >> 2 (four 16x16 accumulators) over the whole contraction,
-// so there is no cross-wavefront reduction and the result is deterministic.  Tiles are unpadded and XOR-swizzled as in the
-// fused GEMM: 128-byte rows keep chunk c of row t at c ^ (t & 7), the 256-byte rows of the A_i tile at c ^ (nn_swz(k) << 1).
-// Rows past the block and ranks past r_i are clamped to valid addresses; they only feed outputs that are not stored.
-constexpr int SW_NST = 6;
-constexpr int SW_XT = 8192, SW_STAGE = SW_XT + 16384;
+// GEMM-tiled shrink / dShrink, used when the contraction is a multiple of 64 and (shrink only) every rank a multiple of 8.
+// Per 64-wide contraction step the work group shares one X / dY tile [64 rows][64] and one adapter tile (of A_i, read
+// with the transposing load, or of B_i), both brought in by direct global -> LDS loads into a ring of stages (no staging
+// registers, no LDS stores, the loads of all but the current step in flight), one barrier per step.  Every output block
+// is accumulated by one wavefront over the whole contraction, so there is no cross-wavefront reduction and the result is
+// deterministic.  RB16 = 16-wide rank blocks the body is built for:
+//   4 (ranks <= 64): adapter tile 8 KB, nine 16 KB stages; wavefront w owns row block w & 3 and rank blocks 2 (w >> 2) + {0, 1};
+//   8 (ranks <= 128): adapter tile 16 KB, six 24 KB stages; wavefront w owns row block w & 3 and rank blocks 4 (w >> 2) + {0..3}.
+// Against the register-staged builds above it keeps more bytes in flight with an eighth of the registers, has no LDS stores
+// and no reduction epilogue: 8 x 2048 tokens, k = 4096: rank 16 forward 41 -> 33 us, rank 128 68 -> 51 us.
+// Tiles are unpadded and XOR-swizzled as in the fused GEMM: 128-byte rows of a tile read along its rows keep chunk c of row t
+// at c ^ (t & 7); the A_i tile [k][ranks], read with the transposing load, keeps 32-byte unit u of row k at u ^ nn_swz(k)
+// (256-byte rows) or u ^ (((k >> 1) & 1) | (((k >> 3) & 1) << 1)) (128-byte rows).  Rows past the block and ranks past r_i
+// are clamped to valid addresses; they only feed outputs that are not stored.
+constexpr int ST_XT = 8192;     // X / dY tile bytes
 
-template <bool FWD>
-__global__ __launch_bounds__(64 * SNW) void shrink_wide_kernel(ShrinkArgs g) {
-    __shared__ __attribute__((aligned(1024))) unsigned char lds[SW_NST * SW_STAGE];
+template <bool FWD, int RB16>
+__device__ __forceinline__ void shrink_tiled_body(const ShrinkArgs& g, const Entry4 e, unsigned char* lds) {
+    constexpr int FT = RB16 * 2048;                 // adapter tile bytes
+    constexpr int STAGE = ST_XT + FT;
+    constexpr int NST = RB16 == 8 ? 6 : 9;          // ring stages (144 KB either way)
+    constexpr int NF = RB16 / 4;                    // adapter-tile loads per wavefront per step
+    constexpr int NCB = RB16 / 2;                   // rank blocks per wavefront
+    constexpr int FROW = RB16 * 32;                 // FWD: bytes per contraction row of the A_i tile
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l16 = lane & 15, g4 = lane >> 4;
-    const Entry4 e = g.pv.row_blocks[g.list[blockIdx.x]];
     const int i = e.a, row0 = e.c, rows = e.d;
     const int r = g.pv.rank[i];
     const u16* F = (const u16*)(FWD ? g.pv.ptrs[i].A : g.pv.ptrs[i].B);
     const float s = FWD ? 1.0f : g.pv.scale[i];
+    // swizzle key of contraction row k of the A_i tile
+    auto fkey = [](int k) { return RB16 == 8 ? nn_swz(k) : (((k >> 1) & 1) | (((k >> 3) & 1) << 1)); };
 
-    // per-lane byte offsets of the three direct loads this wavefront issues per step
-    unsigned voffX, voffF[2];
+    // per-lane byte offsets of the direct loads this wavefront issues per step
+    unsigned voffX, voffF[NF];
     {
         const int row = 8 * wave + (lane >> 3);
         voffX = (unsigned)(((int64_t)min(row, rows - 1) * g.ld + (((lane & 7) ^ (lane >> 3)) << 3)) * 2);
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            if (FWD) {     // A_i rows k0 + krow, 16 chunks of 8 ranks
-                const int krow = 4 * (2 * wave + j) + (lane >> 4);
-                const int chunk = min((lane & 15) ^ (nn_swz(krow) << 1), r / 8 - 1);
+        for (int j = 0; j < NF; ++j) {
+            const int kb = NF * wave + j;        // 1 KB piece of the adapter tile
+            if (FWD) {     // piece = 1024 / FROW contraction rows of FROW bytes
+                constexpr int LPR = FROW / 16;   // lanes (16-byte chunks) per row
+                const int krow = kb * (64 / LPR) + lane / LPR, pos = lane % LPR;
+                const int chunk = min((((pos >> 1) ^ fkey(krow)) << 1) | (pos & 1), r / 8 - 1);
                 voffF[j] = (unsigned)((krow * r + chunk * 8) * 2);
-            } else {       // B_i rows rho, 8 chunks of 8 contraction elements
-                const int rho = 8 * (2 * wave + j) + (lane >> 3);
+            } else {       // piece = 8 rank rows of 128 bytes
+                const int rho = 8 * kb + (lane >> 3);
                 voffF[j] = (unsigned)(((int64_t)min(rho, r - 1) * g.ld + (((lane & 7) ^ (lane >> 3)) << 3)) * 2);
             }
         }
     }
     const int steps = g.Kdim / 64;
-    const char* baseX = reinterpret_cast<const char*>(g.src + (int64_t)row0 * g.ld);
-    const char* baseF = reinterpret_cast<const char*>(F);
-    const int64_t stepF = FWD ? (int64_t)64 * r * 2 : 128;
+    const char* baseX = uniform_ptr(g.src + (int64_t)row0 * g.ld);
+    const char* baseF = uniform_ptr(F);
+    const int64_t stepF = FWD ? (int64_t)64 * __builtin_amdgcn_readfirstlane(r) * 2 : 128;
     const unsigned lds0 = (unsigned)(uintptr_t)lds;
     int issued = 0, slot_in = 0;          // next step to load and the ring slot it goes to
     auto issue = [&]() {                  // past the last step the last one is loaded again (keeps the wait counts uniform)
         const int t = min(issued, steps - 1);
-        const unsigned dst = lds0 + slot_in * SW_STAGE;
+        const unsigned dst = lds0 + slot_in * STAGE;
         dma16(voffX, baseX + (int64_t)t * 128, dst + wave * 1024);
-        dma16(voffF[0], baseF + t * stepF, dst + SW_XT + (2 * wave) * 1024);
-        dma16(voffF[1], baseF + t * stepF, dst + SW_XT + (2 * wave + 1) * 1024);
+#pragma unroll
+        for (int j = 0; j < NF; ++j) dma16(voffF[j], baseF + t * stepF, dst + ST_XT + (NF * wave + j) * 1024);
         ++issued;
-        slot_in = slot_in == SW_NST - 1 ? 0 : slot_in + 1;
+        slot_in = slot_in == NST - 1 ? 0 : slot_in + 1;
     };
 
     const int rb = wave & 3, ch = wave >> 2;
-    f32x4 acc[4];
+    f32x4 acc[NCB];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int j = 0; j < NCB; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
     const int xrow = 16 * rb + l16;
-    const int vq = ((l16 >> 2) & 3) | ((g4 & 1) << 2);     // nn_swz of the A_i tile rows this lane reads
+    const int vq = fkey(8 * g4 + (l16 >> 2));      // key of the A_i tile rows this lane reads (rows +4, +32 share it)
     auto compute = [&](int slot) {
-        const unsigned char* Xs = lds + slot * SW_STAGE;
-        const unsigned char* Fs = Xs + SW_XT;
+        const unsigned char* Xs = lds + slot * STAGE;
+        const unsigned char* Fs = Xs + ST_XT;
 #pragma unroll
         for (int k32 = 0; k32 < 2; ++k32) {
             const bf16x8 a = lds_read_frag(reinterpret_cast<const u16*>(Xs + xrow * 128 + (((k32 * 4 + g4) ^ (l16 & 7)) << 4)));
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int cb = ch * 4 + j;
+            for (int j = 0; j < NCB; ++j) {
+                const int cb = ch * NCB + j;
                 if (cb * 16 >= r) continue;
                 bf16x8 b;
                 if (FWD) {
-                    const unsigned char* p = Fs + (k32 * 32 + 8 * g4 + (l16 >> 2)) * 256 + ((cb ^ vq) << 5) + (l16 & 3) * 8;
-                    b = lds_read_frag_tr(reinterpret_cast<const u16*>(p), reinterpret_cast<const u16*>(p + 4 * 256));
+                    const unsigned char* p = Fs + (k32 * 32 + 8 * g4 + (l16 >> 2)) * FROW + ((cb ^ vq) << 5) + (l16 & 3) * 8;
+                    b = lds_read_frag_tr(reinterpret_cast<const u16*>(p), reinterpret_cast<const u16*>(p + 4 * FROW));
                 } else {
                     const int rho = 16 * cb + l16;
                     b = lds_read_frag(reinterpret_cast<const u16*>(Fs + rho * 128 + (((k32 * 4 + g4) ^ (l16 & 7)) << 4)));
@@ -306,26 +317,27 @@ __global__ __launch_bounds__(64 * SNW) void shrink_wide_kernel(ShrinkArgs g) {
         }
     };
 
-    for (int t = 0; t < SW_NST - 1; ++t) issue();
+    for (int t = 0; t < NST - 1; ++t) issue();
     int slot = 0;
     for (int t = 0; t < steps; ++t) {
-        // step t has landed (only the loads of the SW_NST - 2 later steps may be in flight) and every wavefront is past
+        // step t has landed (only the loads of the NST - 2 later steps may be in flight) and every wavefront is past
         // step t-1, whose slot the next load overwrites
-        asm volatile("s_waitcnt vmcnt(12)\n\ts_barrier" ::: "memory");
-        static_assert(3 * (SW_NST - 2) == 12, "wait count = loads of the steps that may still be in flight");
+        if (RB16 == 8) asm volatile("s_waitcnt vmcnt(12)\n\ts_barrier" ::: "memory");
+        else           asm volatile("s_waitcnt vmcnt(14)\n\ts_barrier" ::: "memory");
+        static_assert((1 + NF) * (NST - 2) == (RB16 == 8 ? 12 : 14), "wait count = loads of the steps that may still be in flight");
         issue();
         compute(slot);
-        slot = slot == SW_NST - 1 ? 0 : slot + 1;
+        slot = slot == NST - 1 ? 0 : slot + 1;
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // no load may still be writing LDS when the work group ends
 
-    // lane (l16, g4) holds rows 16 rb + 4 g4 + i, rank 16 cb + l16
+    // lane (l16, g4) holds rows 16 rb + 4 g4 + q, rank 16 cb + l16
     const int64_t so = g.pv.soff[i];
     const int seg0 = g.pv.off[i];
     u16* out = g.out + so + (int64_t)(row0 - seg0) * r;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int rank = 16 * (ch * 4 + j) + l16;
+    for (int j = 0; j < NCB; ++j) {
+        const int rank = 16 * (ch * NCB + j) + l16;
         if (rank >= r) continue;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
@@ -335,21 +347,43 @@ __global__ __launch_bounds__(64 * SNW) void shrink_wide_kernel(ShrinkArgs g) {
     }
 }
 
+// WIDE: the launch may contain row blocks of adapters with ranks above 64.  MIXED: it may contain adapters whose rank is
+// not a multiple of 8 (forward form only); those row blocks take the register-staged body.  Uniform branches per work group.
+template <bool FWD, bool WIDE, bool MIXED>
+__global__ __launch_bounds__(64 * SNW) void shrink_tiled_kernel(ShrinkArgs g) {
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[MIXED ? 163840 : 147456];
+    const Entry4 e = g.pv.row_blocks[g.list ? g.list[blockIdx.x] : (int)blockIdx.x];
+    const int r = g.pv.rank[e.a];
+    if (MIXED && (r & 7) != 0) {
+        u16* l16p = reinterpret_cast<u16*>(lds);
+        if (WIDE && r > 64) shrink_body<FWD, 4, 32, 2, 1>(g, e, l16p);
+        else shrink_body<FWD, 2, 64, 2, 1>(g, e, l16p);
+    } else if (WIDE && r > 64) {
+        shrink_tiled_body<FWD, 8>(g, e, lds);
+    } else {
+        shrink_tiled_body<FWD, 4>(g, e, lds);
+    }
+}
+
 template <bool FWD>
 static void launch_shrink(mlora_plan* p, ShrinkArgs a, hipStream_t st) {
     const dim3 grid(p->n_row_blocks), block(64 * SNW);
-    if (p->n_blocks_wide == 0) {
-        a.list = nullptr;
-        hipLaunchKernelGGL((shrink_kernel<FWD, false>), grid, block, 0, st, a);
-    } else if (p->n_blocks_narrow == 0 && p->wide_ranks_mult8 && a.Kdim >= 64 && a.Kdim % 64 == 0 && a.ld <= ((int64_t)1 << 22)) {
-        // every row block is a wide one: the tiled kernel (32-bit lane offsets: rows of at most 2^22 elements).  Plans that
-        // mix the classes keep the single launch below: two launches of kernels that each want a whole CU's LDS measured
-        // slower there, overlapped or not.
-        a.list = p->d_block_lists;
-        hipLaunchKernelGGL((shrink_wide_kernel<FWD>), dim3(p->n_blocks_wide), block, 0, st, a);
+    a.list = p->n_blocks_wide == 0 ? nullptr : p->d_block_lists;      // wide blocks first when there are any
+    // the tiled kernels address rows with 32-bit lane offsets: rows of at most 2^22 elements
+    const bool tiled = a.Kdim >= 64 && a.Kdim % 64 == 0 && a.ld <= ((int64_t)1 << 22);
+    const bool wide = p->n_blocks_wide != 0;
+    // (the forward form reads A_i in 16-byte chunks of a rank row: row blocks of adapters whose rank is not a multiple of 8
+    // keep the register-staged body; B_i is read along its rows, any rank will do)
+    const bool mixed = FWD && !p->ranks_mult8;
+    if (tiled && !mixed) {
+        if (!wide) hipLaunchKernelGGL((shrink_tiled_kernel<FWD, false, false>), grid, block, 0, st, a);
+        else       hipLaunchKernelGGL((shrink_tiled_kernel<FWD, true, false>), grid, block, 0, st, a);
+    } else if (tiled) {
+        if (!wide) hipLaunchKernelGGL((shrink_tiled_kernel<FWD, false, true>), grid, block, 0, st, a);
+        else       hipLaunchKernelGGL((shrink_tiled_kernel<FWD, true, true>), grid, block, 0, st, a);
     } else {
-        a.list = p->d_block_lists;
-        hipLaunchKernelGGL((shrink_kernel<FWD, true>), grid, block, 0, st, a);
+        if (!wide) hipLaunchKernelGGL((shrink_kernel<FWD, false>), grid, block, 0, st, a);
+        else       hipLaunchKernelGGL((shrink_kernel<FWD, true>), grid, block, 0, st, a);
     }
 }
 

@@ -301,7 +301,8 @@ static int plan_create_impl(mlora_plan** out, int dtype, int64_t T, int64_t k, i
         bool wide = false;
         for (int32_t i = 0; i < N; ++i) {
             if (p->off[i + 1] == p->off[i] || ranks[i] == 0) continue;
-            if (ranks[i] > 64) { wide = true; if (ranks[i] % 8) p->wide_ranks_mult8 = false; }
+            if (ranks[i] % 8) p->ranks_mult8 = false;
+            if (ranks[i] > 64) wide = true;
             else if (ranks[i] > p->max_rank_narrow) p->max_rank_narrow = ranks[i];
         }
         p->wgrad_two_classes = wide && p->max_rank_narrow > 0;
