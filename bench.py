@@ -302,6 +302,7 @@ def main() -> int:
         prof = os.path.join(ROOT, "profiles", "bench_config2_pmc_traffic_mfma.md")
         if args.config == 2 and os.path.exists(prof):
             names = {"fused_gemm_kernel<true>": "gemm_fwd", "fused_gemm_kernel<false>": "gemm_bwd",
+                     "shrink_tiled_kernel<true": "shrink", "shrink_tiled_kernel<false": "dshrink",
                      "shrink_kernel<true": "shrink", "shrink_kernel<false": "dshrink", "wgrad_kernel": "wgrad"}
             for line in open(prof):
                 parts = line.split()
