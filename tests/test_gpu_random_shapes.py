@@ -1,4 +1,4 @@
-"""Seeded random layers against the oracle: widths that are and are not multiples of 8 (MFMA and FMA kernels), ranks
+"""Seeded random layers against the oracle: widths that are and are not multiples of 8 (MFMA and FMA kernels) and of 64, ranks
 from 0 to 128 including odd ones and the class boundaries, segment lengths around the 64-row block and 256-row tile
 boundaries including empty ones, in the fused mode, the decoupled mode (frozen-weight pass, then LoRA-only pass in
 place) and with gradient accumulation."""
@@ -14,13 +14,16 @@ from util import rel_fro
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("block", range(4))
+@pytest.mark.parametrize("block", range(6))
 def test_random_layers(block):
     for case in range(block * 12, block * 12 + 12):
         rng = np.random.default_rng(9000 + case)
         dtype = "bf16" if rng.random() < 0.8 else "f32"
-        k = int(rng.integers(1, 200)) * 8 if rng.random() < 0.85 else int(rng.integers(1, 300))
-        n = int(rng.integers(1, 200)) * 8 if rng.random() < 0.85 else int(rng.integers(1, 300))
+        if block >= 4:      # widths that are multiples of 64: the shrink kernels take their tiled form
+            k, n = int(rng.integers(1, 30)) * 64, int(rng.integers(1, 30)) * 64
+        else:
+            k = int(rng.integers(1, 200)) * 8 if rng.random() < 0.85 else int(rng.integers(1, 300))
+            n = int(rng.integers(1, 200)) * 8 if rng.random() < 0.85 else int(rng.integers(1, 300))
         N = int(rng.integers(1, 7))
         ranks = [int(rng.choice([0, 1, 3, 4, 8, 16, 24, 32, 40, 64, 65, 96, 100, 128])) for _ in range(N)]
         lens = [int(rng.choice([0, 1, 2, 63, 64, 65, 127, 255, 256, 257, 300, 700, 1500])) for _ in range(N)]
