@@ -235,8 +235,9 @@ __global__ __launch_bounds__(64 * SNW) void shrink_kernel(ShrinkArgs g) {
 // are clamped to valid addresses; they only feed outputs that are not stored.
 constexpr int ST_XT = 8192;     // X / dY tile bytes
 
-template <bool FWD, int RB16>
+template <bool FWD, int RB16, bool DENSE = false>
 __device__ __forceinline__ void shrink_tiled_body(const ShrinkArgs& g, const Entry4 e, unsigned char* lds) {
+    static_assert(FWD || !DENSE, "the dense adapter tile is a layout of A_i");
     constexpr int FT = RB16 * 2048;                 // adapter tile bytes
     constexpr int STAGE = ST_XT + FT;
     constexpr int NST = RB16 == 8 ? 6 : 9;          // ring stages (144 KB either way)
@@ -261,7 +262,9 @@ __device__ __forceinline__ void shrink_tiled_body(const ShrinkArgs& g, const Ent
 #pragma unroll
         for (int j = 0; j < NF; ++j) {
             const int kb = NF * wave + j;        // 1 KB piece of the adapter tile
-            if (FWD) {     // piece = 1024 / FROW contraction rows of FROW bytes
+            if (DENSE) {   // the step's 64 rows of A_i are 128 r contiguous bytes: copied as they are
+                voffF[j] = (unsigned)min(kb * 1024 + lane * 16, 128 * r - 16);
+            } else if (FWD) {     // piece = 1024 / FROW contraction rows of FROW bytes
                 constexpr int LPR = FROW / 16;   // lanes (16-byte chunks) per row
                 const int krow = kb * (64 / LPR) + lane / LPR, pos = lane % LPR;
                 const int chunk = min((((pos >> 1) ^ fkey(krow)) << 1) | (pos & 1), r / 8 - 1);
@@ -305,7 +308,11 @@ __device__ __forceinline__ void shrink_tiled_body(const ShrinkArgs& g, const Ent
                 const int cb = ch * NCB + j;
                 if (cb * 16 >= r) continue;
                 bf16x8 b;
-                if (FWD) {
+                if (DENSE) {   // rows of 2 r bytes, unswizzled; a lane past r_i reads ranks 0..3 again (output not stored)
+                    const int rk = 16 * cb + (l16 & 3) * 4;
+                    const unsigned char* p = Fs + (k32 * 32 + 8 * g4 + (l16 >> 2)) * (2 * r) + (rk < r ? rk * 2 : 0);
+                    b = lds_read_frag_tr(reinterpret_cast<const u16*>(p), reinterpret_cast<const u16*>(p + 8 * r));
+                } else if (FWD) {
                     const unsigned char* p = Fs + (k32 * 32 + 8 * g4 + (l16 >> 2)) * FROW + ((cb ^ vq) << 5) + (l16 & 3) * 8;
                     b = lds_read_frag_tr(reinterpret_cast<const u16*>(p), reinterpret_cast<const u16*>(p + 4 * FROW));
                 } else {
@@ -348,13 +355,18 @@ __device__ __forceinline__ void shrink_tiled_body(const ShrinkArgs& g, const Ent
 }
 
 // WIDE: the launch may contain row blocks of adapters with ranks above 64.  MIXED: it may contain adapters whose rank is
-// not a multiple of 8 (forward form only); those row blocks take the register-staged body.  Uniform branches per work group.
+// not a multiple of 8 (forward form only): a rank that is a multiple of 4 takes the tiled body with the adapter tile kept
+// dense in LDS (rows of 2 r bytes: 8-byte granules, which is what one lane of the transposing load reads), any other rank
+// the register-staged body.  Uniform branches per work group.
 template <bool FWD, bool WIDE, bool MIXED>
 __global__ __launch_bounds__(64 * SNW) void shrink_tiled_kernel(ShrinkArgs g) {
     __shared__ __attribute__((aligned(1024))) unsigned char lds[MIXED ? 163840 : 147456];
     const Entry4 e = g.pv.row_blocks[g.list ? g.list[blockIdx.x] : (int)blockIdx.x];
     const int r = g.pv.rank[e.a];
-    if (MIXED && (r & 7) != 0) {
+    if (MIXED && FWD && (r & 7) == 4) {
+        if (WIDE && r > 64) shrink_tiled_body<FWD, 8, FWD>(g, e, lds);
+        else shrink_tiled_body<FWD, 4, FWD>(g, e, lds);
+    } else if (MIXED && (r & 7) != 0) {
         u16* l16p = reinterpret_cast<u16*>(lds);
         if (WIDE && r > 64) shrink_body<FWD, 4, 32, 2, 1>(g, e, l16p);
         else shrink_body<FWD, 2, 64, 2, 1>(g, e, l16p);
@@ -448,6 +460,9 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradArgs g) {
     const u16* small = (isA ? g.dS : g.S) + so + (int64_t)(row0 - seg0) * r;
     const int col0 = panel * WP;
     const bool s_vec = ((r & 7) == 0) && ((so & 7) == 0);
+    // ranks that are multiples of 4 but not of 8: 8-byte halves of a chunk, loaded straight into the prefetch registers
+    // (the element-wise path combines what it loads at once, which would make every step wait for its own loads)
+    const bool s_v8 = !s_vec && ((r & 3) == 0) && ((so & 3) == 0) && ((reinterpret_cast<uintptr_t>(isA ? g.dS : g.S) & 7) == 0);
 
     f32x16 acc[MAXNB];
 #pragma unroll
@@ -470,8 +485,19 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradArgs g) {
         for (int jj = 0; jj < MAXNB; ++jj) {
             const int idx = tid + 256 * jj, trow = idx / CPRS, cc = idx % CPRS;
             rb[set][jj] = zero4();
-            if (t0 + trow < rows && cc * 8 < r)
-                rb[set][jj] = load_chunk(small + (int64_t)(t0 + trow) * r + cc * 8, min(8, r - cc * 8), s_vec);
+            if (t0 + trow < rows && cc * 8 < r) {
+                const u16* ps = small + (int64_t)(t0 + trow) * r + cc * 8;
+                if (s_v8) {
+                    const uint2 lo = *reinterpret_cast<const uint2*>(ps);
+                    rb[set][jj].x = lo.x; rb[set][jj].y = lo.y;
+                    if (r - cc * 8 >= 8) {
+                        const uint2 hi = *reinterpret_cast<const uint2*>(ps + 4);
+                        rb[set][jj].z = hi.x; rb[set][jj].w = hi.y;
+                    }
+                } else {
+                    rb[set][jj] = load_chunk(ps, min(8, r - cc * 8), s_vec);
+                }
+            }
         }
     };
     auto lstore = [&](int stage, int set) {

@@ -271,6 +271,17 @@ def test_plans_with_only_wide_ranks(ranks, lens, k, n):
     check_full(w)
 
 
+@pytest.mark.parametrize("ranks,lens,k,n", [((4, 12, 20, 36, 60, 8, 5), (300, 64, 131, 70, 129, 65, 40), 256, 320),
+                                             ((4,), (1,), 64, 64),
+                                             ((68, 100, 124, 4, 16), (130, 65, 200, 90, 64), 1024, 192)])
+def test_ranks_that_are_multiples_of_4_but_not_of_8(ranks, lens, k, n):
+    """Rows of such an A_i are 8-byte, not 16-byte, granular: the forward shrink keeps their adapter tile dense in LDS
+    and the weight-gradient kernel loads their S / dS rows in 8-byte halves; mixed with ranks that take the other
+    builds (multiples of 8, an odd rank) in one launch, narrow and wide."""
+    w = wl.make_workload("rank_mod8_is_4", "bf16", k, n, list(ranks), list(lens), [0.5] * len(ranks), seed=59, b_sigma=0.3)
+    check_full(w)
+
+
 def test_single_token_segments():
     w = wl.make_workload("ones", "bf16", 256, 256, [4, 8, 16, 32, 5], [1, 1, 1, 1, 1],
                          [1.0, 2.0, 0.5, 0.25, 3.0], seed=53, b_sigma=0.3)
