@@ -428,12 +428,13 @@ struct WgradArgs {
     int32_t rank_class;        // 0: every item; 1: only adapters with rank <= 64; 2: only wider ones
 };
 
-template <int MAXNB>
-__global__ __launch_bounds__(256) void wgrad_kernel(WgradArgs g) {
+// One work item; isA: a dA_i item (panel of X against dS_i), else a dB_i item (panel of dY against S_i).  The two forms
+// are separate instantiations (the kernel branches once, uniformly): they use the MFMA operands the other way round.
+template <int MAXNB, bool isA>
+__device__ __forceinline__ void wgrad_body(const WgradArgs& g, u16* lds, const int ce, const int panel) {
     constexpr int SW = MAXNB * 32;                 // S / dS tile width (elements)
     constexpr int CPRS = SW / 8;                   // 16-byte chunks per S tile row
     constexpr int W_STAGE = WX_TILE + WT * SW;     // elements per stage
-    __shared__ __attribute__((aligned(16))) u16 lds[2 * W_STAGE];
     // byte offset of element column c (multiple of 4) of token row t
     auto x_off = [](int t, int c) { return t * 256 + ((((c >> 5) ^ (t & 3)) << 6) | ((c & 31) << 1)); };
     auto s_off = [](int t, int c) {
@@ -442,13 +443,8 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradArgs g) {
         return t * (SW * 2) + ((us << 6) | ((c & 31) << 1));
     };
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int panels = g.panels_k + g.panels_n;
-    const int ce = blockIdx.x / panels;
-    int panel = blockIdx.x - ce * panels;
     const Entry4 e = g.pv.wgrad_chunks[ce];
     const int i = e.a, chunk = e.b, row0 = e.c, rows = e.d;
-    const bool isA = panel < g.panels_k;
-    if (!isA) panel -= g.panels_k;
     const int r = g.pv.rank[i];
     if ((g.rank_class == 1 && r > 64) || (g.rank_class == 2 && r <= 64)) return;   // the other launch's item (uniform)
     const int rpad = (r + 31) & ~31;
@@ -529,7 +525,9 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradArgs g) {
                 if (nb < nblk) {
                     const unsigned char* pb = Ss + s_off(trow, nb * 32 + coff);
                     const bf16x8 b = lds_read_frag_tr(reinterpret_cast<const u16*>(pb), reinterpret_cast<const u16*>(pb + 4 * SW * 2));
-                    acc[nb] = mfma32(a, b, acc[nb]);
+                    // dA_i items compute the transposed block (ranks down the accumulator rows), so that for both outputs a
+                    // lane ends up with 4 consecutive elements of an output row
+                    acc[nb] = isA ? mfma32(b, a, acc[nb]) : mfma32(a, b, acc[nb]);
                 }
             }
         }
@@ -560,25 +558,65 @@ __global__ __launch_bounds__(256) void wgrad_kernel(WgradArgs g) {
     const int nchunks = g.pv.wgrad_chunk_start[i + 1] - g.pv.wgrad_chunk_start[i];
     const float s = isA ? 1.0f : g.pv.scale[i];
     const int64_t kk = g.pv.k, nn = g.pv.n;
+    // Accumulator element q of lane (lm, h) of block nb is at (row 8 (q >> 2) + 4 h + (q & 3), column lm) of a 32 x 32 block.
+    //   dB_i item: rows = panel columns, lane column = rank: out[rho][c], 4 consecutive c per (lane, q >> 2)
+    //   dA_i item (transposed block): rows = ranks, lane column = panel column: out[c][rho], 4 consecutive rho
+    // so every lane stores 8-byte (bf16) or 16-byte (fp32 partial) pieces; ranks that are not multiples of 4 and
+    // the ragged edge go element by element.
+    u16* out = (u16*)(isA ? g.pv.ptrs[i].dA : g.pv.ptrs[i].dB);
+    float* part = nchunks == 1 ? nullptr
+                               : g.partials + g.part_off[i] + (int64_t)chunk * (kk + nn) * r + (isA ? 0 : kk * r);
+    const bool vec = isA ? ((r & 3) == 0) : ((nn & 3) == 0);
+    const bool part_vec = vec && ((reinterpret_cast<uintptr_t>(part) & 15) == 0);
 #pragma unroll
     for (int nb = 0; nb < MAXNB; ++nb) {
         if (nb >= nblk) continue;
-        const int rho = nb * 32 + lm;
-        if (rho >= r) continue;
 #pragma unroll
-        for (int q = 0; q < 16; ++q) {
-            const int c = col0 + wave * 32 + (q >> 2) * 8 + h * 4 + (q & 3);
-            if (c >= width) continue;
-            const int64_t idx = isA ? ((int64_t)c * r + rho) : ((int64_t)rho * nn + c);
-            if (nchunks == 1) {
-                u16* out = (u16*)(isA ? g.pv.ptrs[i].dA : g.pv.ptrs[i].dB);
-                out[idx] = f2bf(g.accumulate ? s * acc[nb][q] + bf2f(out[idx]) : s * acc[nb][q]);
+        for (int qg = 0; qg < 4; ++qg) {
+            const int inner = 8 * qg + 4 * h;
+            const int c = col0 + wave * 32 + (isA ? lm : inner);
+            const int rho = nb * 32 + (isA ? inner : lm);
+            if (c >= width || rho >= r) continue;
+            const int64_t idx0 = isA ? ((int64_t)c * r + rho) : ((int64_t)rho * nn + c);
+            const int nvalid = min(4, isA ? r - rho : width - c);
+            float v[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) v[q] = s * acc[nb][4 * qg + q];
+            if (part) {
+                if (part_vec && nvalid == 4) {
+                    *reinterpret_cast<float4*>(part + idx0) = make_float4(v[0], v[1], v[2], v[3]);
+                } else {
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        if (q < nvalid) part[idx0 + q] = v[q];
+                }
+            } else if (vec && nvalid == 4) {
+                uint2* dst = reinterpret_cast<uint2*>(out + idx0);
+                if (g.accumulate) {
+                    const uint2 old = *dst;
+                    v[0] += __uint_as_float(old.x << 16); v[1] += __uint_as_float(old.x & 0xffff0000u);
+                    v[2] += __uint_as_float(old.y << 16); v[3] += __uint_as_float(old.y & 0xffff0000u);
+                }
+                *dst = make_uint2(pack2(v[0], v[1]), pack2(v[2], v[3]));
             } else {
-                float* part = g.partials + g.part_off[i] + (int64_t)chunk * (kk + nn) * r + (isA ? 0 : kk * r);
-                part[idx] = s * acc[nb][q];
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (q < nvalid) out[idx0 + q] = f2bf(g.accumulate ? v[q] + bf2f(out[idx0 + q]) : v[q]);
             }
         }
     }
+}
+
+// (the register budget is stated per build: the work groups per CU that its LDS footprint allows, one wavefront of each per SIMD)
+template <int MAXNB>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MAXNB == 4 ? 2 : MAXNB == 2 ? 3 : 4)))
+void wgrad_kernel(WgradArgs g) {
+    __shared__ __attribute__((aligned(16))) u16 lds[2 * (WX_TILE + WT * MAXNB * 32)];
+    const int panels = g.panels_k + g.panels_n;
+    const int ce = blockIdx.x / panels;
+    const int panel = blockIdx.x - ce * panels;
+    if (panel < g.panels_k) wgrad_body<MAXNB, true>(g, lds, ce, panel);
+    else wgrad_body<MAXNB, false>(g, lds, ce, panel - g.panels_k);
 }
 
 // Adds the chunk partials of one adapter in chunk order and rounds once.
