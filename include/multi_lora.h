@@ -83,7 +83,9 @@ typedef enum {
     MLORA_TABLE_WGRAD_CHUNKS = 2 /* token chunks reduced by the weight-gradient kernels, 4 x int32:
                                    adapter, chunk index within the adapter, first global row, rows.
                                    Same entries as a block table with MLORA_GEO_WGRAD_CHUNK_ROWS rows per
-                                   block, but ordered by decreasing cost rows x (64 + rank), ties in
+                                   block (MLORA_GEO_WGRAD_CHUNK_ROWS_WIDE for adapters with a rank above 64; the
+                                   two differ only in plans that hold ranks on both sides of 64, whose two rank
+                                   classes are balanced separately), but ordered by decreasing cost rows x (64 + rank), ties in
                                    canonical order (the device-side balancing of heterogeneous segments);
                                    tables above 16384 entries keep the canonical order. */
 } mlora_table;
@@ -97,6 +99,7 @@ enum {
     MLORA_GEO_R1_LO = 4,          /* sum_i T_i r_i, low and high 31 bits */
     MLORA_GEO_R1_HI = 5,
     MLORA_GEO_USES_MFMA = 6,      /* 1 if the bf16 MFMA kernels serve this plan, 0 for the fp32-FMA kernels */
+    MLORA_GEO_WGRAD_CHUNK_ROWS_WIDE = 7, /* token chunk of adapters with a rank above 64 */
     MLORA_GEO_COUNT = 8
 };
 
@@ -113,9 +116,6 @@ enum {
  *   scales       host [N], finite
  *   seg_offsets  host [N+1], seg_offsets[0] = 0, non-decreasing, seg_offsets[N] = T (N >= 1)
  * The only entry point that allocates device memory; freed by multi_lora_plan_destroy.
- * A bf16 plan whose adapters mix ranks <= 64 with wider ones also owns one HIP stream (default priority) and two events:
- * multi_lora_bwd runs the weight gradients of the two rank classes as two overlapping launches, the second on that
- * stream, forked from and joined back to the caller's stream with the events (legal under stream capture).
  */
 int multi_lora_plan_create(mlora_plan** out, int dtype, int64_t T, int64_t k, int64_t n,
                            int32_t N, const int32_t* ranks, const float* scales,

@@ -17,6 +17,7 @@ constexpr int kBlockRows = 64;       // rows per LoRA block of the shrink kernel
 constexpr int kGemmTileRows = 256;   // fused GEMM macro tile
 constexpr int kGemmTileCols = 256;
 constexpr int kWgradMinChunkRows = 512;  // smallest token chunk one weight-gradient work item reduces
+constexpr int kNarrowMaxRank = 64;       // ranks above it form the wide rank class (their own kernel builds)
 constexpr int kMaxSortedChunks = 16384;  // larger weight-gradient tables keep the canonical order
 constexpr int kWgradPanelCols = 128;     // columns of X / dY one weight-gradient work item covers
 
@@ -80,14 +81,12 @@ struct mlora_plan {
     int32_t n_blocks_narrow = 0, n_blocks_wide = 0;
     int32_t* d_block_lists = nullptr;
     int32_t wgrad_chunk_rows = 0;     // token chunk of the weight-gradient items (chosen per plan)
-    // Plans that mix ranks <= 64 and wider ones run the weight-gradient items of the two classes as two launches that
-    // overlap (the wide class on aux_stream, forked from and joined to the caller's stream with the two events), each
-    // through the kernel build - and so at the workgroups per CU - its class allows.
+    int32_t wgrad_chunk_rows_wide = 0;   // the same for adapters of the wide rank class (differs only when the plan mixes the classes)
+    // Plans that mix ranks <= 64 and wider ones run the weight-gradient items of the two classes as two launches, each
+    // through the kernel build - and so at the workgroups per CU - its class allows, and chunk the tokens per class.
     int32_t max_rank_narrow = 0;      // largest rank <= 64 among adapters with tokens
     bool ranks_mult8 = true;          // every rank of an adapter with tokens is a multiple of 8
     bool wgrad_two_classes = false;
-    hipStream_t aux_stream = nullptr;
-    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     // one device allocation carved into the tables below; a plan made by multi_lora_plan_create_like also holds the
     // allocation of the plan whose segmentation tables it uses, so the two may be destroyed in any order
     std::shared_ptr<mlora::DeviceBlock> d_block, d_shared_block;
@@ -102,6 +101,8 @@ struct mlora_plan {
     void* d_probs = nullptr;          // descriptor scratch of the FMA grouped GEMM
     void* d_adamw = nullptr;          // [N] optimizer entries (pointers + hyper-parameters), refreshed per call
     int64_t* d_part_off = nullptr;    // [N] float offset of each adapter's partial weight-gradient block
+    std::vector<int32_t> reduce_list; // adapters whose tokens are split over several weight-gradient chunks
+    int32_t* d_reduce_list = nullptr;
     bool has_empty_ranked = false;    // some adapter has a rank but no tokens (its dA, dB are zero-filled)
     size_t ws_ds_bytes = 0;           // workspace: dS
     size_t ws_partial_bytes = 0;      // workspace: fp32 partial weight gradients

@@ -619,21 +619,30 @@ void wgrad_kernel(WgradArgs g) {
     else wgrad_body<MAXNB, false>(g, lds, ce, panel - g.panels_k);
 }
 
-// Adds the chunk partials of one adapter in chunk order and rounds once.
-__global__ __launch_bounds__(256) void wgrad_reduce_kernel(WgradArgs g) {
-    const int i = blockIdx.y;
+// Adds the chunk partials of one adapter in chunk order and rounds once.  blockIdx.y walks the adapters that have
+// partials; a thread owns 4 consecutive elements (k, n are multiples of 8 on this path, so a group never straddles
+// the dA_i / dB_i boundary and every access is 16- resp. 8-byte aligned).
+__global__ __launch_bounds__(256) void wgrad_reduce_kernel(WgradArgs g, const int32_t* list) {
+    const int i = list[blockIdx.y];
     const int nchunks = g.pv.wgrad_chunk_start[i + 1] - g.pv.wgrad_chunk_start[i];
-    if (nchunks <= 1) return;
     const int r = g.pv.rank[i];
     const int64_t kk = g.pv.k, nn = g.pv.n;
     const int64_t per = (kk + nn) * r;
-    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t idx = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
     if (idx >= per) return;
     const float* part = g.partials + g.part_off[i] + idx;
-    float v = 0.f;
-    for (int c = 0; c < nchunks; ++c) v += part[(int64_t)c * per];
-    u16* out = idx < kk * r ? (u16*)g.pv.ptrs[i].dA + idx : (u16*)g.pv.ptrs[i].dB + (idx - kk * r);
-    *out = f2bf(g.accumulate ? v + bf2f(*out) : v);
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int c = 0; c < nchunks; ++c) {
+        const float4 t = *reinterpret_cast<const float4*>(part + (int64_t)c * per);
+        v.x += t.x; v.y += t.y; v.z += t.z; v.w += t.w;
+    }
+    uint2* out = reinterpret_cast<uint2*>(idx < kk * r ? (u16*)g.pv.ptrs[i].dA + idx : (u16*)g.pv.ptrs[i].dB + (idx - kk * r));
+    if (g.accumulate) {
+        const uint2 old = *out;
+        v.x += __uint_as_float(old.x << 16); v.y += __uint_as_float(old.x & 0xffff0000u);
+        v.z += __uint_as_float(old.y << 16); v.w += __uint_as_float(old.y & 0xffff0000u);
+    }
+    *out = make_uint2(pack2(v.x, v.y), pack2(v.z, v.w));
 }
 
 // Zero-fills dA_i, dB_i of adapters that have a rank but no tokens (no work item reaches them).
@@ -894,16 +903,14 @@ int mfma_backward(mlora_plan* p, const void* dY, const void* X, const void* W, c
                     else                hipLaunchKernelGGL(wgrad_kernel<2>, dim3((unsigned)grid), dim3(256), 0, s, w);
                 };
                 if (p->wgrad_two_classes) {
-                    // fork: the wide class on the plan's own stream, overlapping the narrow class; join before anything else
-                    MLORA_HIP_TRY(hipEventRecord(p->ev_fork, st));
-                    MLORA_HIP_TRY(hipStreamWaitEvent(p->aux_stream, p->ev_fork, 0));
+                    // one launch per rank class, each through the build - and so at the work groups per CU - its class
+                    // allows, one after the other (overlapping them on two streams was measured and is slower: the
+                    // classes then share the CUs, and neither runs at its own occupancy)
                     w.rank_class = 2;
-                    hipLaunchKernelGGL(wgrad_kernel<4>, dim3((unsigned)grid), dim3(256), 0, p->aux_stream, w);
+                    hipLaunchKernelGGL(wgrad_kernel<4>, dim3((unsigned)grid), dim3(256), 0, st, w);
                     w.rank_class = 1;
                     narrow(p->max_rank_narrow, st);
                     w.rank_class = 0;
-                    MLORA_HIP_TRY(hipEventRecord(p->ev_join, p->aux_stream));
-                    MLORA_HIP_TRY(hipStreamWaitEvent(st, p->ev_join, 0));
                 } else if (p->max_rank <= 64) {
                     narrow(p->max_rank, st);
                 } else {
@@ -913,7 +920,8 @@ int mfma_backward(mlora_plan* p, const void* dY, const void* X, const void* W, c
             if (p->max_chunks_per_adapter > 1) {
                 const int64_t per = (p->k + p->n) * (int64_t)p->max_rank;
                 ProfScope prof(p, MLORA_K_WGRAD_REDUCE, st);
-                hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)((per + 255) / 256), p->N), dim3(256), 0, st, w);
+                hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)((per + 1023) / 1024), (unsigned)p->reduce_list.size()),
+                                   dim3(256), 0, st, w, (const int32_t*)p->d_reduce_list);
             }
         }
         if (p->has_empty_ranked && !w.accumulate) {   // adapters without tokens add nothing when accumulating

@@ -28,7 +28,7 @@ static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 // Sequential prefix sums over the adapters (N <= 4096, done by one thread).  soff / rb_start may be NULL (not wanted).
 __global__ void plan_scan_kernel(int32_t N, const int32_t* off, const int32_t* rank, int64_t* soff,
                                  int32_t* rb_start, int32_t* wc_start, int block_rows,
-                                 int chunk_rows) {
+                                 int chunk_rows, int chunk_rows_wide) {
     if (threadIdx.x != 0 || blockIdx.x != 0) return;
     int64_t s = 0;
     int32_t rb = 0, wc = 0;
@@ -41,7 +41,8 @@ __global__ void plan_scan_kernel(int32_t N, const int32_t* off, const int32_t* r
         s += (int64_t)Ti * r;
         if (Ti > 0 && r > 0) {
             rb += (Ti + block_rows - 1) / block_rows;
-            wc += (Ti + chunk_rows - 1) / chunk_rows;
+            const int cr = r > kNarrowMaxRank ? chunk_rows_wide : chunk_rows;
+            wc += (Ti + cr - 1) / cr;
         }
     }
     if (soff) soff[N] = s;
@@ -59,9 +60,11 @@ __device__ inline int32_t find_owner(const int32_t* start, int32_t N, int32_t e)
     return lo;
 }
 
-// Fills a block table: entry e of adapter i = (i, b, off[i] + b*rows_per, min(rows_per, rest)).
+// Fills a block table: entry e of adapter i = (i, b, off[i] + b*rows_per, min(rows_per, rest)).  With `rank` given,
+// adapters of the wide rank class take `rows_per_wide` rows per entry instead.
 __global__ void plan_fill_blocks_kernel(int32_t N, const int32_t* off, const int32_t* start,
-                                        int rows_per, Entry4* out, int32_t count) {
+                                        int rows_per_narrow, Entry4* out, int32_t count,
+                                        const int32_t* rank, int rows_per_wide) {
     const int32_t e = blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= count) return;
     // adapters without entries have start[i] == start[i+1]; the owner is the last i with start[i] <= e
@@ -73,6 +76,7 @@ __global__ void plan_fill_blocks_kernel(int32_t N, const int32_t* off, const int
     }
     const int32_t i = lo;
     const int32_t b = e - start[i];
+    const int rows_per = (rank && rank[i] > kNarrowMaxRank) ? rows_per_wide : rows_per_narrow;
     const int32_t row0 = off[i] + b * rows_per;
     const int32_t rest = off[i + 1] - row0;
     out[e] = Entry4{i, b, row0, rest < rows_per ? rest : rows_per};
@@ -263,23 +267,38 @@ static int plan_create_impl(mlora_plan** out, int dtype, int64_t T, int64_t k, i
     // Weight-gradient work items are (token chunk, 128-column panel).  Balance heterogeneous segment
     // lengths across the CUs: keep whole segments when that already yields two items per CU (no
     // partial sums at all), otherwise halve the chunk until it does or the minimum is reached.
+    // A plan that mixes the two rank classes launches them as two kernels that overlap; the rule then holds for
+    // each launch by itself (a few long wide-rank segments would otherwise run on after everything else has ended).
     {
-        const int64_t panels = ceil_div(k, kWgradPanelCols) + ceil_div(n, kWgradPanelCols);
-        int64_t chunk = (int64_t)1 << 30;
-        for (;;) {
-            int64_t items = 0;
-            for (int32_t i = 0; i < N; ++i) {
-                const int64_t Ti = seg_offsets[i + 1] - seg_offsets[i];
-                if (Ti > 0 && ranks[i] > 0) items += ceil_div(Ti, chunk) * panels;
-            }
-            if (items >= 2 * (int64_t)p->num_cus || chunk <= kWgradMinChunkRows) break;
-            chunk /= 2;
+        bool wide = false, narrow = false;
+        for (int32_t i = 0; i < N; ++i) {
+            if (seg_offsets[i + 1] == seg_offsets[i] || ranks[i] == 0) continue;
+            (ranks[i] > kNarrowMaxRank ? wide : narrow) = true;
         }
-        p->wgrad_chunk_rows = (int32_t)chunk;
+        const bool two = wide && narrow;
+        const int64_t panels = ceil_div(k, kWgradPanelCols) + ceil_div(n, kWgradPanelCols);
+        auto choose = [&](int cls) {      // 0: every adapter, 1: narrow ranks only, 2: wide ranks only
+            int64_t chunk = (int64_t)1 << 30;
+            for (;;) {
+                int64_t items = 0;
+                for (int32_t i = 0; i < N; ++i) {
+                    const int64_t Ti = seg_offsets[i + 1] - seg_offsets[i];
+                    if (Ti <= 0 || ranks[i] <= 0) continue;
+                    if ((cls == 1 && ranks[i] > kNarrowMaxRank) || (cls == 2 && ranks[i] <= kNarrowMaxRank)) continue;
+                    items += ceil_div(Ti, chunk) * panels;
+                }
+                if (items >= 2 * (int64_t)p->num_cus || chunk <= kWgradMinChunkRows) break;
+                chunk /= 2;
+            }
+            return (int32_t)chunk;
+        };
+        p->wgrad_chunk_rows = choose(two ? 1 : 0);
+        p->wgrad_chunk_rows_wide = two ? choose(2) : p->wgrad_chunk_rows;
     }
     p->shares_tables = like != nullptr;
     // the weight-gradient item table depends on the layer shape only through the token chunk
-    p->shares_wgrad_table = like != nullptr && like->wgrad_chunk_rows == p->wgrad_chunk_rows;
+    p->shares_wgrad_table = like != nullptr && like->wgrad_chunk_rows == p->wgrad_chunk_rows &&
+                            like->wgrad_chunk_rows_wide == p->wgrad_chunk_rows_wide;
 
     // host-side sizes (the device rebuilds the same numbers; multi_lora_plan_dump exposes them)
     int64_t s = 0;
@@ -291,7 +310,7 @@ static int plan_create_impl(mlora_plan** out, int dtype, int64_t T, int64_t k, i
         s += Ti * ranks[i];
         if (Ti > 0 && ranks[i] > 0) {
             rb += ceil_div(Ti, kBlockRows);
-            const int64_t c = ceil_div(Ti, p->wgrad_chunk_rows);
+            const int64_t c = ceil_div(Ti, ranks[i] > kNarrowMaxRank ? p->wgrad_chunk_rows_wide : p->wgrad_chunk_rows);
             wc += c;
             if (c > p->max_chunks_per_adapter) p->max_chunks_per_adapter = (int32_t)c;
         }
@@ -337,7 +356,10 @@ static int plan_create_impl(mlora_plan** out, int dtype, int64_t T, int64_t k, i
     for (int32_t i = 0; i < N; ++i) {
         const int64_t c = p->wchunk_start[i + 1] - p->wchunk_start[i];
         part_off[i] = (int64_t)part;
-        if (c > 1) part += (size_t)c * (size_t)(k + n) * (size_t)ranks[i];
+        if (c > 1) {
+            part += (size_t)c * (size_t)(k + n) * (size_t)ranks[i];
+            p->reduce_list.push_back(i);
+        }
         if (ranks[i] > 0 && p->off[i + 1] == p->off[i]) p->has_empty_ranked = true;
     }
     p->ws_partial_bytes = up256(part * sizeof(float));
@@ -358,7 +380,7 @@ static int plan_create_impl(mlora_plan** out, int dtype, int64_t T, int64_t k, i
     const size_t o_wc = take(own_wc ? sizeof(Entry4) * (size_t)(p->n_wgrad_chunks + 1) : 0);
     const size_t o_wc_tmp = take(own_wc ? sizeof(Entry4) * (size_t)(p->n_wgrad_chunks + 1) : 0);
     const size_t o_probs = take(128 * (size_t)(5 * N + 8));
-    const size_t o_part = take(sizeof(int64_t) * (N + 1));
+    const size_t o_part = take(sizeof(int64_t) * (N + 1) + sizeof(int32_t) * (N + 1));   // partial offsets, then the reduce list
     const size_t o_adamw = take(96 * (size_t)(N + 1));
     const size_t o_lists = take(own_seg ? sizeof(int32_t) * (size_t)(p->n_row_blocks + 1) : 0);
     p->d_block_bytes = o;
@@ -384,6 +406,7 @@ static int plan_create_impl(mlora_plan** out, int dtype, int64_t T, int64_t k, i
     Entry4* d_wc = own_wc ? (Entry4*)(base + o_wc) : const_cast<Entry4*>(lv->wgrad_chunks);
     p->d_probs = base + o_probs;
     p->d_part_off = (int64_t*)(base + o_part);
+    p->d_reduce_list = (int32_t*)(base + o_part + sizeof(int64_t) * (N + 1));
     p->d_adamw = base + o_adamw;
     p->d_block_lists = own_seg ? (int32_t*)(base + o_lists) : like->d_block_lists;
 
@@ -392,9 +415,6 @@ static int plan_create_impl(mlora_plan** out, int dtype, int64_t T, int64_t k, i
     off32.resize(N + 1);
     for (int32_t i = 0; i <= N; ++i) off32[i] = (int32_t)p->off[i];
     auto fail = [&](hipError_t err, const char* what) {
-        if (p->ev_fork) (void)hipEventDestroy(p->ev_fork);
-        if (p->ev_join) (void)hipEventDestroy(p->ev_join);
-        if (p->aux_stream) (void)hipStreamDestroy(p->aux_stream);
         delete p;
         return hip_fail(err, what);
     };
@@ -408,6 +428,10 @@ static int plan_create_impl(mlora_plan** out, int dtype, int64_t T, int64_t k, i
     }
     if ((e = hipMemcpyAsync(p->d_part_off, part_off.data(), sizeof(int64_t) * (N + 1), hipMemcpyHostToDevice, st)) != hipSuccess)
         return fail(e, "hipMemcpyAsync(partial offsets)");
+    if (!p->reduce_list.empty() &&
+        (e = hipMemcpyAsync(p->d_reduce_list, p->reduce_list.data(), sizeof(int32_t) * p->reduce_list.size(),
+                            hipMemcpyHostToDevice, st)) != hipSuccess)
+        return fail(e, "hipMemcpyAsync(reduce list)");
     if (own_seg && !p->block_lists.empty() &&
         (e = hipMemcpyAsync(p->d_block_lists, p->block_lists.data(), sizeof(int32_t) * p->block_lists.size(),
                             hipMemcpyHostToDevice, st)) != hipSuccess)
@@ -415,24 +439,26 @@ static int plan_create_impl(mlora_plan** out, int dtype, int64_t T, int64_t k, i
     // (a plan that shares the segmentation tables but chunks the tokens differently scans again for its chunk starts)
     if (own_seg)
         hipLaunchKernelGGL(plan_scan_kernel, dim3(1), dim3(64), 0, st, N, d_off, d_rank, d_soff, d_rbs, d_wcs,
-                           kBlockRows, p->wgrad_chunk_rows);
+                           kBlockRows, p->wgrad_chunk_rows, p->wgrad_chunk_rows_wide);
     else if (own_wc)
         hipLaunchKernelGGL(plan_scan_kernel, dim3(1), dim3(64), 0, st, N, d_off, d_rank, (int64_t*)nullptr,
-                           (int32_t*)nullptr, d_wcs, kBlockRows, p->wgrad_chunk_rows);
+                           (int32_t*)nullptr, d_wcs, kBlockRows, p->wgrad_chunk_rows, p->wgrad_chunk_rows_wide);
     if (own_seg && p->n_row_blocks > 0)
         hipLaunchKernelGGL(plan_fill_blocks_kernel, dim3((p->n_row_blocks + 255) / 256), dim3(256), 0, st, N,
-                           d_off, d_rbs, kBlockRows, d_rb, p->n_row_blocks);
+                           d_off, d_rbs, kBlockRows, d_rb, p->n_row_blocks, (const int32_t*)nullptr, 0);
     if (own_wc && p->n_wgrad_chunks > 0) {
         Entry4* d_wc_tmp = (Entry4*)(base + o_wc_tmp);
         const unsigned blocks = (unsigned)((p->n_wgrad_chunks + 255) / 256);
         if (p->n_wgrad_chunks <= kMaxSortedChunks) {   // canonical table, then reordered by cost
             hipLaunchKernelGGL(plan_fill_blocks_kernel, dim3(blocks), dim3(256), 0, st, N, d_off, d_wcs,
-                               p->wgrad_chunk_rows, d_wc_tmp, p->n_wgrad_chunks);
+                               p->wgrad_chunk_rows, d_wc_tmp, p->n_wgrad_chunks, (const int32_t*)d_rank,
+                               p->wgrad_chunk_rows_wide);
             hipLaunchKernelGGL(plan_sort_chunks_kernel, dim3(blocks), dim3(256), 0, st, d_wc_tmp, d_rank, d_wc,
                                p->n_wgrad_chunks);
         } else {
             hipLaunchKernelGGL(plan_fill_blocks_kernel, dim3(blocks), dim3(256), 0, st, N, d_off, d_wcs,
-                               p->wgrad_chunk_rows, d_wc, p->n_wgrad_chunks);
+                               p->wgrad_chunk_rows, d_wc, p->n_wgrad_chunks, (const int32_t*)d_rank,
+                               p->wgrad_chunk_rows_wide);
         }
     }
     if (own_seg && p->n_gemm_tiles > 0)
@@ -447,11 +473,6 @@ static int plan_create_impl(mlora_plan** out, int dtype, int64_t T, int64_t k, i
     v.gemm_tiles = d_gt; v.n_gemm_tiles = p->n_gemm_tiles;
     v.wgrad_chunks = d_wc; v.n_wgrad_chunks = p->n_wgrad_chunks;
     v.wgrad_chunk_start = d_wcs;
-    if (p->wgrad_two_classes && p->use_mfma) {
-        if ((e = hipStreamCreateWithFlags(&p->aux_stream, hipStreamNonBlocking)) != hipSuccess) return fail(e, "hipStreamCreateWithFlags");
-        if ((e = hipEventCreateWithFlags(&p->ev_fork, hipEventDisableTiming)) != hipSuccess) return fail(e, "hipEventCreateWithFlags");
-        if ((e = hipEventCreateWithFlags(&p->ev_join, hipEventDisableTiming)) != hipSuccess) return fail(e, "hipEventCreateWithFlags");
-    }
     *out = p;
     return MLORA_OK;
 }
@@ -552,9 +573,6 @@ extern "C" int multi_lora_profile_end(mlora_plan* plan, int32_t* kernel_ids, flo
 extern "C" int multi_lora_plan_destroy(mlora_plan* plan) {
     if (!plan) return MLORA_OK;
     free_events(plan);
-    if (plan->ev_fork) (void)hipEventDestroy(plan->ev_fork);
-    if (plan->ev_join) (void)hipEventDestroy(plan->ev_join);
-    if (plan->aux_stream) (void)hipStreamDestroy(plan->aux_stream);
     delete plan;      // frees the device block unless another plan still shares it
     return MLORA_OK;
 }
@@ -574,6 +592,7 @@ extern "C" int multi_lora_plan_geometry(const mlora_plan* plan, int32_t* out) {
     out[MLORA_GEO_GEMM_TILE_ROWS] = kGemmTileRows;
     out[MLORA_GEO_GEMM_TILE_COLS] = kGemmTileCols;
     out[MLORA_GEO_WGRAD_CHUNK_ROWS] = plan->wgrad_chunk_rows;
+    out[MLORA_GEO_WGRAD_CHUNK_ROWS_WIDE] = plan->wgrad_chunk_rows_wide;
     out[MLORA_GEO_R1_LO] = (int32_t)(plan->R1 & 0x7fffffff);
     out[MLORA_GEO_R1_HI] = (int32_t)(plan->R1 >> 31);
     out[MLORA_GEO_USES_MFMA] = plan->use_mfma ? 1 : 0;
