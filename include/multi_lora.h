@@ -323,6 +323,56 @@ int multi_lora_admission_exit(mlora_admission* scheduler, int32_t job_id, int32_
 int multi_lora_admission_running(const mlora_admission* scheduler, int32_t* job_ids, int32_t* batch_sizes, int32_t cap,
                                  int32_t* count);
 
+/* ---------------------------------------------------------------------------------------------
+ * Dynamic inter-task scheduling (Sec. 6.2).  Host only, no GPU work.  n tasks with profiled durations d_i > 0 and GPU
+ * requirements g_i in [1, G] on G interchangeable GPUs; a task holds its g_i GPUs from its start for d_i; the makespan
+ * is minimised exactly (the problem the paper states as a constraint program over start times, GPU assignments and
+ * pair orders with no-overlap constraints per shared GPU).
+ *
+ * multi_lora_schedule_tasks: one solve.
+ *   durations, gpus_needed  host [n], n in [0, MLORA_MAX_TASKS]
+ *   release                 host [G] or NULL: time from which GPU q may be used (GPUs still held by running work);
+ *                           values before `now`, and NULL, mean `now`
+ *   starts                  host [n] out, start times >= now
+ *   gpu_masks               host [n] out, bit q set = the task runs on GPU q; handed out in order of start time
+ *                           (ties: more GPUs first, then longer, then lower index), lowest idle GPU first
+ *   makespan                host out, max(now, max_i starts[i] + d_i)
+ *   proved_optimal          host out or NULL: 1 if the search ran to its end (the schedule is the optimum described
+ *                           below), 0 if it ran out of its budget of about a second of search and the schedule is the
+ *                           best one found until then (valid, not proved optimal; only seen above some 12 tasks)
+ * Among the schedules that reach the optimum the result is a fixed one: tasks are ordered by (g descending, d
+ * descending, index ascending), orders of the tasks are walked depth first in that order (tasks with equal d and g only
+ * in index order), every order is turned into a schedule by placing its tasks one after the other at their earliest
+ * feasible start, and the first order that reaches the minimum wins.  Times closer than 1e-9 count as equal.
+ * Exact search, exponential in the worst case: meant for the handful of tasks of a cluster queue (the paper's case, 11
+ * tasks on 8 GPUs, takes milliseconds).
+ *
+ * mlora_cluster: the event loop around it.  Task arrival (_submit) and task completion (_complete, usually earlier than
+ * the estimate because adapters exit early) re-plan all waiting tasks around the running ones, whose GPUs count as
+ * released at their estimated end (or `now` once that has passed).  _poll(now) starts every waiting task whose planned
+ * start has come and for which enough GPUs are idle - in order of planned start, lowest idle GPUs first - and reports
+ * them; if a task had to start late or could not start because a running task has overrun its estimate it re-plans.
+ * _plan reports the waiting tasks in submission order with their planned starts, and the planned makespan.
+ * Task ids are handed out by _submit (0, 1, 2, ...).  If an output array is too small the call returns MLORA_ERR_SHAPE
+ * with *count set; for _poll the tasks have been started all the same.
+ * Errors: MLORA_ERR_NULL, MLORA_ERR_SHAPE (bad parameter, too many waiting tasks, task not running).  Not thread safe.
+ */
+#define MLORA_MAX_TASKS 24
+#define MLORA_MAX_CLUSTER_GPUS 64
+typedef struct mlora_cluster mlora_cluster;
+
+int multi_lora_schedule_tasks(int32_t n, const double* durations, const int32_t* gpus_needed, int32_t G,
+                              const double* release, double now, double* starts, uint64_t* gpu_masks,
+                              double* makespan, int32_t* proved_optimal);
+int multi_lora_cluster_create(mlora_cluster** out, int32_t G);
+int multi_lora_cluster_destroy(mlora_cluster* cluster);
+int multi_lora_cluster_submit(mlora_cluster* cluster, double now, double duration, int32_t gpus, int32_t* task_id);
+int multi_lora_cluster_complete(mlora_cluster* cluster, double now, int32_t task_id);
+int multi_lora_cluster_poll(mlora_cluster* cluster, double now, int32_t* task_ids, uint64_t* gpu_masks, int32_t cap,
+                            int32_t* count);
+int multi_lora_cluster_plan(const mlora_cluster* cluster, int32_t* task_ids, double* planned_starts, int32_t cap,
+                            int32_t* count, double* planned_makespan);
+
 #ifdef __cplusplus
 }
 #endif

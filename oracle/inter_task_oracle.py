@@ -11,9 +11,10 @@ What this file holds, slow and plain:
                        in time; nobody starts before `now` or before an assigned GPU is released.
 * ``time_indexed_optimum``  brute force straight on that definition for small integer data: every combination of
                        integer start times up to a horizon, capacity checked instant by instant.
-* ``optimal_schedule`` the exact optimum by enumeration of task orders, each order turned into a schedule by placing
-                       the tasks one after the other at their earliest feasible start (for a regular objective such
-                       as the makespan some order yields an optimal schedule).
+* ``optimal_schedule`` the exact optimum by enumeration of task lists, each list turned into a schedule by starting
+                       its tasks in list order, each as early as possible but not before the one before it (every
+                       schedule in which no task can start earlier with the others left alone is the schedule of
+                       its own tasks listed by start time, and some such schedule is optimal).
 * ``Cluster``          the event loop: arrival and completion re-plan; ``poll`` starts what the plan says is due.
 
 Readings where the paper is silent:
@@ -22,9 +23,10 @@ Readings where the paper is silent:
      GPUs are then handed out in order of start time, lowest free index first.  (Intervals: a demand-feasible set of
      intervals can always be coloured this way.)
   2. Several schedules reach the optimum.  The canonical one: candidate order = tasks sorted by (g descending,
-     d descending, index ascending); orders are enumerated depth first in that candidate order, tasks with equal (d, g)
-     only in index order; the first order whose schedule attains the minimum (strict improvement replaces the incumbent)
-     is the answer.  The library must return exactly this schedule.
+     d descending, index ascending); lists are enumerated depth first in that candidate order, tasks with equal (d, g)
+     only in index order, tasks that come out with equal start times only in candidate order (other lists repeat a
+     schedule); the first list whose schedule attains the minimum (strict improvement replaces the incumbent) is the
+     answer.  The library must return exactly this schedule.
   3. Re-planning keeps running tasks where they are: a GPU held by a running task is released at that task's estimated
      end (start + d), or `now` if that estimate has already passed.
   4. ``poll(now)`` starts, in order of planned start (ties in candidate order), every pending task whose planned start
@@ -41,38 +43,20 @@ from typing import Dict, List, Optional, Sequence, Tuple
 EPS = 1e-9
 
 
-def _avail(release: Sequence[float], t: float) -> int:
-    return sum(1 for r in release if r <= t + EPS)
-
-
-def _fits(placed: List[Tuple[float, float, int]], release: Sequence[float], s: float, dur: float, need: int) -> bool:
-    """Would a task of `need` GPUs fit over [s, s + dur) next to the placed (start, end, gpus) tasks?  A task takes its
-    GPUs at its start from those released and idle then, so demand <= supply has to hold at every start time: at s with
-    the new task counted, and at the start of every placed task inside the interval."""
-    points = [s] + [ps for ps, pe, pg in placed if s + EPS < ps < s + dur - EPS]
-    for t in points:
-        used = sum(pg for ps, pe, pg in placed if ps <= t + EPS and t < pe - EPS)
-        if used + need > _avail(release, t):
-            return False
-    return True
-
-
-def earliest_start(placed, release, now: float, dur: float, need: int) -> float:
-    """Earliest s >= now at which the task fits; candidates are now, the release times and the ends of placed tasks."""
-    cands = sorted({now} | {r for r in release if r > now} | {pe for ps, pe, pg in placed if pe > now})
-    for s in cands:
-        if _fits(placed, release, s, dur, need):
-            return s
-    raise ValueError("task needs more GPUs than the cluster has")
-
-
-def serial_schedule(order: Sequence[int], d, g, G: int, release: Optional[Sequence[float]] = None, now: float = 0.0):
-    release = list(release) if release is not None else [now] * G
-    placed: List[Tuple[float, float, int]] = []
+def list_schedule(order: Sequence[int], d, g, G: int, release: Optional[Sequence[float]] = None, now: float = 0.0):
+    """Tasks are started in the order of the list, none before the one listed before it: each at the earliest time, not
+    before the previous start, at which g_i GPUs are idle (GPUs are only ever taken from a start time on, so "idle at s"
+    means idle for good).  Returns ({task: start}, makespan of the listed tasks)."""
+    free = [max(float(r), now) for r in release] if release is not None else [now] * G
+    front = now
     starts: Dict[int, float] = {}
     for i in order:
-        s = earliest_start(placed, release, now, float(d[i]), int(g[i]))
-        placed.append((s, s + float(d[i]), int(g[i])))
+        need = int(g[i])
+        by_time = sorted(range(G), key=lambda q: (free[q], q))
+        s = max(front, free[by_time[need - 1]])
+        for q in by_time[:need]:
+            free[q] = s + float(d[i])
+        front = s
         starts[i] = s
     makespan = max([now] + [starts[i] + float(d[i]) for i in order])
     return starts, makespan
@@ -89,12 +73,17 @@ def optimal_schedule(d, g, G: int, release: Optional[Sequence[float]] = None, no
         if not (1 <= int(g[i]) <= G) or not float(d[i]) > 0.0:
             raise ValueError("bad task")
     cand = candidate_order(d, g)
+    pos_of = {i: p for p, i in enumerate(cand)}
     best = (None, float("inf"))
 
     def rec(prefix: List[int], left: List[int]):
         nonlocal best
         if not left:
-            starts, mk = serial_schedule(prefix, d, g, G, release, now)
+            starts, mk = list_schedule(prefix, d, g, G, release, now)
+            for p in range(n - 1):
+                a, b = prefix[p], prefix[p + 1]
+                if abs(starts[b] - starts[a]) <= EPS and pos_of[b] < pos_of[a]:
+                    return    # equal starts out of candidate order: the same schedule comes up under another list
             if mk < best[1] - EPS:
                 best = ([starts[i] for i in range(n)], mk)
             return

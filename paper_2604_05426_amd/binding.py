@@ -36,7 +36,10 @@ EXPORTS = ["multi_lora_plan_create", "multi_lora_plan_create_like", "multi_lora_
            "multi_lora_monitor_val_loss", "multi_lora_monitor_warmup_select", "multi_lora_monitor_state",
            "multi_lora_memory_model_fit", "multi_lora_admission_create", "multi_lora_admission_destroy",
            "multi_lora_admission_submit", "multi_lora_admission_fill", "multi_lora_admission_exit",
-           "multi_lora_admission_running"]
+           "multi_lora_admission_running",
+           "multi_lora_schedule_tasks", "multi_lora_cluster_create", "multi_lora_cluster_destroy",
+           "multi_lora_cluster_submit", "multi_lora_cluster_complete", "multi_lora_cluster_poll",
+           "multi_lora_cluster_plan"]
 
 EXIT_CONTINUE, EXIT_DIVERGING, EXIT_OVERFITTING, EXIT_UNDERPERFORMING = 0, 1, 2, 3
 
@@ -144,6 +147,21 @@ def lib() -> ctypes.CDLL:
         L.multi_lora_admission_exit.restype = ctypes.c_int
         L.multi_lora_admission_running.argtypes = [vp, vp, vp, i32, ctypes.POINTER(i32)]
         L.multi_lora_admission_running.restype = ctypes.c_int
+        dbl = ctypes.c_double
+        L.multi_lora_schedule_tasks.argtypes = [i32, vp, vp, i32, vp, dbl, vp, vp, dp, ctypes.POINTER(i32)]
+        L.multi_lora_schedule_tasks.restype = ctypes.c_int
+        L.multi_lora_cluster_create.argtypes = [ctypes.POINTER(vp), i32]
+        L.multi_lora_cluster_create.restype = ctypes.c_int
+        L.multi_lora_cluster_destroy.argtypes = [vp]
+        L.multi_lora_cluster_destroy.restype = ctypes.c_int
+        L.multi_lora_cluster_submit.argtypes = [vp, dbl, dbl, i32, ctypes.POINTER(i32)]
+        L.multi_lora_cluster_submit.restype = ctypes.c_int
+        L.multi_lora_cluster_complete.argtypes = [vp, dbl, i32]
+        L.multi_lora_cluster_complete.restype = ctypes.c_int
+        L.multi_lora_cluster_poll.argtypes = [vp, dbl, vp, vp, i32, ctypes.POINTER(i32)]
+        L.multi_lora_cluster_poll.restype = ctypes.c_int
+        L.multi_lora_cluster_plan.argtypes = [vp, vp, vp, i32, ctypes.POINTER(i32), dp]
+        L.multi_lora_cluster_plan.restype = ctypes.c_int
         L.multi_lora_last_error.restype = ctypes.c_char_p
         L.multi_lora_version.restype = ctypes.c_char_p
         _lib = L
@@ -387,6 +405,65 @@ class Admission:
     def destroy(self) -> None:
         if self._h:
             lib().multi_lora_admission_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+MAX_TASKS, MAX_CLUSTER_GPUS = 24, 64
+
+
+def _mask_to_gpus(mask: int) -> List[int]:
+    return [q for q in range(MAX_CLUSTER_GPUS) if mask >> q & 1]
+
+
+def schedule_tasks(durations: Sequence[float], gpus_needed: Sequence[int], G: int,
+                   release: Optional[Sequence[float]] = None, now: float = 0.0, with_proof: bool = False):
+    """multi_lora_schedule_tasks: (starts, gpus per task, makespan) of the minimum-makespan schedule; with_proof adds
+    whether the search ran to its end (it gives up after about a second and then returns the best schedule found)."""
+    n = len(durations)
+    d = (ctypes.c_double * max(n, 1))(*[float(x) for x in durations])
+    g = (ctypes.c_int32 * max(n, 1))(*[int(x) for x in gpus_needed])
+    rel = (ctypes.c_double * G)(*[float(x) for x in release]) if release is not None else None
+    starts, masks, mk = (ctypes.c_double * max(n, 1))(), (ctypes.c_uint64 * max(n, 1))(), ctypes.c_double()
+    proved = ctypes.c_int32(0)
+    _check(lib().multi_lora_schedule_tasks(n, d, g, G, rel, float(now), starts, masks, ctypes.byref(mk), ctypes.byref(proved)))
+    out = ([starts[i] for i in range(n)], [_mask_to_gpus(masks[i]) for i in range(n)], mk.value)
+    return out + (bool(proved.value),) if with_proof else out
+
+
+class Cluster:
+    """Owns one mlora_cluster (event-driven inter-task scheduler; host only)."""
+
+    def __init__(self, G: int):
+        self._h = ctypes.c_void_p()
+        _check(lib().multi_lora_cluster_create(ctypes.byref(self._h), G))
+
+    def submit(self, now: float, duration: float, gpus: int) -> int:
+        tid = ctypes.c_int32(-1)
+        _check(lib().multi_lora_cluster_submit(self._h, float(now), float(duration), int(gpus), ctypes.byref(tid)))
+        return tid.value
+
+    def complete(self, now: float, task: int) -> None:
+        _check(lib().multi_lora_cluster_complete(self._h, float(now), int(task)))
+
+    def poll(self, now: float) -> List[tuple]:
+        ids, masks, cnt = (ctypes.c_int32 * MAX_TASKS)(), (ctypes.c_uint64 * MAX_TASKS)(), ctypes.c_int32(0)
+        _check(lib().multi_lora_cluster_poll(self._h, float(now), ids, masks, MAX_TASKS, ctypes.byref(cnt)))
+        return [(ids[i], _mask_to_gpus(masks[i])) for i in range(cnt.value)]
+
+    def plan(self):
+        ids, st, cnt, mk = (ctypes.c_int32 * MAX_TASKS)(), (ctypes.c_double * MAX_TASKS)(), ctypes.c_int32(0), ctypes.c_double()
+        _check(lib().multi_lora_cluster_plan(self._h, ids, st, MAX_TASKS, ctypes.byref(cnt), ctypes.byref(mk)))
+        return {ids[i]: st[i] for i in range(cnt.value)}, mk.value
+
+    def destroy(self) -> None:
+        if self._h:
+            lib().multi_lora_cluster_destroy(self._h)
             self._h = ctypes.c_void_p()
 
     def __del__(self):

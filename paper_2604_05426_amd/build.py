@@ -19,7 +19,7 @@ INCLUDE = os.path.join(ROOT, "include")
 OBJDIR = os.path.join(ROOT, "_build")
 LIB = os.path.join(HERE, "libmultilora.so")
 
-SOURCES = ["plan.hip", "api.hip", "grouped_fma.hip", "mfma_gemm.hip", "mfma_lora.hip", "adamw.hip", "calibrate.hip", "early_exit.hip", "admission.hip"]
+SOURCES = ["plan.hip", "api.hip", "grouped_fma.hip", "mfma_gemm.hip", "mfma_lora.hip", "adamw.hip", "calibrate.hip", "early_exit.hip", "admission.hip", "inter_task.hip"]
 
 # packed fp32 ALU forms are switched off on purpose (they have produced wrong results on the test machines)
 HIPCC_FLAGS = [

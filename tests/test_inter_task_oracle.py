@@ -28,7 +28,7 @@ def test_motivating_case_short_first_wastes_gpus():
     # Sec. 3 (motivation): placing the short tasks first leaves GPUs idle while the long task runs alone
     d, g, G = [10, 2, 2, 2, 2], [1, 1, 1, 1, 1], 2
     sjf = sorted(range(5), key=lambda i: d[i])
-    _, mk_sjf = its.serial_schedule(sjf, d, g, G)
+    _, mk_sjf = its.list_schedule(sjf, d, g, G)
     _, mk_opt = its.optimal_schedule(d, g, G)
     assert mk_sjf == 14 and mk_opt == 10
 
