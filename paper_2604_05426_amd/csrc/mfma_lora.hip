@@ -460,9 +460,16 @@ __device__ __forceinline__ void wgrad_body(const WgradArgs& g, u16* lds, const i
     // (the element-wise path combines what it loads at once, which would make every step wait for its own loads)
     const bool s_v8 = !s_vec && ((r & 3) == 0) && ((so & 3) == 0) && ((reinterpret_cast<uintptr_t>(isA ? g.dS : g.S) & 7) == 0);
 
-    f32x16 acc[MAXNB];
+    // Accumulator blocks of a wavefront: NCB 32-column blocks x NRB 32-rank blocks.  Up to 64 ranks every wavefront takes
+    // 32 panel columns against all ranks; the widest build splits the work group 2 x 2 (64 columns x 64 ranks per wavefront),
+    // which reads a fifth less from LDS for the same MFMAs - that build is bound by LDS bandwidth.
+    constexpr int NCB = MAXNB == 4 ? 2 : 1;
+    constexpr int NRB = MAXNB == 4 ? 2 : MAXNB;
+    const int cwave = MAXNB == 4 ? (wave & 1) * 64 : wave * 32;      // first panel column of this wavefront
+    const int rb0 = MAXNB == 4 ? (wave >> 1) * 2 : 0;                // its first rank block
+    f32x16 acc[NCB * NRB];
 #pragma unroll
-    for (int nb = 0; nb < MAXNB; ++nb)
+    for (int nb = 0; nb < NCB * NRB; ++nb)
 #pragma unroll
         for (int q = 0; q < 16; ++q) acc[nb][q] = 0.f;
 
@@ -518,16 +525,22 @@ __device__ __forceinline__ void wgrad_body(const WgradArgs& g, u16* lds, const i
         for (int ks = 0; ks < WT / 16; ++ks) {
             const int trow = ks * 16 + 8 * (gq >> 1) + (j >> 2);    // token rows trow and trow + 4 share their swizzle keys
             const int coff = 16 * (gq & 1) + 4 * (j & 3);
-            const unsigned char* pa = Xs + x_off(trow, wave * 32 + coff);
-            const bf16x8 a = lds_read_frag_tr(reinterpret_cast<const u16*>(pa), reinterpret_cast<const u16*>(pa + 4 * 256));
+            bf16x8 a[NCB];
 #pragma unroll
-            for (int nb = 0; nb < MAXNB; ++nb) {
-                if (nb < nblk) {
-                    const unsigned char* pb = Ss + s_off(trow, nb * 32 + coff);
+            for (int cb = 0; cb < NCB; ++cb) {
+                const unsigned char* pa = Xs + x_off(trow, cwave + cb * 32 + coff);
+                a[cb] = lds_read_frag_tr(reinterpret_cast<const u16*>(pa), reinterpret_cast<const u16*>(pa + 4 * 256));
+            }
+#pragma unroll
+            for (int rbl = 0; rbl < NRB; ++rbl) {
+                if (rb0 + rbl < nblk) {
+                    const unsigned char* pb = Ss + s_off(trow, (rb0 + rbl) * 32 + coff);
                     const bf16x8 b = lds_read_frag_tr(reinterpret_cast<const u16*>(pb), reinterpret_cast<const u16*>(pb + 4 * SW * 2));
                     // dA_i items compute the transposed block (ranks down the accumulator rows), so that for both outputs a
                     // lane ends up with 4 consecutive elements of an output row
-                    acc[nb] = isA ? mfma32(b, a, acc[nb]) : mfma32(a, b, acc[nb]);
+#pragma unroll
+                    for (int cb = 0; cb < NCB; ++cb)
+                        acc[cb * NRB + rbl] = isA ? mfma32(b, a[cb], acc[cb * NRB + rbl]) : mfma32(a[cb], b, acc[cb * NRB + rbl]);
                 }
             }
         }
@@ -569,19 +582,20 @@ __device__ __forceinline__ void wgrad_body(const WgradArgs& g, u16* lds, const i
     const bool vec = isA ? ((r & 3) == 0) : ((nn & 3) == 0);
     const bool part_vec = vec && ((reinterpret_cast<uintptr_t>(part) & 15) == 0);
 #pragma unroll
-    for (int nb = 0; nb < MAXNB; ++nb) {
+    for (int ab = 0; ab < NCB * NRB; ++ab) {
+        const int nb = rb0 + ab % NRB, cbase = cwave + (ab / NRB) * 32;
         if (nb >= nblk) continue;
 #pragma unroll
         for (int qg = 0; qg < 4; ++qg) {
             const int inner = 8 * qg + 4 * h;
-            const int c = col0 + wave * 32 + (isA ? lm : inner);
+            const int c = col0 + cbase + (isA ? lm : inner);
             const int rho = nb * 32 + (isA ? inner : lm);
             if (c >= width || rho >= r) continue;
             const int64_t idx0 = isA ? ((int64_t)c * r + rho) : ((int64_t)rho * nn + c);
             const int nvalid = min(4, isA ? r - rho : width - c);
             float v[4];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) v[q] = s * acc[nb][4 * qg + q];
+            for (int q = 0; q < 4; ++q) v[q] = s * acc[ab][4 * qg + q];
             if (part) {
                 if (part_vec && nvalid == 4) {
                     *reinterpret_cast<float4*>(part + idx0) = make_float4(v[0], v[1], v[2], v[3]);
