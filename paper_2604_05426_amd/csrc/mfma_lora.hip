@@ -684,7 +684,7 @@ __global__ void wgrad_zero_empty_kernel(PlanView pv) {
 // epilogue (operands are swapped so that a lane holds 4 consecutive columns, as in the fused GEMM).
 // fwd: B_i is [r][n] (contraction index outermost), so the work group stages its [r][128] tile in LDS once
 // (256-byte rows, 16-byte chunk c of row k at c ^ (nn_swz(k) << 1)) and reads it with the transposing load;
-// bwd: A_i is [k][r], contraction contiguous: operand fragments come straight from memory.
+// bwd: A_i is [k][r], contraction contiguous: the work group stages its 128 rows in LDS (padded pitch) and reads plain fragments.
 // =========================================================================================
 constexpr int XC = 128;               // output columns per work item
 constexpr int XE_LD = 64 + 8;         // epilogue staging row of one wavefront (elements)
@@ -703,7 +703,8 @@ struct ExpandArgs {
 // first MFMA, so a wavefront pays the memory latency once; many small work items per CU overlap each other.
 template <bool FWD, int MAXKS>
 __global__ __launch_bounds__(256) void expand_add_kernel(ExpandArgs g) {
-    constexpr int BT_BYTES = FWD ? MAXKS * 32 * 256 : 0;        // staged B_i tile
+    constexpr int AT_PITCH = MAXKS * 64 + 16;                    // bwd: bytes per column of the staged A_i rows (padded: bank spread)
+    constexpr int BT_BYTES = FWD ? MAXKS * 32 * 256 : XC * AT_PITCH;   // staged B_i tile / A_i rows
     constexpr int EP_WAVE = 32 * XE_LD * 2;                      // bytes of epilogue staging per wavefront
     __shared__ __attribute__((aligned(16))) unsigned char lds[BT_BYTES + 4 * EP_WAVE];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -774,15 +775,32 @@ __global__ __launch_bounds__(256) void expand_add_kernel(ExpandArgs g) {
                 }
             }
     } else {
+        // the work group's 128 rows of A_i (one per output column; r contiguous elements each, the rows contiguous too)
+        // -> LDS with a padded pitch, then plain 16-byte fragment reads.  Straight from memory every wavefront fetched
+        // the fragments of its 64 columns itself: twice the bytes, in 64-byte pieces.
+        constexpr int CPR = MAXKS * 4;          // 16-byte chunks per staged row
         const bool f_vec = (r & 7) == 0;
+        uint4 st[2 * MAXKS];
+#pragma unroll
+        for (int jj = 0; jj < 2 * MAXKS; ++jj) {
+            const int idx = tid + 256 * jj, c = idx / CPR, cc = idx % CPR;
+            const int col = ct * XC + c;
+            st[jj] = zero4();
+            if (col < g.Ncols && cc * 8 < r) st[jj] = load_chunk_a8(F + (int64_t)col * r + cc * 8, min(8, r - cc * 8), f_vec);
+        }
+#pragma unroll
+        for (int jj = 0; jj < 2 * MAXKS; ++jj) {
+            const int idx = tid + 256 * jj, c = idx / CPR, cc = idx % CPR;
+            if (cc < ksteps * 4) *reinterpret_cast<uint4*>(lds + c * AT_PITCH + cc * 16) = st[jj];
+        }
+        __syncthreads();
 #pragma unroll
         for (int ks = 0; ks < MAXKS; ++ks)
 #pragma unroll
             for (int cb = 0; cb < 4; ++cb) {
-                const int col = colw + cb * 16 + l16, rho = ks * 32 + g4 * 8;
                 fv[cb][ks] = zero4();
-                if (ks < ksteps && col < g.Ncols && rho < r)
-                    fv[cb][ks] = load_chunk_a8(F + (int64_t)col * r + rho, min(8, r - rho), f_vec);
+                if (ks < ksteps)
+                    fv[cb][ks] = *reinterpret_cast<const uint4*>(lds + (wc * 64 + cb * 16 + l16) * AT_PITCH + (ks * 32 + g4 * 8) * 2);
             }
     }
 
