@@ -1,5 +1,5 @@
-"""A layer whose output has more than 2^31 elements (4.65 GB in bf16): element and byte offsets past the 32-bit range in
-every kernel that walks Y / dY (fused GEMMs, dShrink, weight gradients, expand-add).  Inputs are drawn on the GPU; the
+"""Layers whose wide tensors (Y and dY, or X and dX) have more than 2^31 elements (4.65 GB in bf16): element and byte offsets
+past the 32-bit range in every kernel that walks them (shrink / dShrink, fused GEMMs, weight gradients, expand-add).  Inputs are drawn on the GPU; the
 oracle runs on the sampled rows, regrouped into a small workload with the same adapters: rows at the very start, around
 2^31 elements, and the whole last adapter (300 tokens at the end of the buffer), whose S_i, dA_i and dB_i are compared
 in full."""
@@ -15,20 +15,21 @@ from util import rel_fro
 pytestmark = pytest.mark.gpu
 
 
-def test_offsets_beyond_32_bits():
-    k, n = 512, 14336
+@pytest.mark.parametrize("k,n", [(512, 14336), (14336, 512)])     # the wide side is Y / dY, then X / dX
+def test_offsets_beyond_32_bits(k, n):
     ranks = [32, 16, 64, 8, 128, 16, 32, 64, 4, 16]
     lens = [18000] * 9 + [300]
     scales = [0.5, 1.0, 0.25, 2.0, 0.125, 1.0, 0.5, 0.25, 4.0, 1.0]
     dl = DeviceLayer.synthetic("large_offsets", "bf16", k, n, ranks, lens, scales, seed=77)
     T, off = dl.w.T, dl.w.offsets
-    assert T * n > 2 ** 31 and T * n * 2 > 2 ** 32
-    print(f"[case] T={T} k={k} n={n}: Y has {T * n} elements", flush=True)
+    wide = max(k, n)
+    assert T * wide > 2 ** 31 and T * wide * 2 > 2 ** 32
+    print(f"[case] T={T} k={k} n={n}: the wide tensors have {T * wide} elements", flush=True)
     dl.Y.fill_(float("nan")); dl.dX.fill_(float("nan"))
     dl.forward(); dl.backward(); dl.sync()
 
     # sampled rows, grouped by adapter (so that the sample is itself a valid segmentation)
-    wrap = (2 ** 31) // n                      # the row in which the element index passes 2^31
+    wrap = (2 ** 31) // wide                   # the row in which the element index passes 2^31
     rows, sub_off = [], [0]
     for i in range(len(ranks)):
         lo, hi = off[i], off[i + 1]
