@@ -12,8 +12,10 @@ namespace mlora {
 // =========================================================================================
 // Shrink:   S_i  = X_i A_i            (FWD: A_i is [k][r], column index contiguous -> transposing reads)
 // dShrink:  dS_i = s_i dY_i B_i^T     (!FWD: B_i is [r][n], contraction contiguous)
-// One workgroup per row block (64 rows of one adapter), 8 wavefronts.  The work is a pure
-// stream of X (or dY), so the kernel is built for bytes in flight: every wavefront owns a
+// One workgroup per row block (64 rows of one adapter), 8 wavefronts.  Two bodies: the GEMM-tiled one further down
+// (shrink_tiled_body) serves contractions that are multiples of 64 and, in the forward form, ranks that are multiples
+// of 4; the register-staged one below is the first design and remains for everything else.  Register-staged body: the
+// work is a pure stream of X (or dY), so it is built for bytes in flight: every wavefront owns a
 // contiguous slice of the contraction and runs its own register-prefetch -> private LDS tile
 // -> MFMA pipeline with no workgroup barrier in the loop, so eight independent streams per
 // CU keep loads outstanding.  The eight partial tiles are added in LDS in wavefront order
@@ -219,7 +221,7 @@ __global__ __launch_bounds__(64 * SNW) void shrink_kernel(ShrinkArgs g) {
     else shrink_body<FWD, 2, 64, 2, 1>(g, e, lds);
 }
 
-// GEMM-tiled shrink / dShrink, used when the contraction is a multiple of 64 and (shrink only) every rank a multiple of 8.
+// GEMM-tiled shrink / dShrink, used when the contraction is a multiple of 64 (shrink: for adapters whose rank is a multiple of 4).
 // Per 64-wide contraction step the work group shares one X / dY tile [64 rows][64] and one adapter tile (of A_i, read
 // with the transposing load, or of B_i), both brought in by direct global -> LDS loads into a ring of stages (no staging
 // registers, no LDS stores, the loads of all but the current step in flight), one barrier per step.  Every output block
