@@ -30,7 +30,7 @@ using mlora::set_error;
 namespace {
 
 constexpr double kEps = 1e-9;            // two times closer than this are the same time
-constexpr size_t kMaxSeenNodes = 2000000;   // memory bound of the table of expanded nodes (the search stays exact without it)
+constexpr size_t kMaxSeenBytes = (size_t)128 << 20;   // memory bound of the table of expanded nodes (the search stays exact without it)
 constexpr int64_t kMaxNodes = 4000000;      // search budget (about a second); beyond it the best schedule found so far is returned
 
 struct Solver {
@@ -86,7 +86,7 @@ struct Solver {
             std::memcpy(w, &mk, sizeof mk); w += sizeof mk;
             std::memcpy(w, idle, sizeof(double) * (size_t)G);
             if (seen.count(key)) return;
-            if (seen.size() < kMaxSeenNodes) seen.insert(std::move(key));
+            if (seen.size() * (key.size() + 64) < kMaxSeenBytes) seen.insert(std::move(key));   // 64: node and bucket overhead
         }
         double next[MLORA_MAX_CLUSTER_GPUS];
         for (int p = 0; p < n; ++p) {
