@@ -185,6 +185,23 @@ int multi_lora_bwd(mlora_plan* plan, const void* dY, const void* X, const void* 
                    void* const* dA, void* const* dB, void* workspace, uint32_t flags,
                    void* stream);
 
+/*
+ * multi_lora_bwd for callers that cannot allocate device memory or pass a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results (bit for bit) and errors as
+ * multi_lora_bwd, but the workspace (dS and the fp32 partial weight gradients) is a static device array of
+ * MLORA_STATIC_WORKSPACE_BYTES that belongs to the loaded library; every GPU the library runs on holds one copy until
+ * the process ends.  The call allocates and frees nothing on host or device through HIP.  A plan whose
+ * multi_lora_workspace_bytes() exceeds MLORA_STATIC_WORKSPACE_BYTES is rejected with MLORA_ERR_WORKSPACE before any
+ * GPU work.  All calls on one GPU share the one array and it keeps the last call's contents (nothing in it has to start
+ * at zero: each call writes dS and every partial sum it reads): two multi_lora_bwd_static calls that may overlap on
+ * one GPU - different streams, different plans or different threads - race on it and must be serialised by the caller.
+ * dS of the last call is not exposed.
+ */
+#define MLORA_STATIC_WORKSPACE_BYTES (64u << 20)
+int multi_lora_bwd_static(mlora_plan* plan, const void* dY, const void* X, const void* W,
+                          const void* const* A, const void* const* B, const void* S, void* dX,
+                          void* const* dA, void* const* dB, uint32_t flags, void* stream);
+
 /* kernel ids reported by multi_lora_profile_end */
 enum {
     MLORA_K_SHRINK = 0,      /* S_i = X_i A_i (grouped) */

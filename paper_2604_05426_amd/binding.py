@@ -28,7 +28,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmultilor
 # every symbol include/multi_lora.h declares
 EXPORTS = ["multi_lora_plan_create", "multi_lora_plan_create_like", "multi_lora_plan_destroy", "multi_lora_validate",
            "multi_lora_workspace_bytes", "multi_lora_plan_geometry", "multi_lora_plan_dump",
-           "multi_lora_fwd", "multi_lora_bwd", "multi_lora_last_error", "multi_lora_version",
+           "multi_lora_fwd", "multi_lora_bwd", "multi_lora_bwd_static", "multi_lora_last_error", "multi_lora_version",
            "multi_lora_profile_begin", "multi_lora_profile_end",
            "multi_lora_adamw_init", "multi_lora_adamw_step",
            "multi_lora_calib_mfma", "multi_lora_calib_read",
@@ -108,6 +108,8 @@ def lib() -> ctypes.CDLL:
         L.multi_lora_fwd.restype = ctypes.c_int
         L.multi_lora_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, u32, vp]
         L.multi_lora_bwd.restype = ctypes.c_int
+        L.multi_lora_bwd_static.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, u32, vp]
+        L.multi_lora_bwd_static.restype = ctypes.c_int
         L.multi_lora_profile_begin.argtypes = [vp, i32]
         L.multi_lora_profile_begin.restype = ctypes.c_int
         L.multi_lora_profile_end.argtypes = [vp, vp, vp, i32, ctypes.POINTER(i32)]
@@ -291,6 +293,16 @@ def multi_lora_bwd(plan: Plan, dY, X, W, A, B, S, dX, dA, dB, workspace, flags: 
     _check(lib().multi_lora_bwd(plan.handle, _addr(dY), _addr(X), _addr(W), _ptr_array(A, plan.N),
                                 _ptr_array(B, plan.N), _addr(S), _addr(dX), _ptr_array(dA, plan.N),
                                 _ptr_array(dB, plan.N), _addr(workspace), flags, ctypes.c_void_p(stream)))
+
+
+STATIC_WORKSPACE_BYTES = 64 << 20
+
+
+def multi_lora_bwd_static(plan: Plan, dY, X, W, A, B, S, dX, dA, dB, flags: int = 0, stream: int = 0) -> None:
+    """multi_lora_bwd with the workspace in the library's static device array (allocates nothing)."""
+    _check(lib().multi_lora_bwd_static(plan.handle, _addr(dY), _addr(X), _addr(W), _ptr_array(A, plan.N),
+                                       _ptr_array(B, plan.N), _addr(S), _addr(dX), _ptr_array(dA, plan.N),
+                                       _ptr_array(dB, plan.N), flags, ctypes.c_void_p(stream)))
 
 
 def multi_lora_adamw_init(plan: Plan, A, B, stateA, stateB, stream: int = 0) -> None:

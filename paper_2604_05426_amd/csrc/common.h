@@ -143,6 +143,9 @@ struct ProfScope {
     }
 };
 
+// api.hip : looks up the static workspace of multi_lora_bwd_static on the current device (idempotent)
+void prepare_static_workspace();
+
 // plan.hip
 int upload_ptrs(mlora_plan* p, const void* const* A, const void* const* B, void* const* dA,
                 void* const* dB, hipStream_t st);

@@ -465,6 +465,7 @@ static int plan_create_impl(mlora_plan** out, int dtype, int64_t T, int64_t k, i
         hipLaunchKernelGGL(plan_fill_gemm_tiles_kernel, dim3((p->n_gemm_tiles + 255) / 256), dim3(256), 0, st, N,
                            d_off, (int32_t)T, kGemmTileRows, d_gt, p->n_gemm_tiles);
     if ((e = hipGetLastError()) != hipSuccess) return fail(e, "plan build kernels");
+    prepare_static_workspace();
 
     PlanView& v = p->view;
     v.N = N; v.T = T; v.k = k; v.n = n;
