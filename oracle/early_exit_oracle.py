@@ -22,6 +22,9 @@ Readings where the paper is silent (listed in the design notes as well):
   7. Ranking at the warmup boundary uses each survivor's latest validation loss, ascending; equal losses keep adapter
      order; survivors that have never been evaluated rank last.  k = ceil(ratio x n) is taken on the exact product: a
      product within 1e-9 of an integer counts as that integer (0.1 x 30 must give 3, not 4).
+  8. A training or validation loss that is NaN or infinite is the end point of Pattern 1 (the loss has left the number
+     line): the adapter exits as diverging at that report; the value enters neither the average nor the histories
+     (inside them it would turn every later comparison false, and the warmup ranking would have no order).
 """
 from __future__ import annotations
 
@@ -87,6 +90,11 @@ class Monitor:
 
     def train_loss(self, i: int, loss: float) -> None:
         a = self.a[i]
+        if a.status != CONTINUE:
+            return
+        if not math.isfinite(loss):       # reading: a non-finite loss is divergence, decided at once
+            a.status = DIVERGING
+            return
         a.lhat = float(loss) if a.lhat is None else self.p.alpha * float(loss) + (1.0 - self.p.alpha) * a.lhat
 
     def val_loss(self, i: int, val: float) -> int:
@@ -95,6 +103,9 @@ class Monitor:
             return a.status
         if a.lhat is None:
             raise ValueError("validation loss before any training loss")
+        if not math.isfinite(val):
+            a.status = DIVERGING
+            return a.status
         a.hist_train.append(a.lhat)
         a.hist_val.append(float(val))
         if val < a.best_val:

@@ -90,6 +90,13 @@ extern "C" int multi_lora_monitor_train_loss(mlora_monitor* m, int32_t adapter, 
     const int rc = check_adapter(m, adapter);
     if (rc != MLORA_OK) return rc;
     AdapterState& a = m->a[adapter];
+    if (a.status != MLORA_EXIT_CONTINUE) return MLORA_OK;      // already out
+    if (!std::isfinite(loss)) {
+        // a loss that is no number any more is the end point of the divergence pattern: decided at once (fed into the
+        // moving average it would turn every later comparison false and the job would never be caught)
+        a.status = MLORA_EXIT_DIVERGING;
+        return MLORA_OK;
+    }
     a.lhat = a.have_lhat ? m->p.ema_alpha * loss + (1.0 - m->p.ema_alpha) * a.lhat : loss;
     a.have_lhat = true;
     return MLORA_OK;
@@ -111,6 +118,11 @@ extern "C" int multi_lora_monitor_val_loss(mlora_monitor* m, int32_t adapter, do
     if (!a.have_lhat) {
         set_error("validation loss reported before any training loss of this adapter");
         return MLORA_ERR_SHAPE;
+    }
+    if (!std::isfinite(val_loss)) {      // as for the training loss; the histories keep finite values only
+        a.status = MLORA_EXIT_DIVERGING;
+        *decision = a.status;
+        return MLORA_OK;
     }
     a.hist_train.push_back(a.lhat);
     a.hist_val.push_back(val_loss);

@@ -94,3 +94,29 @@ def test_monitor_rejects_bad_arguments():
         m.warmup_select(1.5)
     assert math.isnan(m.state(1).ema_train_loss) and m.state(1).best_eval_step == -1
     m.destroy()
+
+
+def test_non_finite_losses_decide_alike():
+    prm = ee.Params(alpha=0.3, w=3, tau_slope=1e-3, tau_gap=0.2, p_div=2, p_ovf=2)
+    rng = np.random.default_rng(99)
+    n = 8
+    orc = ee.Monitor(n, prm)
+    mon = ml.Monitor(n, prm.alpha, prm.w, prm.tau_slope, prm.tau_gap, prm.p_div, prm.p_ovf)
+    bad = [float("nan"), float("inf"), -float("inf")]
+    for e in range(12):
+        for i in range(n):
+            for _ in range(3):
+                l = float(rng.uniform(0.5, 1.5))
+                if rng.random() < 0.04:
+                    l = bad[int(rng.integers(0, 3))]
+                orc.train_loss(i, l); mon.train_loss(i, l)
+            v = float(rng.uniform(0.5, 1.5))
+            if rng.random() < 0.04:
+                v = bad[int(rng.integers(0, 3))]
+            assert mon.val_loss(i, v) == orc.val_loss(i, v), (e, i)
+            st, a = mon.state(i), orc.a[i]
+            assert st.ema_train_loss == a.lhat and st.status == a.status and st.evaluations == len(a.hist_val)
+        if e == 5:
+            assert mon.warmup_select(0.5) == orc.warmup_select(0.5)
+    assert any(a.status == ee.DIVERGING for a in orc.a)
+    mon.destroy()

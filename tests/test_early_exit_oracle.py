@@ -140,3 +140,19 @@ def test_paper_detector_settings_and_sweep_sizes():
     assert st == [ee.CONTINUE, ee.OVERFITTING]
     st, _ = _run([1.0, 1.0, 1.0], [1.09, 1.09, 1.09], p)
     assert st == [0, 0, 0]
+
+
+def test_non_finite_losses_are_divergence_decided_at_once():
+    # hand-worked: a NaN / Inf loss never enters the average or the histories, the adapter is out from that report on,
+    # and the others (and the warmup ranking) are not disturbed by it
+    m = ee.Monitor(4, ee.Params(alpha=0.5, w=2, tau_slope=1e-3, tau_gap=10.0, p_div=2, p_ovf=2))
+    for i in range(4):
+        m.train_loss(i, 1.0)
+    m.train_loss(0, float("nan"))
+    assert m.a[0].status == ee.DIVERGING and m.a[0].lhat == 1.0
+    assert m.val_loss(0, 0.5) == ee.DIVERGING and m.a[0].hist_val == []
+    assert m.val_loss(1, float("inf")) == ee.DIVERGING and m.a[1].hist_val == [] and m.a[1].best_eval == -1
+    m.train_loss(1, 0.3)                                  # ignored: the decision is final
+    assert m.a[1].lhat == 1.0
+    assert m.val_loss(2, 0.9) == ee.CONTINUE and m.val_loss(3, 0.8) == ee.CONTINUE
+    assert m.warmup_select(0.5) == [ee.DIVERGING, ee.DIVERGING, ee.UNDERPERFORMING, ee.CONTINUE]
