@@ -1,12 +1,13 @@
 #!/usr/bin/env python3
 """Benchmark of the fused multi-LoRA layer (forward + backward) on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config I] [--no-cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config I] [--no-configs] [--no-cpu]
 
 A step is one pass of the whole hot path -- multi_lora_fwd then multi_lora_bwd in fused mode --
-over one synthetic batch that is already resident in HBM.  The default workload is the
-Llama-8B q_proj config (8 adapters x 2048 tokens, ranks 8..64, W 4096 x 4096, bf16).
-Prints one JSON line: whole-job tokens/s, ms per step, the roofline of the dominant kernel
+over one synthetic batch that is already resident in HBM.  The default (headline) workload is the
+largest single-GPU config, the Llama-70B MLP shape (config 5: 16 adapters x 2048 tokens, ranks 16..128,
+W 8192 x 28672, bf16); configs 2, 3 and 4 are timed in the same run and reported with the same fields
+under `configs`.  Prints one JSON line: whole-job tokens/s, ms per step, the roofline of the dominant kernel
 (per-kernel times from HIP events recorded on the launch stream), the LoRA-only path against
 the HBM roofline, and the CPU oracle timed on a bounded sample of the same workload.
 """
@@ -176,12 +177,252 @@ def bench_kernel_table(args, np, torch, ml, wl) -> int:
     return 0
 
 
+KERNEL_SOURCES = ("mfma_common.h", "mfma_gemm.hip", "mfma_lora.hip", "plan.hip", "common.h")
+
+
+def kernel_sources_sha256() -> str:
+    """Hash of the kernel sources a PMC summary under profiles/ was measured on (it names the same hash)."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_2604_05426_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
+def committed_traffic(config: int):
+    """HBM-side bytes per launch from the committed rocprofv3 --pmc summary of this config (FETCH_SIZE and WRITE_SIZE,
+    each scaled by what the same counter reads for a plain copy of known size).  The summary names the hash of the
+    kernel sources it was measured on; if the sources have changed since, nothing is reported."""
+    prof = os.path.join(ROOT, "profiles", f"bench_config{config}_pmc_traffic.md")
+    if not os.path.exists(prof):
+        return {}, None
+    names = {"fused_gemm_kernel<true>": "gemm_fwd", "fused_gemm_kernel<false>": "gemm_bwd",
+             "shrink_tiled_kernel<true": "shrink", "shrink_tiled_kernel<false": "dshrink",
+             "shrink_kernel<true": "shrink", "shrink_kernel<false": "dshrink", "wgrad_kernel": "wgrad"}
+    traffic, sha = {}, None
+    for line in open(prof):
+        parts = line.split()
+        if len(parts) == 3 and parts[0] == "traffic_bytes" and parts[1] in names:
+            traffic[names[parts[1]]] = traffic.get(names[parts[1]], 0.0) + float(parts[2])
+        if len(parts) == 2 and parts[0] == "kernel_sources_sha256":
+            sha = parts[1]
+    if sha != kernel_sources_sha256():
+        return {}, f"profiles/{os.path.basename(prof)} was measured on other kernel sources"
+    return traffic, f"profiles/{os.path.basename(prof)}"
+
+
+def cpu_oracle_baseline(w, np, budget_s: float):
+    """The CPU oracle as it stands (naive fp64 loops, OpenMP over rows) on a bounded sample of the workload: the first
+    rows of every adapter's segment, whole fwd + bwd.  A short calibration run sizes the sample for about budget_s."""
+    from oracle import multilora_oracle as orc
+
+    def sample(per_adapter):
+        keep, lens = [], []
+        for i in range(w.N):
+            c = min(per_adapter, w.seg_lens[i])
+            keep.extend(range(w.offsets[i], w.offsets[i] + c))
+            lens.append(c)
+        off = [0] + [int(x) for x in np.cumsum(lens)]
+        Xs, dYs = np.ascontiguousarray(w.X[keep]), np.ascontiguousarray(w.dY[keep])
+        t0 = time.perf_counter()
+        fw = orc.forward(Xs, w.W, w.A, w.B, w.scales, off)
+        orc.backward(dYs, Xs, w.W, w.A, w.B, w.scales, off, S=fw.S)
+        return len(keep), time.perf_counter() - t0
+
+    # calibration: about 4 GFLOP of oracle work, at least one token per adapter
+    per_token = 4.0 * w.k * w.n
+    cal_per_adapter = int(max(1, min(max(w.seg_lens), 4e9 / per_token / max(1, w.N))))
+    cal_tokens, cal_dt = sample(cal_per_adapter)
+    per_adapter = int(max(1, min(max(w.seg_lens), (budget_s / max(cal_dt, 1e-3)) * cal_tokens / max(1, w.N))))
+    ntok, dt = sample(per_adapter)
+    return {"value": ntok / dt, "unit": "tokens/s", "cores": orc.num_threads(), "kind": "oracle", "seconds": dt,
+            "sample": f"first {per_adapter} tokens of each of the {w.N} adapters ({ntok} of {w.T} tokens), "
+                      f"whole fwd+bwd (Y, S, dS, dX, dA_i, dB_i), naive fp64 loops"}
+
+
+def measure_layer(config: int, args, mods, extras: bool, lora_and_base: bool, ceilings: bool, cpu_budget_s: float) -> dict:
+    """Everything bench.py reports for one benchmark config (1-based): the timed fused step, per-kernel times and
+    roofline fractions, the LoRA-only path against the HBM roofline, the frozen-weight GEMMs alone, the CPU oracle."""
+    np, torch, ml, wl, DeviceLayer = mods
+    t_draw = time.perf_counter()
+    w = wl.config(config - 1)
+    dl = DeviceLayer(w, canary=0.0, guards=False)
+    draw_s = time.perf_counter() - t_draw
+    K, W = args.steps, args.warmup
+    T, k, n, R1 = w.T, w.k, w.n, w.R1
+    e = 2 if w.dtype == "bf16" else 4
+    sum_r = sum(r for r, t in zip(w.ranks, w.seg_lens) if t > 0)
+
+    def step(flags=0):
+        dl.forward(flags)
+        dl.backward(flags)
+
+    def timed(fn, reps):
+        start, end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        start.record()
+        for _ in range(reps):
+            fn()
+        end.record()
+        torch.cuda.synchronize()
+        return start.elapsed_time(end) / reps
+
+    for _ in range(W):
+        step()
+    # The GPU's power management needs tens of milliseconds of continuous load to settle its clocks (the first ~50 steps
+    # after idle run up to 10 % slower).  Keep stepping, untimed, until 0.2 s of load have passed, so that the K timed
+    # steps measure the steady state whatever W was asked for.
+    extra_warmup = 0
+    torch.cuda.synchronize()
+    t_settle = time.perf_counter()
+    while time.perf_counter() - t_settle < 0.2 and extra_warmup < 2000:
+        for _ in range(10 if T * k * n < 1e12 else 2):
+            step()
+            extra_warmup += 1
+        torch.cuda.synchronize()
+    ms_step = timed(step, K)
+
+    flops_base = 4.0 * T * k * n
+    flops_lora = 6.0 * R1 * (k + n)
+    flops = flops_base + flops_lora
+    out = {
+        "workload": f"config{config}:{w.name}", "dtype": w.dtype, "T": T, "k": k, "n": n, "adapters": w.N,
+        "ranks": w.ranks, "tokens_per_adapter": w.seg_lens, "mode": "fused fwd+bwd",
+        "value": T / (ms_step * 1e-3), "unit": "tokens/s", "ms_per_step": ms_step, "steps": K, "warmup": W,
+        "warmup_clock_settle_steps": extra_warmup,
+        "tflops": flops / (ms_step * 1e-3) / 1e12,
+        "frac_bf16_mfma_peak_whole_step": flops / (ms_step * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS,
+        "host_input_generation_s": draw_s,
+    }
+
+    if extras:
+        # per-kernel times: the same K steps again, every launch bracketed by HIP events on its stream
+        dl.plan.profile_begin(K * 16)
+        for _ in range(K):
+            step()
+        recs = dl.plan.profile_end(K * 16)
+        per = {}
+        for kid, ms in recs:
+            per.setdefault(ml.KERNEL_NAMES[kid], []).append(ms)
+        kern = {name: {"launches_per_step": len(v) / K, "avg_ms": float(np.mean(v))} for name, v in per.items()}
+        # algorithmic work of one launch of each kernel
+        alg = {
+            "gemm_fwd": ("mfma", 2.0 * T * k * n + 2.0 * R1 * n),
+            "gemm_bwd": ("mfma", 2.0 * T * k * n + 2.0 * R1 * k),
+            "shrink": ("hbm", (T * k + sum_r * k + R1) * e),
+            "dshrink": ("hbm", (T * n + sum_r * n + R1) * e),
+            "wgrad": ("hbm", (T * k + T * n + 2 * R1 + sum_r * (k + n)) * e),
+        }
+        for name, (bound, work) in alg.items():
+            if name in kern:
+                # a kernel that a plan launches several times per step (one launch per rank class) is priced as a whole
+                t = kern[name]["avg_ms"] * kern[name]["launches_per_step"] * 1e-3
+                if bound == "mfma":
+                    kern[name].update(bound="mfma", achieved_tflops=work / t / 1e12,
+                                      frac=work / t / 1e12 / PEAK_BF16_MFMA_TFLOPS)
+                else:
+                    kern[name].update(bound="hbm", achieved_gbs=work / t / 1e9, frac=work / t / 1e9 / PEAK_HBM_GBS)
+        out["kernels"] = kern
+        traffic, traffic_source = committed_traffic(config)
+        named = [nm for nm in kern if nm in alg]
+        if not named:
+            # fp32 / odd-width plans run every step through the grouped FMA kernel on the vector ALUs
+            out["roofline"] = {"kernel": "fma_grouped_gemm_kernel (all launches of a step)", "bound": "alu",
+                               "achieved": flops / (ms_step * 1e-3) / 1e12, "peak": 157.3, "unit": "TFLOP/s",
+                               "frac": flops / (ms_step * 1e-3) / 1e12 / 157.3, "traffic": None}
+        dom = max(named, key=lambda nm: kern[nm]["avg_ms"] * kern[nm]["launches_per_step"]) if named else None
+        bound, work = alg[dom] if dom else (None, 0.0)
+        t = kern[dom]["avg_ms"] * kern[dom]["launches_per_step"] * 1e-3 if dom else 1.0
+        if bound == "mfma":
+            out["roofline"] = {"kernel": dom, "bound": "mfma", "achieved": work / t / 1e12, "peak": PEAK_BF16_MFMA_TFLOPS,
+                               "unit": "TFLOP/s", "frac": work / t / 1e12 / PEAK_BF16_MFMA_TFLOPS, "traffic": traffic.get(dom),
+                               "traffic_source": traffic_source, "algorithmic_flop_per_launch": work,
+                               "avg_kernel_ms": kern[dom]["avg_ms"]}
+        elif bound == "hbm":
+            out["roofline"] = {"kernel": dom, "bound": "hbm", "achieved": work / t / 1e9, "peak": PEAK_HBM_GBS,
+                               "unit": "GB/s", "frac": work / t / 1e9 / PEAK_HBM_GBS, "traffic": traffic.get(dom),
+                               "traffic_source": traffic_source, "algorithmic_bytes_per_launch": work,
+                               "avg_kernel_ms": kern[dom]["avg_ms"]}
+        if traffic:
+            out["traffic_per_launch_bytes"] = traffic
+
+    if extras and lora_and_base:
+        # LoRA grouped path alone (W skipped; Y and dX updated in place) against the HBM roofline
+        for _ in range(2):
+            step(ml.FLAG_LORA_ONLY)
+        ms_lf = timed(lambda: dl.forward(ml.FLAG_LORA_ONLY), K)
+        ms_lb = timed(lambda: dl.backward(ml.FLAG_LORA_ONLY), K)
+        small = (2 * sum_r * (k + n) + 2 * R1) * e
+        bytes_f = (T * k + 2 * T * n) * e + (sum_r * (k + n) + 2 * R1) * e
+        bytes_b = (2 * T * n + T * k + 2 * T * k) * e + small + 3 * R1 * e
+        out["lora_path"] = {
+            "mode": "MLORA_FLAG_LORA_ONLY", "fwd_ms": ms_lf, "bwd_ms": ms_lb,
+            "fwd_gbs": bytes_f / (ms_lf * 1e-3) / 1e9, "bwd_gbs": bytes_b / (ms_lb * 1e-3) / 1e9,
+            "frac_hbm": (bytes_f + bytes_b) / ((ms_lf + ms_lb) * 1e-3) / 1e9 / PEAK_HBM_GBS,
+            "algorithmic_bytes_fwd": bytes_f, "algorithmic_bytes_bwd": bytes_b,
+        }
+        # frozen-weight GEMMs alone, for the cost of the LoRA terms inside the fused step
+        for _ in range(2):
+            step(ml.FLAG_BASE_ONLY)
+        ms_base = timed(lambda: step(ml.FLAG_BASE_ONLY), K)
+        # the paper's decoupled execution (base GEMM, grouped shrink, fused GEMM-add as separate launches) is
+        # BASE_ONLY followed by LORA_ONLY; the default fused step folds the expand into the base GEMM
+        out["decoupled"] = {"ms_per_step": ms_base + ms_lf + ms_lb, "decoupled_over_fused": (ms_base + ms_lf + ms_lb) / ms_step}
+        out["base_only"] = {"ms_per_step": ms_base, "tflops": flops_base / (ms_base * 1e-3) / 1e12,
+                            "frac_bf16_mfma_peak": flops_base / (ms_base * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS,
+                            "fused_over_base": ms_step / ms_base}
+
+    if ceilings:
+        # what this GPU sustains right now for the two resources the fractions above are priced against (the published
+        # peaks stay the denominators of `frac`): a register-only loop of the GEMM's 16x16x32 MFMAs on random operands
+        # (runs into the board power limit like the GEMM does) and on zeros (no throttling), and a streaming read
+        scratch = torch.zeros(4096, dtype=torch.uint8, device=dl.device)
+        buf = torch.zeros(1 << 30, dtype=torch.uint8, device=dl.device)
+        meas = {
+            "mfma_loop_random_tflops": ml.multi_lora_calib_mfma(True, scratch, dl.stream),
+            "mfma_loop_zeros_tflops": ml.multi_lora_calib_mfma(False, scratch, dl.stream),
+            "stream_read_gbs": ml.multi_lora_calib_read(buf, 1 << 30, scratch, dl.stream),
+        }
+        del buf
+        out["measured_ceilings"] = meas
+        if out.get("roofline", {}).get("bound") == "mfma":
+            out["roofline"]["frac_of_measured_mfma_loop"] = out["roofline"]["achieved"] / meas["mfma_loop_random_tflops"]
+        if "lora_path" in out:
+            lp = out["lora_path"]
+            lp["frac_of_measured_stream_read"] = ((lp["fwd_gbs"] * lp["fwd_ms"] + lp["bwd_gbs"] * lp["bwd_ms"])
+                                                  / (lp["fwd_ms"] + lp["bwd_ms"]) / meas["stream_read_gbs"])
+
+    if args.calib_copy:
+        src = torch.zeros(1 << 30, dtype=torch.uint8, device=dl.device)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        out["calib_copy_bytes"] = 1 << 30
+        del src, dst
+
+    dl.plan.destroy()
+    del dl
+    torch.cuda.empty_cache()
+    if cpu_budget_s > 0:
+        out["cpu_baseline"] = cpu_oracle_baseline(w, np, cpu_budget_s)
+    return out
+
+
+HEADLINE_CONFIG = 5       # the largest single-GPU configuration: Llama-70B MLP shape, 16 adapters x 2048 tokens
+OTHER_CONFIGS = (2, 3, 4)
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=2, help="benchmark config number 1..5 (default 2: Llama-8B q_proj)")
+    ap.add_argument("--config", type=int, default=None,
+                    help="time only this benchmark config (1..5).  Default: config 5 (Llama-70B MLP shape) as the headline, "
+                         "and configs 2, 3, 4 with the same fields in `configs`")
+    ap.add_argument("--no-configs", action="store_true", help="headline config only, no `configs` array")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-extra", action="store_true", help="skip the per-kernel / LoRA-only passes")
     ap.add_argument("--fused-only", action="store_true",
@@ -217,194 +458,28 @@ def main() -> int:
     if args.kernel_table:
         return bench_kernel_table(args, np, torch, ml, wl)
 
-    index = args.config - 1
-    w = wl.config(index)
-    dl = DeviceLayer(w, canary=0.0)
-    K, W = args.steps, args.warmup
-    T, k, n, R1 = w.T, w.k, w.n, w.R1
-    e = 2 if w.dtype == "bf16" else 4
-    sum_r = sum(r for r, t in zip(w.ranks, w.seg_lens) if t > 0)
-
-    def step(flags=0):
-        dl.forward(flags)
-        dl.backward(flags)
-
-    def timed(fn, reps):
-        start, end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
-        start.record()
-        for _ in range(reps):
-            fn()
-        end.record()
-        torch.cuda.synchronize()
-        return start.elapsed_time(end) / reps
-
-    for _ in range(W):
-        step()
-    # The GPU's power management needs tens of milliseconds of continuous load to settle its clocks (the first ~50 steps
-    # after idle run up to 10 % slower).  Keep stepping, untimed, until 0.2 s of load have passed, so that the K timed
-    # steps measure the steady state whatever W was asked for.
-    extra_warmup = 0
-    torch.cuda.synchronize()
-    t_settle = time.perf_counter()
-    while time.perf_counter() - t_settle < 0.2 and extra_warmup < 2000:
-        for _ in range(10):
-            step()
-        torch.cuda.synchronize()
-        extra_warmup += 10
-    ms_step = timed(step, K)
-
-    flops_base = 4.0 * T * k * n
-    flops_lora = 6.0 * R1 * (k + n)
-    flops = flops_base + flops_lora
-    tokens_per_s = T / (ms_step * 1e-3)
+    mods = (np, torch, ml, wl, DeviceLayer)
+    head_cfg = args.config if args.config is not None else HEADLINE_CONFIG
+    extras = not args.no_extra
+    full = extras and not args.fused_only
+    h = measure_layer(head_cfg, args, mods, extras=extras, lora_and_base=full, ceilings=full,
+                      cpu_budget_s=0.0 if args.no_cpu else 15.0)
     out = {
-        "metric": "multi-LoRA layer fwd+bwd tokens/s", "value": tokens_per_s, "unit": "tokens/s",
-        "n_gpus": 1, "steps": K, "warmup": W, "warmup_clock_settle_steps": extra_warmup, "ms_per_step": ms_step, "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None,
-        "dtype": w.dtype, "data": "synthetic",
-        "config": {"workload": f"config{args.config}:{w.name}", "T": T, "k": k, "n": n, "adapters": w.N,
-                   "ranks": w.ranks, "tokens_per_adapter": w.seg_lens, "mode": "fused fwd+bwd"},
-        "tflops": flops / (ms_step * 1e-3) / 1e12,
-        "frac_bf16_mfma_peak_whole_step": flops / (ms_step * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS,
+        "metric": "multi-LoRA layer fwd+bwd tokens/s", "value": h["value"], "unit": "tokens/s",
+        "n_gpus": 1, "steps": h["steps"], "warmup": h["warmup"], "warmup_clock_settle_steps": h["warmup_clock_settle_steps"],
+        "ms_per_step": h["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": h["dtype"], "data": "synthetic",
+        "config": {"workload": h["workload"], "T": h["T"], "k": h["k"], "n": h["n"], "adapters": h["adapters"],
+                   "ranks": h["ranks"], "tokens_per_adapter": h["tokens_per_adapter"], "mode": h["mode"]},
     }
-
-    if not args.no_extra:
-        # per-kernel times: the same K steps again, every launch bracketed by HIP events on its stream
-        dl.plan.profile_begin(K * 16)
-        for _ in range(K):
-            step()
-        recs = dl.plan.profile_end(K * 16)
-        per = {}
-        for kid, ms in recs:
-            per.setdefault(ml.KERNEL_NAMES[kid], []).append(ms)
-        kern = {name: {"launches_per_step": len(v) / K, "avg_ms": float(np.mean(v))} for name, v in per.items()}
-        # algorithmic work of one launch of each kernel
-        alg = {
-            "gemm_fwd": ("mfma", 2.0 * T * k * n + 2.0 * R1 * n),
-            "gemm_bwd": ("mfma", 2.0 * T * k * n + 2.0 * R1 * k),
-            "shrink": ("hbm", (T * k + sum_r * k + R1) * e),
-            "dshrink": ("hbm", (T * n + sum_r * n + R1) * e),
-            "wgrad": ("hbm", (T * k + T * n + 2 * R1 + sum_r * (k + n)) * e),
-        }
-        for name, (bound, work) in alg.items():
-            if name in kern:
-                t = kern[name]["avg_ms"] * 1e-3
-                if bound == "mfma":
-                    kern[name].update(bound="mfma", achieved_tflops=work / t / 1e12,
-                                      frac=work / t / 1e12 / PEAK_BF16_MFMA_TFLOPS)
-                else:
-                    kern[name].update(bound="hbm", achieved_gbs=work / t / 1e9, frac=work / t / 1e9 / PEAK_HBM_GBS)
-        out["kernels"] = kern
-        # HBM-side traffic per launch from the committed rocprofv3 --pmc summary (FETCH_SIZE / WRITE_SIZE, scaled by a
-        # copy kernel of known size); it was measured on this workload only
-        traffic = {}
-        prof = os.path.join(ROOT, "profiles", "bench_config2_pmc_traffic_mfma.md")
-        if args.config == 2 and os.path.exists(prof):
-            names = {"fused_gemm_kernel<true>": "gemm_fwd", "fused_gemm_kernel<false>": "gemm_bwd",
-                     "shrink_tiled_kernel<true": "shrink", "shrink_tiled_kernel<false": "dshrink",
-                     "shrink_kernel<true": "shrink", "shrink_kernel<false": "dshrink", "wgrad_kernel": "wgrad"}
-            for line in open(prof):
-                parts = line.split()
-                if len(parts) == 3 and parts[0] == "traffic_bytes" and parts[1] in names:
-                    traffic[names[parts[1]]] = float(parts[2])
-        named = [nm for nm in kern if nm in alg]
-        if not named:
-            # fp32 / odd-width plans run every step through the grouped FMA kernel on the vector ALUs
-            out["roofline"] = {"kernel": "fma_grouped_gemm_kernel (all launches of a step)", "bound": "alu",
-                               "achieved": flops / (ms_step * 1e-3) / 1e12, "peak": 157.3, "unit": "TFLOP/s",
-                               "frac": flops / (ms_step * 1e-3) / 1e12 / 157.3, "traffic": None}
-        dom = max(named, key=lambda nm: kern[nm]["avg_ms"] * kern[nm]["launches_per_step"]) if named else None
-        bound, work = alg[dom] if dom else (None, 0.0)
-        t = kern[dom]["avg_ms"] * 1e-3 if dom else 1.0
-        if bound == "mfma":
-            out["roofline"] = {"kernel": dom, "bound": "mfma", "achieved": work / t / 1e12, "peak": PEAK_BF16_MFMA_TFLOPS,
-                               "unit": "TFLOP/s", "frac": work / t / 1e12 / PEAK_BF16_MFMA_TFLOPS, "traffic": traffic.get(dom),
-                               "avg_kernel_ms": kern[dom]["avg_ms"]}
-        elif bound == "hbm":
-            out["roofline"] = {"kernel": dom, "bound": "hbm", "achieved": work / t / 1e9, "peak": PEAK_HBM_GBS,
-                               "unit": "GB/s", "frac": work / t / 1e9 / PEAK_HBM_GBS, "traffic": traffic.get(dom),
-                               "avg_kernel_ms": kern[dom]["avg_ms"]}
-
-    if not args.no_extra and not args.fused_only:
-        # LoRA grouped path alone (W skipped; Y and dX updated in place) against the HBM roofline
-        for _ in range(2):
-            step(ml.FLAG_LORA_ONLY)
-        ms_lf = timed(lambda: dl.forward(ml.FLAG_LORA_ONLY), K)
-        ms_lb = timed(lambda: dl.backward(ml.FLAG_LORA_ONLY), K)
-        small = (2 * sum_r * (k + n) + 2 * R1) * e
-        bytes_f = (T * k + 2 * T * n) * e + (sum_r * (k + n) + 2 * R1) * e
-        bytes_b = (2 * T * n + T * k + 2 * T * k) * e + small + 3 * R1 * e
-        out["lora_path"] = {
-            "mode": "MLORA_FLAG_LORA_ONLY", "fwd_ms": ms_lf, "bwd_ms": ms_lb,
-            "fwd_gbs": bytes_f / (ms_lf * 1e-3) / 1e9, "bwd_gbs": bytes_b / (ms_lb * 1e-3) / 1e9,
-            "frac_hbm": (bytes_f + bytes_b) / ((ms_lf + ms_lb) * 1e-3) / 1e9 / PEAK_HBM_GBS,
-            "algorithmic_bytes_fwd": bytes_f, "algorithmic_bytes_bwd": bytes_b,
-        }
-        # frozen-weight GEMMs alone, for the cost of the LoRA terms inside the fused step
-        for _ in range(2):
-            step(ml.FLAG_BASE_ONLY)
-        ms_base = timed(lambda: step(ml.FLAG_BASE_ONLY), K)
-        # the paper's decoupled execution (base GEMM, grouped shrink, fused GEMM-add as separate launches) is
-        # BASE_ONLY followed by LORA_ONLY; the default fused step folds the expand into the base GEMM
-        out["decoupled"] = {"ms_per_step": ms_base + ms_lf + ms_lb, "decoupled_over_fused": (ms_base + ms_lf + ms_lb) / ms_step}
-        out["base_only"] = {"ms_per_step": ms_base, "tflops": flops_base / (ms_base * 1e-3) / 1e12,
-                            "frac_bf16_mfma_peak": flops_base / (ms_base * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS,
-                            "fused_over_base": ms_step / ms_base}
-
-    if not args.no_extra and not args.fused_only:
-        # what this GPU sustains right now for the two resources the fractions above are priced against (the published
-        # peaks stay the denominators of `frac`): a register-only loop of the GEMM's 16x16x32 MFMAs on random operands
-        # (runs into the board power limit like the GEMM does) and on zeros (no throttling), and a streaming read
-        scratch = torch.zeros(4096, dtype=torch.uint8, device=dl.device)
-        buf = torch.zeros(1 << 30, dtype=torch.uint8, device=dl.device)
-        meas = {
-            "mfma_loop_random_tflops": ml.multi_lora_calib_mfma(True, scratch, dl.stream),
-            "mfma_loop_zeros_tflops": ml.multi_lora_calib_mfma(False, scratch, dl.stream),
-            "stream_read_gbs": ml.multi_lora_calib_read(buf, 1 << 30, scratch, dl.stream),
-        }
-        del buf
-        out["measured_ceilings"] = meas
-        if out.get("roofline", {}).get("bound") == "mfma":
-            out["roofline"]["frac_of_measured_mfma_loop"] = out["roofline"]["achieved"] / meas["mfma_loop_random_tflops"]
-        if "lora_path" in out:
-            out["lora_path"]["frac_of_measured_stream_read"] = (
-                (out["lora_path"]["fwd_gbs"] * out["lora_path"]["fwd_ms"] + out["lora_path"]["bwd_gbs"] * out["lora_path"]["bwd_ms"])
-                / (out["lora_path"]["fwd_ms"] + out["lora_path"]["bwd_ms"]) / meas["stream_read_gbs"])
-
-    if args.calib_copy:
-        src = torch.zeros(1 << 30, dtype=torch.uint8, device=dl.device)
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        out["calib_copy_bytes"] = 1 << 30
-
-    if not args.no_cpu:
-        # CPU oracle (as it stands) on a bounded sample: the first rows of every adapter's segment
-        from oracle import multilora_oracle as orc
-        def sample(per_adapter):
-            keep, lens = [], []
-            for i in range(w.N):
-                c = min(per_adapter, w.seg_lens[i])
-                keep.extend(range(w.offsets[i], w.offsets[i] + c))
-                lens.append(c)
-            off = [0] + [int(x) for x in np.cumsum(lens)]
-            Xs, dYs = np.ascontiguousarray(w.X[keep]), np.ascontiguousarray(w.dY[keep])
-            t0 = time.perf_counter()
-            fw = orc.forward(Xs, w.W, w.A, w.B, w.scales, off)
-            orc.backward(dYs, Xs, w.W, w.A, w.B, w.scales, off, S=fw.S)
-            return len(keep), time.perf_counter() - t0
-
-        # a short calibration run sizes the sample for roughly 15 s of CPU work (capped at the whole batch)
-        cal_tokens, cal_dt = sample(max(1, 256 // max(1, w.N)))
-        per_adapter = int(max(1, min(max(w.seg_lens), (15.0 / max(cal_dt, 1e-3)) * cal_tokens / max(1, w.N))))
-        ntok, dt = sample(per_adapter)
-        keep = range(ntok)
-        out["cpu_baseline"] = {"value": len(keep) / dt, "unit": "tokens/s", "cores": orc.num_threads(),
-                               "kind": "oracle", "seconds": dt,
-                               "sample": f"first {per_adapter} tokens of each of the {w.N} adapters "
-                                         f"({len(keep)} of {T} tokens), full fwd+bwd, naive fp64 loops"}
+    for key in ("tflops", "frac_bf16_mfma_peak_whole_step", "kernels", "roofline", "traffic_per_launch_bytes", "lora_path",
+                "decoupled", "base_only", "measured_ceilings", "calib_copy_bytes", "cpu_baseline", "host_input_generation_s"):
+        if key in h:
+            out[key] = h[key]
+    if args.config is None and not args.no_configs:
+        # the other bf16 configs, same fields, a shorter CPU leg each
+        out["configs"] = [measure_layer(c, args, mods, extras=extras, lora_and_base=full, ceilings=False,
+                                        cpu_budget_s=0.0 if args.no_cpu else 4.0) for c in OTHER_CONFIGS]
     print(json.dumps(out))
     return 0
 

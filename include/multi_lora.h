@@ -80,14 +80,23 @@ typedef enum {
     MLORA_TABLE_GEMM_ROW_TILES = 1, /* row tiles of the flat buffer used by the fused GEMMs,
                                    4 x int32 per entry: first row, rows, first adapter touched,
                                    last adapter touched + 1. */
-    MLORA_TABLE_WGRAD_CHUNKS = 2 /* token chunks reduced by the weight-gradient kernels, 4 x int32:
+    MLORA_TABLE_WGRAD_CHUNKS = 2, /* token chunks reduced by the weight-gradient kernels, 4 x int32:
                                    adapter, chunk index within the adapter, first global row, rows.
                                    Same entries as a block table with MLORA_GEO_WGRAD_CHUNK_ROWS rows per
                                    block (MLORA_GEO_WGRAD_CHUNK_ROWS_WIDE for adapters with a rank above 64; the
                                    two differ only in plans that hold ranks on both sides of 64, whose two rank
-                                   classes are balanced separately), but ordered by decreasing cost rows x (64 + rank), ties in
+                                   classes are balanced separately), in launch order: adapters with a rank above 64
+                                   first, then the others; inside a class by decreasing cost rows x (64 + rank), ties in
                                    canonical order (the device-side balancing of heterogeneous segments);
-                                   tables above 16384 entries keep the canonical order. */
+                                   tables above 16384 entries keep the canonical order inside each class. */
+    MLORA_TABLE_CLASS_BLOCKS = 3, /* the entries of MLORA_TABLE_ROW_BLOCKS in the order the grouped kernels walk them:
+                                   adapters with a rank above 64 first (their blocks run longest and take a kernel
+                                   build of their own), then the others, canonical order inside a class. */
+    MLORA_TABLE_GEMM_BAND_ORDER = 4 /* launch order of the fused GEMMs' row bands (MLORA_GEO_GEMM_BAND_TILES consecutive
+                                   row tiles x all column tiles are in flight together), 4 x int32: band, first row tile,
+                                   row tiles, cost = rank-extension passes of its row tiles (per row tile, one per 64 ranks
+                                   of every adapter that owns rows of it).  Full bands by decreasing cost, ties by band
+                                   index; a last band with fewer row tiles stays last.  Above 16384 bands: band order. */
 } mlora_table;
 
 /* geometry words returned by multi_lora_plan_geometry */
@@ -100,7 +109,12 @@ enum {
     MLORA_GEO_R1_HI = 5,
     MLORA_GEO_USES_MFMA = 6,      /* 1 if the bf16 MFMA kernels serve this plan, 0 for the fp32-FMA kernels */
     MLORA_GEO_WGRAD_CHUNK_ROWS_WIDE = 7, /* token chunk of adapters with a rank above 64 */
-    MLORA_GEO_COUNT = 8
+    MLORA_GEO_BLOCK_ROWS_WIDE = 8,    /* rows per LoRA block of adapters with a rank above 64 */
+    MLORA_GEO_GEMM_BAND_TILES = 9,    /* row tiles per band of the fused GEMMs' tile order */
+    MLORA_GEO_NUM_CUS = 10,           /* compute units the token chunks were balanced for */
+    MLORA_GEO_WGRAD_PANEL_COLS = 11,  /* columns of X / dY one weight-gradient work item covers */
+    MLORA_GEO_WGRAD_MIN_CHUNK_ROWS = 12, /* the token chunk is never cut below this */
+    MLORA_GEO_COUNT = 13
 };
 
 /*
@@ -115,7 +129,10 @@ enum {
  *   ranks        host [N], each in [0, MLORA_MAX_RANK]; rank 0 = rows pass through as X W
  *   scales       host [N], finite
  *   seg_offsets  host [N+1], seg_offsets[0] = 0, non-decreasing, seg_offsets[N] = T (N >= 1)
- * The only entry point that allocates device memory; freed by multi_lora_plan_destroy.
+ * The token chunks of the weight-gradient items are chosen, and all tables are built and ordered, by device kernels from
+ * the offsets and ranks (the device-side scheduler); the call waits for the first of them, which runs on a stream of the
+ * library's own, to read back the sizes it chose - it does not wait for work queued on `stream`.
+ * With multi_lora_plan_create_like the only entry point that allocates device memory; freed by multi_lora_plan_destroy.
  */
 int multi_lora_plan_create(mlora_plan** out, int dtype, int64_t T, int64_t k, int64_t n,
                            int32_t N, const int32_t* ranks, const float* scales,
@@ -127,7 +144,8 @@ int multi_lora_plan_create(mlora_plan** out, int dtype, int64_t T, int64_t k, in
  * uses the device tables of `base` in place (row blocks, row tiles, offsets, ranks, scales; the weight-gradient
  * item table too when both shapes chunk the tokens alike) and builds only what depends on the layer: its pointer
  * table and workspace layout.  `stream` must be the stream `base` was created on.  The two plans are independent
- * afterwards: either may be destroyed first, and each is used by one stream at a time as usual.
+ * afterwards: either may be destroyed first - also along a chain of plans each made from the one before -, and each is
+ * used by one stream at a time as usual.
  */
 int multi_lora_plan_create_like(mlora_plan** out, const mlora_plan* base, int64_t k, int64_t n, void* stream);
 
@@ -275,7 +293,9 @@ const char* multi_lora_version(void);
  *                histories; both >= tau_slope for patience_div evaluations in a row -> MLORA_EXIT_DIVERGING;
  *   overfitting: (val - lhat) / lhat > tau_gap for patience_ovf evaluations in a row -> MLORA_EXIT_OVERFITTING
  *                (multi_lora_monitor_state names the evaluation step with the best validation loss to restore);
- * divergence is tested first.  A decision is final: later reports for that adapter return it again.
+ * divergence is tested first.  A training or validation loss that is NaN or infinite is divergence decided at once
+ * (MLORA_EXIT_DIVERGING from that report on; it enters neither the moving average nor the histories).
+ * A decision is final: later reports for that adapter return it again.
  * multi_lora_monitor_warmup_select is the warmup boundary: the surviving adapters are ranked by their latest
  * validation loss (ascending, ties in adapter order, never-evaluated last) and all but the best
  * ceil(ratio x survivors) become MLORA_EXIT_UNDERPERFORMING; `status` (host, [n]) receives every adapter's status.

@@ -13,9 +13,10 @@ from typing import List, Optional, Sequence
 
 F32, BF16 = 0, 1
 FLAG_BASE_ONLY, FLAG_LORA_ONLY, FLAG_ACCUM_GRADS = 1, 2, 4
-TABLE_ROW_BLOCKS, TABLE_GEMM_ROW_TILES, TABLE_WGRAD_CHUNKS = 0, 1, 2
+TABLE_ROW_BLOCKS, TABLE_GEMM_ROW_TILES, TABLE_WGRAD_CHUNKS, TABLE_CLASS_BLOCKS, TABLE_GEMM_BAND_ORDER = 0, 1, 2, 3, 4
 GEO_BLOCK_ROWS, GEO_GEMM_TILE_ROWS, GEO_GEMM_TILE_COLS, GEO_WGRAD_CHUNK_ROWS = 0, 1, 2, 3
-GEO_R1_LO, GEO_R1_HI, GEO_USES_MFMA, GEO_WGRAD_CHUNK_ROWS_WIDE, GEO_COUNT = 4, 5, 6, 7, 8
+GEO_R1_LO, GEO_R1_HI, GEO_USES_MFMA, GEO_WGRAD_CHUNK_ROWS_WIDE = 4, 5, 6, 7
+GEO_BLOCK_ROWS_WIDE, GEO_GEMM_BAND_TILES, GEO_NUM_CUS, GEO_WGRAD_PANEL_COLS, GEO_WGRAD_MIN_CHUNK_ROWS, GEO_COUNT = 8, 9, 10, 11, 12, 13
 MAX_RANK, MAX_ADAPTERS = 128, 4096
 
 STATUS_NAMES = {0: "MLORA_OK", -1: "MLORA_ERR_NULL", -2: "MLORA_ERR_SHAPE", -3: "MLORA_ERR_SEGMENTS",

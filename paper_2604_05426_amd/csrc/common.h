@@ -14,6 +14,8 @@ namespace mlora {
 
 // ---- tiling constants (reported through multi_lora_plan_geometry) ------------------
 constexpr int kBlockRows = 64;       // rows per LoRA block of the shrink kernels
+constexpr int kBlockRowsWide = 64;   // the same for adapters of the wide rank class
+constexpr int kGemmBandTiles = 8;    // row tiles per band of the fused GEMM's tile order
 constexpr int kGemmTileRows = 256;   // fused GEMM macro tile
 constexpr int kGemmTileCols = 256;
 constexpr int kWgradMinChunkRows = 512;  // smallest token chunk one weight-gradient work item reduces
@@ -51,10 +53,24 @@ struct PlanView {
     const float* scale;     // [N]
     const int64_t* soff;    // [N+1] element offsets of S_i / dS_i in the ragged buffers
     const AdapterPtrs* ptrs; // [N]
-    const Entry4* row_blocks;  int32_t n_row_blocks;
+    const Entry4* row_blocks;  int32_t n_row_blocks;      // canonical order (adapter, block)
+    const Entry4* class_blocks; int32_t n_class_blocks;   // the same blocks, wide rank class first: what the kernels walk
     const Entry4* gemm_tiles;  int32_t n_gemm_tiles;
+    const Entry4* band_order;  int32_t n_bands;           // launch order of the fused GEMM's row bands
     const Entry4* wgrad_chunks; int32_t n_wgrad_chunks;
-    const int32_t* wgrad_chunk_start; // [N+1] first chunk of each adapter
+    const int32_t* wgrad_chunk_start; // [N+1] canonical prefix: adapter i has start[i+1] - start[i] chunks
+    const int64_t* part_off;   // [N] float offset of adapter i's partial weight-gradient block (adapters with > 1 chunk)
+};
+
+// What the device-side scheduler chose and counted; read back once by plan creation (sizes of the chunk table and of
+// the workspace, launch grids).
+struct DevGeo {
+    int32_t chunk_rows, chunk_rows_wide;      // token chunk of the weight-gradient items per rank class
+    int32_t n_chunks, n_chunks_wide;          // entries of the chunk table; the first n_chunks_wide are the wide class
+    int32_t max_chunks_per_adapter, n_reduce; // n_reduce adapters have their tokens split over several chunks
+    int64_t partial_floats;                   // fp32 partial sums those adapters need
+    int64_t R1;                               // cross-checks of the sizes the host derived from the same offsets
+    int32_t n_row_blocks, n_blocks_wide;
 };
 
 }  // namespace mlora
@@ -66,43 +82,38 @@ struct mlora_plan {
     std::vector<int32_t> ranks;
     std::vector<float> scales;
     std::vector<int64_t> off;
-    std::vector<int64_t> soff;       // N+1
-    std::vector<int32_t> wchunk_start; // N+1
-    std::vector<int32_t> off32;      // N+1, upload source (kept alive for the async copy)
-    std::vector<int64_t> part_off;   // N+1, upload source
+    std::vector<int32_t> off32;      // N+1, upload source
     int64_t R1 = 0;
     bool use_mfma = false;
-    int32_t n_row_blocks = 0, n_gemm_tiles = 0, n_wgrad_chunks = 0;
+    int32_t n_row_blocks = 0, n_gemm_tiles = 0, n_bands = 0;
     int32_t max_rank = 0;
-    int32_t max_chunks_per_adapter = 0;
-    // row blocks split by rank class (<= 64 / wider): indices into the row-block table, wide class first (its blocks run longest).  Plans that
-    // mix narrow and wide ranks run each class through the kernel build made for it.
-    std::vector<int32_t> block_lists;   // upload source
+    // Row blocks by rank class (<= 64 / wider): the class table puts the wide class first (its blocks run longest); plans
+    // that mix narrow and wide ranks run each class through the kernel build made for it.
     int32_t n_blocks_narrow = 0, n_blocks_wide = 0;
-    int32_t* d_block_lists = nullptr;
-    int32_t wgrad_chunk_rows = 0;     // token chunk of the weight-gradient items (chosen per plan)
-    int32_t wgrad_chunk_rows_wide = 0;   // the same for adapters of the wide rank class (differs only when the plan mixes the classes)
-    // Plans that mix ranks <= 64 and wider ones run the weight-gradient items of the two classes as two launches, each
-    // through the kernel build - and so at the workgroups per CU - its class allows, and chunk the tokens per class.
+    // Weight-gradient items: chosen, counted and ordered on the device (DevGeo).  Plans that mix ranks <= 64 and wider
+    // ones launch the items of the two classes as two launches over their own parts of the table, each through the
+    // kernel build - and so at the workgroups per CU - its class allows, and chunk the tokens per class.
+    mlora::DevGeo geo{};
     int32_t max_rank_narrow = 0;      // largest rank <= 64 among adapters with tokens
     bool ranks_mult8 = true;          // every rank of an adapter with tokens is a multiple of 8
-    bool wgrad_two_classes = false;
-    // one device allocation carved into the tables below; a plan made by multi_lora_plan_create_like also holds the
-    // allocation of the plan whose segmentation tables it uses, so the two may be destroyed in any order
-    std::shared_ptr<mlora::DeviceBlock> d_block, d_shared_block;
-    size_t d_block_bytes = 0;
-    bool shares_tables = false, shares_wgrad_table = false;
+    // Device allocations: the plan's own blocks, and every block of other plans its view points into (a plan made by
+    // multi_lora_plan_create_like uses the segmentation tables of its base in place - and through it those of the
+    // base's base -, so plans may be destroyed in any order).
+    std::vector<std::shared_ptr<mlora::DeviceBlock>> blocks;
+    std::vector<std::shared_ptr<mlora::DeviceBlock>> shared_blocks;
+    bool shares_tables = false;
     mlora::PlanView view{};
     mlora::AdapterPtrs* d_ptrs = nullptr;
-    // host mirror of the device pointer table: a call whose pointers match what the same stream uploaded last skips the upload
+    // host mirror of the device pointer table: a call whose pointers match what the same stream uploaded last skips the
+    // upload.  Once an upload has been recorded into a captured graph the mirror is never trusted again: a replay
+    // rewrites the table behind the host's back.
     std::vector<mlora::AdapterPtrs> ptr_mirror;
     bool ptr_mirror_valid = false;
+    bool ptr_upload_captured = false;
     hipStream_t ptr_mirror_stream = nullptr;
     void* d_probs = nullptr;          // descriptor scratch of the FMA grouped GEMM
     void* d_adamw = nullptr;          // [N] optimizer entries (pointers + hyper-parameters), refreshed per call
-    int64_t* d_part_off = nullptr;    // [N] float offset of each adapter's partial weight-gradient block
-    std::vector<int32_t> reduce_list; // adapters whose tokens are split over several weight-gradient chunks
-    int32_t* d_reduce_list = nullptr;
+    int32_t* d_reduce_list = nullptr; // adapters whose tokens are split over several weight-gradient chunks
     bool has_empty_ranked = false;    // some adapter has a rank but no tokens (its dA, dB are zero-filled)
     size_t ws_ds_bytes = 0;           // workspace: dS
     size_t ws_partial_bytes = 0;      // workspace: fp32 partial weight gradients

@@ -75,7 +75,31 @@ struct PassDesc {
     const u16* b_src; int64_t b_ld;   // NN: (c, col) at b_src[c * b_ld + col];  NT: at b_src[col * b_ld + c]
     bool b_vec;
     int kc;                            // valid contraction length, 1..64
+    bool isolate;                      // rows of other adapters share the tile: see stage_pass
 };
+
+// Isolation of co-located jobs.  A rank-extension pass masks the rows of other adapters by staging zeros for them, and
+// then multiplies those zeros with adapter j's B_j (A_j^T in the backward).  If job j has diverged and its matrices hold
+// Inf or NaN, 0 x Inf = NaN would land in its neighbours' rows of every tile that straddles the segment boundary.  So in
+// such tiles the staged copy of adapter j's operand has its non-finite values replaced by zero, the columns they sat in
+// are flagged, and after the pass's MFMAs the accumulators of adapter j's own rows in flagged columns are set to NaN
+// (the plain definition gives Inf or NaN there).  Flags: one byte per tile column and one "any" word behind them, in a
+// tile buffer the pass does not use.
+constexpr int FLAG_OFF = TILE_BYTES;          // row stage 1 is free during a pass
+constexpr int FLAG_ANY = FLAG_OFF + BN;       // uint32 behind the BN column bytes
+
+// zeroes the non-finite bf16 values of a chunk; bit e of the result is set if element e was non-finite
+__device__ __forceinline__ unsigned drop_nonfinite(uint4& v) {
+    uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    unsigned mask = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        if ((w[e] & 0x7f80u) == 0x7f80u) { w[e] &= 0xffff0000u; mask |= 1u << (2 * e); }
+        if ((w[e] & 0x7f800000u) == 0x7f800000u) { w[e] &= 0x0000ffffu; mask |= 2u << (2 * e); }
+    }
+    v = make_uint4(w[0], w[1], w[2], w[3]);
+    return mask;
+}
 
 // Writes the pass operands into tile buffers 0 and B_SLOT0 in the same swizzled layouts the main loop uses, zero-filled
 // up to a multiple of 32 in the contraction and outside the rows / columns the pass owns.
@@ -105,6 +129,15 @@ __device__ __forceinline__ void stage_pass(unsigned char* lds, const PassDesc& d
             uint4 v = zero4();
             if (krow < d.kc && gcol < ncols)
                 v = load_chunk(d.b_src + (int64_t)krow * d.b_ld + gcol, min(8, ncols - gcol), d.b_vec);
+            if (d.isolate) {
+                const unsigned bad = drop_nonfinite(v);
+                if (bad) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (bad >> e & 1) lds[FLAG_OFF + nc * 8 + e] = 1;
+                    *reinterpret_cast<uint32_t*>(lds + FLAG_ANY) = 1u;
+                }
+            }
             *reinterpret_cast<uint4*>(Bs + krow * 512 + ((nc ^ (nn_swz(krow) << 1)) << 4)) = v;
         }
     } else {
@@ -114,6 +147,10 @@ __device__ __forceinline__ void stage_pass(unsigned char* lds, const PassDesc& d
         for (int cc = tid >> 8; cc < nch; cc += NTHR / BN) {
             uint4 v = zero4();
             if (gcol < ncols) v = load_chunk(src + cc * 8, min(8, d.kc - cc * 8), d.b_vec);
+            if (d.isolate && drop_nonfinite(v)) {
+                lds[FLAG_OFF + row] = 1;
+                *reinterpret_cast<uint32_t*>(lds + FLAG_ANY) = 1u;
+            }
             *reinterpret_cast<uint4*>(Bs + row * 128 + ((cc ^ (row & 7)) << 4)) = v;
         }
     }
@@ -141,11 +178,14 @@ __global__ __launch_bounds__(NTHR) void fused_gemm_kernel(GemmArgs g) {
     const int xcd = blockIdx.x % 8, slot = blockIdx.x / 8;
     const int L = ((slot / 32) * 8 + xcd) * 32 + (slot % 32);
     if (L >= total) return;
-    constexpr int GM = 8;
-    const int band = L / (GM * g.tiles_n);
-    const int band_rows = min(GM, g.tiles_m - band * GM);
-    const int in_band = L - band * GM * g.tiles_n;
-    const int tm = band * GM + in_band % band_rows;
+    // The bands themselves run in the order the plan's scheduler table gives (most rank-extension work first; a last,
+    // shorter band stays last, so every band before position `ord` is a full one).
+    constexpr int GM = kGemmBandTiles;
+    const int ord = L / (GM * g.tiles_n);
+    const Entry4 band = g.pv.band_order[ord];          // (band, first row tile, row tiles, cost)
+    const int band_rows = band.c;
+    const int in_band = L - ord * GM * g.tiles_n;
+    const int tm = band.b + in_band % band_rows;
     const int tn = in_band / band_rows;
     const int m0 = tm * BM, n0 = tn * BN;
 
@@ -295,12 +335,33 @@ __global__ __launch_bounds__(NTHR) void fused_gemm_kernel(GemmArgs g) {
     // one masked pass: stage into the first row stage and weight slot, then one or two 32-wide MFMA steps
     auto run_pass = [&](const PassDesc& d) {
         wait_all_and_barrier();          // outstanding direct loads have landed; nobody reads the buffers any more
+        if (d.isolate) {                 // (uniform) clear the column flags before anybody sets one
+            if (tid <= BN / 4) reinterpret_cast<uint32_t*>(lds + FLAG_OFF)[tid] = 0u;
+            __syncthreads();
+        }
         stage_pass<NN>(lds, d, m0, n0, g.Ncols, tid);
         __syncthreads();
         const int ksteps = (d.kc + 31) / 32;
         for (int ks = 0; ks < ksteps; ++ks) {
             rfa(0, ks, 0, 0); rfa(0, ks, 1, 1); rfb(0, ks, 0);
             mma(0, 0, 0); mma(1, 1, 0);
+        }
+        if (d.isolate && *reinterpret_cast<const uint32_t*>(lds + FLAG_ANY) != 0u) {
+            // the adapter's operand held Inf / NaN in some columns: its own rows of those columns are NaN
+            const float qnan = __uint_as_float(0x7fc00000u);
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const uint32_t f4 = *reinterpret_cast<const uint32_t*>(lds + FLAG_OFF + wn * TN + b * 16 + 4 * g4);
+                if (f4 == 0u) continue;
+#pragma unroll
+                for (int a = 0; a < 8; ++a) {
+                    const int row = m0 + wm * TM + a * 16 + l16;
+                    if (row < d.a_row_lo || row >= d.a_row_hi) continue;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if ((f4 >> (8 * i)) & 0xffu) acc[a][b][i] = qnan;
+                }
+            }
         }
     };
 
@@ -312,6 +373,7 @@ __global__ __launch_bounds__(NTHR) void fused_gemm_kernel(GemmArgs g) {
         d.a_vec = true; d.scale = 1.0f;
         d.b_src = NN ? g.Bop + (int64_t)k0 * g.ldb : g.Bop + k0; d.b_ld = g.ldb; d.b_vec = true;
         d.kc = g.Kdim - k0;
+        d.isolate = false;
         run_pass(d);
     }
 
@@ -334,6 +396,7 @@ __global__ __launch_bounds__(NTHR) void fused_gemm_kernel(GemmArgs g) {
                 if (NN) { d.b_src = F + (int64_t)r0 * g.Ncols; d.b_ld = g.Ncols; d.b_vec = true; }
                 else    { d.b_src = F + r0; d.b_ld = r; d.b_vec = ((r & 7) == 0); }
                 d.kc = min(BK, r - r0);
+                d.isolate = lo > m0 || hi < min(g.M, m0 + BM);
                 run_pass(d);
             }
         }

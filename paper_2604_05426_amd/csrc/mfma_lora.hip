@@ -29,8 +29,7 @@ struct ShrinkArgs {
     const u16* src; int64_t ld;   // X (ld k) or dY (ld n)
     u16* out;                     // ragged S or dS
     int32_t Kdim;                 // k or n
-    const int32_t* list;          // row-block indices this launch covers (nullptr: all, in table order)
-    PlanView pv;
+    PlanView pv;                  // one workgroup per entry of pv.class_blocks (wide rank class first: its blocks run longest)
 };
 
 // MAXNB: rank blocks of 32 the kernel is built for (2: every rank <= 64, 4: ranks up to 128).
@@ -216,7 +215,7 @@ __device__ __forceinline__ void shrink_body(const ShrinkArgs& g, const Entry4 e,
 template <bool FWD, bool WIDE>
 __global__ __launch_bounds__(64 * SNW) void shrink_kernel(ShrinkArgs g) {
     __shared__ __attribute__((aligned(16))) u16 lds[163840 / 2];
-    const Entry4 e = g.pv.row_blocks[g.list ? g.list[blockIdx.x] : (int)blockIdx.x];
+    const Entry4 e = g.pv.class_blocks[blockIdx.x];
     if (WIDE && g.pv.rank[e.a] > 64) shrink_body<FWD, 4, 32, 2, 1>(g, e, lds);
     else shrink_body<FWD, 2, 64, 2, 1>(g, e, lds);
 }
@@ -363,7 +362,7 @@ __device__ __forceinline__ void shrink_tiled_body(const ShrinkArgs& g, const Ent
 template <bool FWD, bool WIDE, bool MIXED>
 __global__ __launch_bounds__(64 * SNW) void shrink_tiled_kernel(ShrinkArgs g) {
     __shared__ __attribute__((aligned(1024))) unsigned char lds[MIXED ? 163840 : 147456];
-    const Entry4 e = g.pv.row_blocks[g.list ? g.list[blockIdx.x] : (int)blockIdx.x];
+    const Entry4 e = g.pv.class_blocks[blockIdx.x];
     const int r = g.pv.rank[e.a];
     if (MIXED && FWD && (r & 7) == 4) {
         if (WIDE && r > 64) shrink_tiled_body<FWD, 8, FWD>(g, e, lds);
@@ -382,7 +381,6 @@ __global__ __launch_bounds__(64 * SNW) void shrink_tiled_kernel(ShrinkArgs g) {
 template <bool FWD>
 static void launch_shrink(mlora_plan* p, ShrinkArgs a, hipStream_t st) {
     const dim3 grid(p->n_row_blocks), block(64 * SNW);
-    a.list = p->n_blocks_wide == 0 ? nullptr : p->d_block_lists;      // wide blocks first when there are any
     // the tiled kernels address rows with 32-bit lane offsets: rows of at most 2^22 elements
     const bool tiled = a.Kdim >= 64 && a.Kdim % 64 == 0 && a.ld <= ((int64_t)1 << 22);
     const bool wide = p->n_blocks_wide != 0;
@@ -425,9 +423,8 @@ struct WgradArgs {
     float* partials;
     int32_t panels_k, panels_n;
     PlanView pv;
-    const int64_t* part_off;   // [N] float offset of adapter i's partial block (chunks > 1 only)
     int32_t accumulate;        // dA_i, dB_i += result (MLORA_FLAG_ACCUM_GRADS)
-    int32_t rank_class;        // 0: every item; 1: only adapters with rank <= 64; 2: only wider ones
+    int32_t chunk_base;        // first entry of the chunk table this launch covers (the table is ordered by rank class)
 };
 
 // One work item; isA: a dA_i item (panel of X against dS_i), else a dB_i item (panel of dY against S_i).  The two forms
@@ -448,7 +445,6 @@ __device__ __forceinline__ void wgrad_body(const WgradArgs& g, u16* lds, const i
     const Entry4 e = g.pv.wgrad_chunks[ce];
     const int i = e.a, chunk = e.b, row0 = e.c, rows = e.d;
     const int r = g.pv.rank[i];
-    if ((g.rank_class == 1 && r > 64) || (g.rank_class == 2 && r <= 64)) return;   // the other launch's item (uniform)
     const int rpad = (r + 31) & ~31;
     const int nblk = rpad / 32;
     const int64_t so = g.pv.soff[i];
@@ -580,7 +576,7 @@ __device__ __forceinline__ void wgrad_body(const WgradArgs& g, u16* lds, const i
     // the ragged edge go element by element.
     u16* out = (u16*)(isA ? g.pv.ptrs[i].dA : g.pv.ptrs[i].dB);
     float* part = nchunks == 1 ? nullptr
-                               : g.partials + g.part_off[i] + (int64_t)chunk * (kk + nn) * r + (isA ? 0 : kk * r);
+                               : g.partials + g.pv.part_off[i] + (int64_t)chunk * (kk + nn) * r + (isA ? 0 : kk * r);
     const bool vec = isA ? ((r & 3) == 0) : ((nn & 3) == 0);
     const bool part_vec = vec && ((reinterpret_cast<uintptr_t>(part) & 15) == 0);
 #pragma unroll
@@ -629,8 +625,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MAXNB == 4 
 void wgrad_kernel(WgradArgs g) {
     __shared__ __attribute__((aligned(16))) u16 lds[2 * (WX_TILE + WT * MAXNB * 32)];
     const int panels = g.panels_k + g.panels_n;
-    const int ce = blockIdx.x / panels;
-    const int panel = blockIdx.x - ce * panels;
+    const int ce = g.chunk_base + blockIdx.x / panels;
+    const int panel = blockIdx.x % panels;
     if (panel < g.panels_k) wgrad_body<MAXNB, true>(g, lds, ce, panel);
     else wgrad_body<MAXNB, false>(g, lds, ce, panel - g.panels_k);
 }
@@ -646,7 +642,7 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(WgradArgs g, const in
     const int64_t per = (kk + nn) * r;
     const int64_t idx = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
     if (idx >= per) return;
-    const float* part = g.partials + g.part_off[i] + idx;
+    const float* part = g.partials + g.pv.part_off[i] + idx;
     float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int c = 0; c < nchunks; ++c) {
         const float4 t = *reinterpret_cast<const float4*>(part + (int64_t)c * per);
@@ -697,7 +693,7 @@ struct ExpandArgs {
     int32_t Ncols, col_tiles;
     int32_t stream_out;      // streaming stores for the output
     int32_t stream_in;       // non-temporal loads for the old output tile
-    const int32_t* list;     // row-block indices this launch covers (nullptr: all, in table order)
+    const Entry4* blocks;    // the row blocks this launch covers (one rank class of pv.class_blocks, or all of them)
     PlanView pv;
 };
 
@@ -715,7 +711,7 @@ __global__ __launch_bounds__(256) void expand_add_kernel(ExpandArgs g) {
     const int l16 = lane & 15, g4 = lane >> 4;
     // row-block-major: consecutive workgroups cover adjacent column tiles of the same 64 rows
     const int bsel = blockIdx.x / g.col_tiles;
-    const Entry4 e = g.pv.row_blocks[g.list ? g.list[bsel] : bsel];
+    const Entry4 e = g.blocks[bsel];
     const int ct = blockIdx.x % g.col_tiles;
     const int i = e.a, row0 = e.c, rows = e.d;
     const int r = g.pv.rank[i];
@@ -882,21 +878,18 @@ static int launch_expand(mlora_plan* p, bool fwd, void* C, const void* E, hipStr
     // usually still there from whoever wrote it, and stays for whoever reads it next (134 MB output: 0.64 against 0.60).
     a.stream_in = (int64_t)p->T * a.Ncols * 2 > ((int64_t)192 << 20) ? 1 : 0;
     ProfScope prof(p, fwd ? MLORA_K_GEMM_FWD : MLORA_K_GEMM_BWD, st);
-    auto go = [&](bool narrow, int32_t nblocks, const int32_t* list) {
+    auto go = [&](bool narrow, int32_t nblocks, const Entry4* blocks) {
         if (nblocks <= 0) return;
-        a.list = list;
+        a.blocks = blocks;
         const dim3 grid((unsigned)((int64_t)nblocks * a.col_tiles));
         if (fwd && narrow)      hipLaunchKernelGGL((expand_add_kernel<true, 2>), grid, dim3(256), 0, st, a);
         else if (fwd)           hipLaunchKernelGGL((expand_add_kernel<true, 4>), grid, dim3(256), 0, st, a);
         else if (narrow)        hipLaunchKernelGGL((expand_add_kernel<false, 2>), grid, dim3(256), 0, st, a);
         else                    hipLaunchKernelGGL((expand_add_kernel<false, 4>), grid, dim3(256), 0, st, a);
     };
-    if (p->n_blocks_wide == 0) {
-        go(true, p->n_row_blocks, nullptr);
-    } else {   // each rank class through the build made for it
-        go(false, p->n_blocks_wide, p->d_block_lists);
-        go(true, p->n_blocks_narrow, p->d_block_lists + p->n_blocks_wide);
-    }
+    // each rank class through the build made for it (the class table holds the wide class first)
+    go(false, p->n_blocks_wide, p->view.class_blocks);
+    go(true, p->n_blocks_narrow, p->view.class_blocks + p->n_blocks_wide);
     MLORA_HIP_TRY(hipGetLastError());
     return MLORA_OK;
 }
@@ -933,35 +926,32 @@ int mfma_backward(mlora_plan* p, const void* dY, const void* X, const void* W, c
         w.panels_k = (int32_t)((p->k + WP - 1) / WP);
         w.panels_n = (int32_t)((p->n + WP - 1) / WP);
         w.pv = p->view;
-        w.part_off = p->d_part_off;
         w.accumulate = (flags & MLORA_FLAG_ACCUM_GRADS) ? 1 : 0;
-        if (p->n_wgrad_chunks > 0) {
-            const int64_t grid = (int64_t)p->n_wgrad_chunks * (w.panels_k + w.panels_n);
+        const DevGeo& geo = p->geo;
+        if (geo.n_chunks > 0) {
+            const int64_t panels = w.panels_k + w.panels_n;
             {
+                // One launch per rank class over that class's part of the item table (wide class first), each through
+                // the build - and so at the work groups per CU - its class allows, one after the other (overlapping them
+                // on two streams was measured and is slower: the classes then share the CUs, and neither runs at its own
+                // occupancy).
                 ProfScope prof(p, MLORA_K_WGRAD, st);
-                auto narrow = [&](int32_t max_rank, hipStream_t s) {
-                    if (max_rank <= 32) hipLaunchKernelGGL(wgrad_kernel<1>, dim3((unsigned)grid), dim3(256), 0, s, w);
-                    else                hipLaunchKernelGGL(wgrad_kernel<2>, dim3((unsigned)grid), dim3(256), 0, s, w);
-                };
-                if (p->wgrad_two_classes) {
-                    // one launch per rank class, each through the build - and so at the work groups per CU - its class
-                    // allows, one after the other (overlapping them on two streams was measured and is slower: the
-                    // classes then share the CUs, and neither runs at its own occupancy)
-                    w.rank_class = 2;
-                    hipLaunchKernelGGL(wgrad_kernel<4>, dim3((unsigned)grid), dim3(256), 0, st, w);
-                    w.rank_class = 1;
-                    narrow(p->max_rank_narrow, st);
-                    w.rank_class = 0;
-                } else if (p->max_rank <= 64) {
-                    narrow(p->max_rank, st);
-                } else {
-                    hipLaunchKernelGGL(wgrad_kernel<4>, dim3((unsigned)grid), dim3(256), 0, st, w);
+                const int32_t n_wide = geo.n_chunks_wide, n_narrow = geo.n_chunks - geo.n_chunks_wide;
+                if (n_wide > 0) {
+                    w.chunk_base = 0;
+                    hipLaunchKernelGGL(wgrad_kernel<4>, dim3((unsigned)(n_wide * panels)), dim3(256), 0, st, w);
+                }
+                if (n_narrow > 0) {
+                    w.chunk_base = n_wide;
+                    const dim3 grid((unsigned)(n_narrow * panels));
+                    if (p->max_rank_narrow <= 32) hipLaunchKernelGGL(wgrad_kernel<1>, grid, dim3(256), 0, st, w);
+                    else                          hipLaunchKernelGGL(wgrad_kernel<2>, grid, dim3(256), 0, st, w);
                 }
             }
-            if (p->max_chunks_per_adapter > 1) {
+            if (geo.n_reduce > 0) {
                 const int64_t per = (p->k + p->n) * (int64_t)p->max_rank;
                 ProfScope prof(p, MLORA_K_WGRAD_REDUCE, st);
-                hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)((per + 1023) / 1024), (unsigned)p->reduce_list.size()),
+                hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)((per + 1023) / 1024), (unsigned)geo.n_reduce),
                                    dim3(256), 0, st, w, (const int32_t*)p->d_reduce_list);
             }
         }

@@ -7,6 +7,7 @@
 // the offsets and ranks, once per segmentation, and shared by every layer of a step.
 #include <cmath>
 #include <cstring>
+#include <mutex>
 
 #include "common.h"
 
@@ -23,31 +24,113 @@ int hip_fail(hipError_t e, const char* what) {
 
 static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
-// ---- device kernels -----------------------------------------------------------------
+// ---- device kernels: the segment / tile scheduler ------------------------------------------------
 
-// Sequential prefix sums over the adapters (N <= 4096, done by one thread).  soff / rb_start may be NULL (not wanted).
-__global__ void plan_scan_kernel(int32_t N, const int32_t* off, const int32_t* rank, int64_t* soff,
-                                 int32_t* rb_start, int32_t* wc_start, int block_rows,
-                                 int chunk_rows, int chunk_rows_wide) {
-    if (threadIdx.x != 0 || blockIdx.x != 0) return;
-    int64_t s = 0;
-    int32_t rb = 0, wc = 0;
+// Scheduler set-up, one workgroup.  From the offsets and ranks alone it
+//  (1) chooses the token chunk of the weight-gradient items, per rank class.  Work items are (token chunk, 128-column
+//      panel); heterogeneous segment lengths are balanced across the CUs by keeping whole segments when that already
+//      yields two items per CU (no partial sums at all) and otherwise halving the chunk until it does or the minimum is
+//      reached.  A plan that mixes the two rank classes launches them as two kernels; the rule then holds for each
+//      launch by itself (a few long wide-rank segments would otherwise run on after everything else has ended);
+//  (2) scans the adapters: ragged S offsets, first row block / class block / chunk of each adapter and where its
+//      entries go in the class-ordered tables (wide class first), offsets of the fp32 partial sums, the list of
+//      adapters that need the fixed-order sum of partials;
+//  (3) leaves the counts in *geo for the host to size the chunk table, the workspace and the launch grids.
+// soff, rb_start, cb_start, cb_pos may be NULL (a plan over an existing segmentation only needs the chunk side).
+constexpr int kScanThreads = 256;
+
+__global__ __launch_bounds__(kScanThreads) void plan_scan_kernel(
+        int32_t N, const int32_t* off, const int32_t* rank, int64_t panels, int64_t kn, int32_t num_cus,
+        int block_rows, int block_rows_wide, int min_chunk,
+        int64_t* soff, int32_t* rb_start, int32_t* cb_start, int32_t* cb_pos,
+        int32_t* wc_start, int32_t* wc_pos, int64_t* part_off, int32_t* reduce_list, DevGeo* geo) {
+    __shared__ int64_t red[kScanThreads];
+    __shared__ int32_t chosen[2];
+    const int tid = threadIdx.x;
+    // items of one launch if the tokens of class `cls` (0: every adapter, 1: narrow ranks, 2: wide ranks) are cut every `chunk`
+    auto count_items = [&](int64_t chunk, int cls) -> int64_t {
+        int64_t mine = 0;
+        for (int32_t i = tid; i < N; i += kScanThreads) {
+            const int64_t Ti = off[i + 1] - off[i];
+            const int32_t r = rank[i];
+            if (Ti <= 0 || r <= 0) continue;
+            if ((cls == 1 && r > kNarrowMaxRank) || (cls == 2 && r <= kNarrowMaxRank)) continue;
+            mine += (Ti + chunk - 1) / chunk;
+        }
+        red[tid] = mine;
+        __syncthreads();
+        for (int s = kScanThreads / 2; s > 0; s >>= 1) {
+            if (tid < s) red[tid] += red[tid + s];
+            __syncthreads();
+        }
+        const int64_t total = red[0];
+        __syncthreads();
+        return total * panels;
+    };
+    auto choose = [&](int cls) -> int32_t {
+        int64_t chunk = (int64_t)1 << 30;
+        for (;;) {
+            const int64_t items = count_items(chunk, cls);       // uniform over the workgroup
+            if (items >= 2 * (int64_t)num_cus || chunk <= min_chunk) break;
+            chunk >>= 1;
+        }
+        return (int32_t)chunk;
+    };
+    const bool two = count_items((int64_t)1 << 30, 1) > 0 && count_items((int64_t)1 << 30, 2) > 0;
+    const int32_t cn = choose(two ? 1 : 0);
+    const int32_t cw = two ? choose(2) : cn;
+    if (tid != 0) return;
+
+    // class totals first: the wide class comes first in the class-ordered tables
+    int32_t wide_blocks = 0, wide_chunks = 0;
     for (int32_t i = 0; i < N; ++i) {
+        const int32_t Ti = off[i + 1] - off[i], r = rank[i];
+        if (Ti > 0 && r > kNarrowMaxRank) {
+            wide_blocks += (Ti + block_rows_wide - 1) / block_rows_wide;
+            wide_chunks += (Ti + cw - 1) / cw;
+        }
+    }
+    int64_t s = 0, part = 0;
+    int32_t rb = 0, cb = 0, wc = 0, max_c = 0, n_reduce = 0;
+    int32_t cb_wide = 0, cb_narrow = wide_blocks, wc_wide = 0, wc_narrow = wide_chunks;
+    for (int32_t i = 0; i < N; ++i) {
+        const int32_t Ti = off[i + 1] - off[i], r = rank[i];
+        const bool wide = r > kNarrowMaxRank;
         if (soff) soff[i] = s;
         if (rb_start) rb_start[i] = rb;
+        if (cb_start) { cb_start[i] = cb; cb_pos[i] = wide ? cb_wide : cb_narrow; }
         wc_start[i] = wc;
-        const int32_t Ti = off[i + 1] - off[i];
-        const int32_t r = rank[i];
+        wc_pos[i] = wide ? wc_wide : wc_narrow;
+        part_off[i] = part;
         s += (int64_t)Ti * r;
         if (Ti > 0 && r > 0) {
             rb += (Ti + block_rows - 1) / block_rows;
-            const int cr = r > kNarrowMaxRank ? chunk_rows_wide : chunk_rows;
-            wc += (Ti + cr - 1) / cr;
+            const int br = wide ? block_rows_wide : block_rows;
+            const int32_t nb = (Ti + br - 1) / br;
+            cb += nb;
+            (wide ? cb_wide : cb_narrow) += nb;
+            const int cr = wide ? cw : cn;
+            const int32_t c = (Ti + cr - 1) / cr;
+            wc += c;
+            (wide ? wc_wide : wc_narrow) += c;
+            if (c > max_c) max_c = c;
+            if (c > 1) {
+                part += (int64_t)c * kn * r;
+                reduce_list[n_reduce++] = i;
+            }
         }
     }
     if (soff) soff[N] = s;
     if (rb_start) rb_start[N] = rb;
+    if (cb_start) cb_start[N] = cb;
     wc_start[N] = wc;
+    DevGeo gg;
+    gg.chunk_rows = cn; gg.chunk_rows_wide = cw;
+    gg.n_chunks = wc; gg.n_chunks_wide = wide_chunks;
+    gg.max_chunks_per_adapter = max_c; gg.n_reduce = n_reduce;
+    gg.partial_floats = part;
+    gg.R1 = s; gg.n_row_blocks = rb; gg.n_blocks_wide = wide_blocks;
+    *geo = gg;
 }
 
 // index of the adapter whose [start[i], start[i+1]) holds e  (start non-decreasing)
@@ -60,40 +143,38 @@ __device__ inline int32_t find_owner(const int32_t* start, int32_t N, int32_t e)
     return lo;
 }
 
-// Fills a block table: entry e of adapter i = (i, b, off[i] + b*rows_per, min(rows_per, rest)).  With `rank` given,
-// adapters of the wide rank class take `rows_per_wide` rows per entry instead.
-__global__ void plan_fill_blocks_kernel(int32_t N, const int32_t* off, const int32_t* start,
-                                        int rows_per_narrow, Entry4* out, int32_t count,
-                                        const int32_t* rank, int rows_per_wide) {
+// Fills a block table.  Canonical entry e (adapters ascending, blocks ascending; `start` is its prefix over the
+// adapters) belongs to adapter i = owner(e) and is block b = e - start[i]: (i, b, off[i] + b*rows_per, min(rows_per,
+// rest)), written to out[pos[i] + b].  pos == start gives the canonical table, pos = the class-ordered positions the
+// table with the wide rank class first.  Adapters of the wide class take `rows_per_wide` rows per entry.
+// (Adapters without entries have start[i] == start[i+1]; the owner is the last i with start[i] <= e.)
+__global__ void plan_fill_blocks_kernel(int32_t N, const int32_t* off, const int32_t* rank, const int32_t* start,
+                                        const int32_t* pos, int rows_per_narrow, int rows_per_wide, Entry4* out,
+                                        int32_t count) {
     const int32_t e = blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= count) return;
-    // adapters without entries have start[i] == start[i+1]; the owner is the last i with start[i] <= e
-    // that also has start[i+1] > e, which the search below finds because start is non-decreasing.
-    int32_t lo = 0, hi = N;
-    while (hi - lo > 1) {
-        const int32_t mid = (lo + hi) >> 1;
-        if (start[mid] <= e) lo = mid; else hi = mid;
-    }
-    const int32_t i = lo;
+    const int32_t i = find_owner(start, N, e);
     const int32_t b = e - start[i];
-    const int rows_per = (rank && rank[i] > kNarrowMaxRank) ? rows_per_wide : rows_per_narrow;
+    const int rows_per = rank[i] > kNarrowMaxRank ? rows_per_wide : rows_per_narrow;
     const int32_t row0 = off[i] + b * rows_per;
     const int32_t rest = off[i + 1] - row0;
-    out[e] = Entry4{i, b, row0, rest < rows_per ? rest : rows_per};
+    out[pos[i] + b] = Entry4{i, b, row0, rest < rows_per ? rest : rows_per};
 }
 
-// Device-side balancing of the weight-gradient items: entries are reordered by decreasing cost
-// (tokens x (64 + rank): the stream of X / dY dominates, the MFMA work grows with the rank), ties in
-// canonical order.  Workgroups are dispatched in index order, so the long items start first and the short
-// ones fill the CUs as they drain (longest-processing-time-first).  Position = number of entries that
-// sort before this one (counting, no atomics: the result is unique).
-__global__ void plan_sort_chunks_kernel(const Entry4* in, const int32_t* rank, Entry4* out, int32_t count) {
+// Device-side balancing of the weight-gradient items: inside its rank class (entries [0, n_wide) are the wide class,
+// the rest the narrow one) every entry moves to the position given by decreasing cost (tokens x (64 + rank): the
+// stream of X / dY dominates, the MFMA work grows with the rank), ties in the order of the input table.  Workgroups
+// are dispatched in index order, so the long items start first and the short ones fill the CUs as they drain
+// (longest-processing-time-first).  Position = number of entries of the class that sort before this one (counting, no
+// atomics: the result is unique).
+__global__ void plan_sort_chunks_kernel(const Entry4* in, const int32_t* rank, Entry4* out, int32_t count, int32_t n_wide) {
     const int32_t e = blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= count) return;
     const Entry4 me = in[e];
     const int64_t key = (int64_t)me.d * (64 + rank[me.a]);
-    int32_t pos = 0;
-    for (int32_t o = 0; o < count; ++o) {
+    const int32_t lo = e < n_wide ? 0 : n_wide, hi = e < n_wide ? n_wide : count;
+    int32_t pos = lo;
+    for (int32_t o = lo; o < hi; ++o) {
         const Entry4 other = in[o];
         const int64_t ok = (int64_t)other.d * (64 + rank[other.a]);
         if (ok > key || (ok == key && o < e)) ++pos;
@@ -116,6 +197,45 @@ __global__ void plan_fill_gemm_tiles_kernel(int32_t N, const int32_t* off, int32
     out[e] = Entry4{row0, rows, lo, hi};
 }
 
+// Bands of the fused GEMM (kGemmBandTiles consecutive row tiles x all column tiles are worked on by the whole chip at a
+// time).  Cost of a band = rank-extension passes its row tiles run per column tile: for every row tile, one pass per
+// 64 ranks of every adapter that owns rows of it.  Entry: (band, first row tile, row tiles, cost).
+__global__ void plan_band_cost_kernel(int32_t N, const int32_t* off, const int32_t* rank, const Entry4* tiles,
+                                      int32_t n_tiles, int band_tiles, Entry4* out, int32_t n_bands) {
+    const int32_t b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= n_bands) return;
+    const int32_t t0 = b * band_tiles;
+    const int32_t nt = (n_tiles - t0) < band_tiles ? (n_tiles - t0) : band_tiles;
+    int32_t cost = 0;
+    for (int32_t t = t0; t < t0 + nt; ++t) {
+        const Entry4 tile = tiles[t];
+        for (int32_t i = tile.c; i < tile.d; ++i) {
+            const int32_t lo = off[i] > tile.a ? off[i] : tile.a;
+            const int32_t hi = off[i + 1] < tile.a + tile.b ? off[i + 1] : tile.a + tile.b;
+            if (lo < hi && rank[i] > 0) cost += (rank[i] + 63) / 64;
+        }
+    }
+    out[b] = Entry4{b, t0, nt, cost};
+}
+
+// Launch order of the bands: full bands by decreasing cost (the tiles with the most rank-extension work start first, the
+// cheap ones fill the tail of the launch), ties by band index; a last band with fewer row tiles stays last (the
+// kernel's tile numbering needs every band before it to be full).  Counting sort as above.
+__global__ void plan_sort_bands_kernel(const Entry4* in, Entry4* out, int32_t n_bands, int band_tiles) {
+    const int32_t e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= n_bands) return;
+    const Entry4 me = in[e];
+    const bool me_partial = me.c < band_tiles;
+    int32_t pos = 0;
+    for (int32_t o = 0; o < n_bands; ++o) {
+        const Entry4 other = in[o];
+        const bool o_partial = other.c < band_tiles;
+        if (me_partial != o_partial) { if (me_partial) ++pos; continue; }
+        if (other.d > me.d || (other.d == me.d && o < e)) ++pos;
+    }
+    out[pos] = me;
+}
+
 struct PtrBatch {
     AdapterPtrs p[32];
 };
@@ -127,7 +247,9 @@ __global__ void upload_ptrs_kernel(AdapterPtrs* dst, PtrBatch batch, int32_t bas
 
 // Refreshes the device table of per-adapter pointers.  The forward passes no gradient pointers and leaves the ones in
 // the table alone.  The table is left as it is when the same stream already uploaded exactly these pointers (the usual
-// case: the same buffers every training step); a stream under graph capture always records the upload.
+// case: the same buffers every training step); a stream under graph capture always records the upload, and from then
+// on every eager call uploads as well (a replay of the captured graph puts the captured pointers back into the table,
+// which the host mirror cannot see).
 int upload_ptrs(mlora_plan* p, const void* const* A, const void* const* B, void* const* dA,
                 void* const* dB, hipStream_t st) {
     if (p->N == 0) return MLORA_OK;
@@ -139,7 +261,8 @@ int upload_ptrs(mlora_plan* p, const void* const* A, const void* const* B, void*
     hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
     if (hipStreamIsCapturing(st, &cap) != hipSuccess) { (void)hipGetLastError(); cap = hipStreamCaptureStatusNone; }
     const bool capturing = cap != hipStreamCaptureStatusNone;
-    bool same = p->ptr_mirror_valid && p->ptr_mirror_stream == st && !capturing;
+    if (capturing) p->ptr_upload_captured = true;     // replays of that graph rewrite the table: the mirror cannot follow them
+    bool same = p->ptr_mirror_valid && p->ptr_mirror_stream == st && !capturing && !p->ptr_upload_captured;
     for (int32_t i = 0; i < p->N; ++i) {
         AdapterPtrs& m = p->ptr_mirror[i];
         const void* a = A ? A[i] : nullptr;
@@ -161,7 +284,7 @@ int upload_ptrs(mlora_plan* p, const void* const* A, const void* const* B, void*
         hipLaunchKernelGGL(upload_ptrs_kernel, dim3(1), dim3(32), 0, st, p->d_ptrs, batch, base, cnt);
     }
     MLORA_HIP_TRY(hipGetLastError());
-    p->ptr_mirror_valid = !capturing;
+    p->ptr_mirror_valid = !capturing && !p->ptr_upload_captured;
     p->ptr_mirror_stream = st;
     return MLORA_OK;
 }
@@ -228,7 +351,28 @@ extern "C" int multi_lora_validate(int dtype, int64_t T, int64_t k, int64_t n, i
     return MLORA_OK;
 }
 
-// `like`: a plan over the same segmentation (same T, N, ranks, scales, offsets) whose device tables the new plan
+// The scheduler set-up kernel runs on a stream of the library's own (one per device, default priority, created on
+// first use and kept until the process ends), and plan creation waits for that stream only: the counts it reads back
+// arrive without draining whatever the caller has queued on the plan's stream.
+static std::mutex g_sched_mutex;
+constexpr int kMaxSchedDevices = 64;
+static hipStream_t g_sched_stream[kMaxSchedDevices] = {};
+
+static int scheduler_stream(hipStream_t* out) {
+    int dev = 0;
+    MLORA_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxSchedDevices) {
+        set_error("device index beyond the scheduler stream table");
+        return MLORA_ERR_SHAPE;
+    }
+    if (!g_sched_stream[dev]) MLORA_HIP_TRY(hipStreamCreateWithFlags(&g_sched_stream[dev], hipStreamNonBlocking));
+    *out = g_sched_stream[dev];
+    return MLORA_OK;
+}
+
+static inline size_t up256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+// `like`: a plan over the same segmentation (same T, N, ranks, scales, offsets) whose segmentation tables the new plan
 // uses instead of building its own; only what depends on the layer shape or on the caller's buffers is new.
 static int plan_create_impl(mlora_plan** out, int dtype, int64_t T, int64_t k, int64_t n,
                             int32_t N, const int32_t* ranks, const float* scales,
@@ -241,7 +385,8 @@ static int plan_create_impl(mlora_plan** out, int dtype, int64_t T, int64_t k, i
     const int rc = multi_lora_validate(dtype, T, k, n, N, ranks, scales, seg_offsets);
     if (rc != MLORA_OK) return rc;
 
-    mlora_plan* p = new mlora_plan();
+    std::unique_ptr<mlora_plan> holder(new mlora_plan());
+    mlora_plan* p = holder.get();
     p->dtype = dtype;
     p->T = T; p->k = k; p->n = n; p->N = N;
     if (N > 0) {
@@ -251,230 +396,173 @@ static int plan_create_impl(mlora_plan** out, int dtype, int64_t T, int64_t k, i
     } else {
         p->off.assign(1, 0);
     }
-    p->soff.resize(N + 1);
-    p->wchunk_start.resize(N + 1);
     p->build_stream = (hipStream_t)stream;
     // bf16 with 16-byte row granularity goes to the MFMA kernels, everything else to the FMA kernels
     p->use_mfma = (dtype == MLORA_BF16) && (k % 8 == 0) && (n % 8 == 0);
 
     int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e == hipSuccess) {
+    MLORA_HIP_TRY(hipGetDevice(&dev));
+    {
         int cus = 0;
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
             p->num_cus = cus;
     }
-    // Weight-gradient work items are (token chunk, 128-column panel).  Balance heterogeneous segment
-    // lengths across the CUs: keep whole segments when that already yields two items per CU (no
-    // partial sums at all), otherwise halve the chunk until it does or the minimum is reached.
-    // A plan that mixes the two rank classes launches them as two kernels that overlap; the rule then holds for
-    // each launch by itself (a few long wide-rank segments would otherwise run on after everything else has ended).
-    {
-        bool wide = false, narrow = false;
-        for (int32_t i = 0; i < N; ++i) {
-            if (seg_offsets[i + 1] == seg_offsets[i] || ranks[i] == 0) continue;
-            (ranks[i] > kNarrowMaxRank ? wide : narrow) = true;
-        }
-        const bool two = wide && narrow;
-        const int64_t panels = ceil_div(k, kWgradPanelCols) + ceil_div(n, kWgradPanelCols);
-        auto choose = [&](int cls) {      // 0: every adapter, 1: narrow ranks only, 2: wide ranks only
-            int64_t chunk = (int64_t)1 << 30;
-            for (;;) {
-                int64_t items = 0;
-                for (int32_t i = 0; i < N; ++i) {
-                    const int64_t Ti = seg_offsets[i + 1] - seg_offsets[i];
-                    if (Ti <= 0 || ranks[i] <= 0) continue;
-                    if ((cls == 1 && ranks[i] > kNarrowMaxRank) || (cls == 2 && ranks[i] <= kNarrowMaxRank)) continue;
-                    items += ceil_div(Ti, chunk) * panels;
-                }
-                if (items >= 2 * (int64_t)p->num_cus || chunk <= kWgradMinChunkRows) break;
-                chunk /= 2;
-            }
-            return (int32_t)chunk;
-        };
-        p->wgrad_chunk_rows = choose(two ? 1 : 0);
-        p->wgrad_chunk_rows_wide = two ? choose(2) : p->wgrad_chunk_rows;
-    }
-    p->shares_tables = like != nullptr;
-    // the weight-gradient item table depends on the layer shape only through the token chunk
-    p->shares_wgrad_table = like != nullptr && like->wgrad_chunk_rows == p->wgrad_chunk_rows &&
-                            like->wgrad_chunk_rows_wide == p->wgrad_chunk_rows_wide;
 
-    // host-side sizes (the device rebuilds the same numbers; multi_lora_plan_dump exposes them)
-    int64_t s = 0;
-    int64_t rb = 0, wc = 0;
+    // Host side: sizes that follow from the adapters alone (one pass over the adapters, none over blocks or chunks).
+    // The tables themselves, the token chunks and everything that depends on them come from the device.
+    int64_t R1 = 0, rb = 0, rb_wide = 0;
     for (int32_t i = 0; i < N; ++i) {
-        p->soff[i] = s;
-        p->wchunk_start[i] = (int32_t)wc;
         const int64_t Ti = p->off[i + 1] - p->off[i];
-        s += Ti * ranks[i];
-        if (Ti > 0 && ranks[i] > 0) {
-            rb += ceil_div(Ti, kBlockRows);
-            const int64_t c = ceil_div(Ti, ranks[i] > kNarrowMaxRank ? p->wgrad_chunk_rows_wide : p->wgrad_chunk_rows);
-            wc += c;
-            if (c > p->max_chunks_per_adapter) p->max_chunks_per_adapter = (int32_t)c;
-        }
+        R1 += Ti * ranks[i];
         if (ranks[i] > p->max_rank) p->max_rank = ranks[i];
+        if (ranks[i] > 0 && Ti == 0) p->has_empty_ranked = true;
+        if (Ti <= 0 || ranks[i] <= 0) continue;
+        rb += ceil_div(Ti, kBlockRows);
+        if (ranks[i] % 8) p->ranks_mult8 = false;
+        if (ranks[i] > kNarrowMaxRank) rb_wide += ceil_div(Ti, kBlockRowsWide);
+        else if (ranks[i] > p->max_rank_narrow) p->max_rank_narrow = ranks[i];
     }
-    {
-        bool wide = false;
-        for (int32_t i = 0; i < N; ++i) {
-            if (p->off[i + 1] == p->off[i] || ranks[i] == 0) continue;
-            if (ranks[i] % 8) p->ranks_mult8 = false;
-            if (ranks[i] > 64) wide = true;
-            else if (ranks[i] > p->max_rank_narrow) p->max_rank_narrow = ranks[i];
-        }
-        p->wgrad_two_classes = wide && p->max_rank_narrow > 0;
-    }
-    {   // same enumeration as the device-built row-block table: adapters ascending, blocks ascending
-        std::vector<int32_t> narrow;
-        int32_t idx = 0;
-        for (int32_t i = 0; i < N; ++i) {
-            const int64_t Ti = p->off[i + 1] - p->off[i];
-            if (Ti <= 0 || ranks[i] <= 0) continue;
-            const int32_t nb = (int32_t)ceil_div(Ti, kBlockRows);
-            for (int32_t b = 0; b < nb; ++b, ++idx) (ranks[i] <= 64 ? narrow : p->block_lists).push_back(idx);
-        }
-        p->n_blocks_wide = (int32_t)p->block_lists.size();
-        p->n_blocks_narrow = (int32_t)narrow.size();
-        p->block_lists.insert(p->block_lists.end(), narrow.begin(), narrow.end());
-    }
-    p->soff[N] = s;
-    p->wchunk_start[N] = (int32_t)wc;
-    p->R1 = s;
+    static_assert(kBlockRows == kBlockRowsWide, "the class table holds the same blocks as the canonical one");
+    p->R1 = R1;
     p->n_row_blocks = (int32_t)rb;
-    p->n_wgrad_chunks = (int32_t)wc;
+    p->n_blocks_wide = (int32_t)rb_wide;
+    p->n_blocks_narrow = (int32_t)(rb - rb_wide);
     p->n_gemm_tiles = (int32_t)ceil_div(T, kGemmTileRows);
+    p->n_bands = (int32_t)ceil_div(p->n_gemm_tiles, kGemmBandTiles);
+    p->shares_tables = like != nullptr;
 
-    const size_t esz = dtype == MLORA_BF16 ? 2 : 4;
-    auto up256 = [](size_t v) { return (v + 255) & ~(size_t)255; };
-    p->ws_ds_bytes = up256((size_t)p->R1 * esz);
-    // fp32 partials of dA_i, dB_i for adapters whose tokens are split over several chunks
-    size_t part = 0;   // in floats
-    std::vector<int64_t>& part_off = p->part_off;
-    part_off.assign(N + 1, 0);
-    for (int32_t i = 0; i < N; ++i) {
-        const int64_t c = p->wchunk_start[i + 1] - p->wchunk_start[i];
-        part_off[i] = (int64_t)part;
-        if (c > 1) {
-            part += (size_t)c * (size_t)(k + n) * (size_t)ranks[i];
-            p->reduce_list.push_back(i);
-        }
-        if (ranks[i] > 0 && p->off[i + 1] == p->off[i]) p->has_empty_ranked = true;
-    }
-    p->ws_partial_bytes = up256(part * sizeof(float));
-
-    // carve one device allocation
+    // first device allocation: everything whose size the adapters alone fix
+    const bool own_seg = !p->shares_tables;
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t r = o; o += up256(bytes); return r; };
-    const bool own_seg = !p->shares_tables, own_wc = !p->shares_wgrad_table;
-    const size_t o_off = take(own_seg ? sizeof(int32_t) * (N + 1) : 0);
-    const size_t o_rank = take(own_seg ? sizeof(int32_t) * (N + 1) : 0);
-    const size_t o_scale = take(own_seg ? sizeof(float) * (N + 1) : 0);
-    const size_t o_soff = take(own_seg ? sizeof(int64_t) * (N + 1) : 0);
-    const size_t o_rbs = take(own_seg ? sizeof(int32_t) * (N + 1) : 0);
-    const size_t o_wcs = take(own_wc ? sizeof(int32_t) * (N + 1) : 0);
-    const size_t o_ptrs = take(sizeof(AdapterPtrs) * (N + 1));
+    const size_t nI = sizeof(int32_t) * (size_t)(N + 1), nL = sizeof(int64_t) * (size_t)(N + 1);
+    const size_t o_off = take(own_seg ? nI : 0), o_rank = take(own_seg ? nI : 0), o_scale = take(own_seg ? nI : 0);
+    const size_t o_soff = take(own_seg ? nL : 0), o_rbs = take(own_seg ? nI : 0), o_cbs = take(own_seg ? nI : 0);
+    const size_t o_cbp = take(own_seg ? nI : 0);
+    const size_t o_wcs = take(nI), o_wcp = take(nI), o_part = take(nL), o_red = take(nI), o_geo = take(sizeof(DevGeo));
+    const size_t o_ptrs = take(sizeof(AdapterPtrs) * (size_t)(N + 1));
     const size_t o_rb = take(own_seg ? sizeof(Entry4) * (size_t)(p->n_row_blocks + 1) : 0);
+    const size_t o_cb = take(own_seg ? sizeof(Entry4) * (size_t)(p->n_row_blocks + 1) : 0);
     const size_t o_gt = take(own_seg ? sizeof(Entry4) * (size_t)(p->n_gemm_tiles + 1) : 0);
-    const size_t o_wc = take(own_wc ? sizeof(Entry4) * (size_t)(p->n_wgrad_chunks + 1) : 0);
-    const size_t o_wc_tmp = take(own_wc ? sizeof(Entry4) * (size_t)(p->n_wgrad_chunks + 1) : 0);
+    const size_t o_bo = take(own_seg ? sizeof(Entry4) * (size_t)(p->n_bands + 1) : 0);
+    const size_t o_bo_tmp = take(own_seg ? sizeof(Entry4) * (size_t)(p->n_bands + 1) : 0);
     const size_t o_probs = take(128 * (size_t)(5 * N + 8));
-    const size_t o_part = take(sizeof(int64_t) * (N + 1) + sizeof(int32_t) * (N + 1));   // partial offsets, then the reduce list
     const size_t o_adamw = take(96 * (size_t)(N + 1));
-    const size_t o_lists = take(own_seg ? sizeof(int32_t) * (size_t)(p->n_row_blocks + 1) : 0);
-    p->d_block_bytes = o;
-
-    p->d_block = std::make_shared<DeviceBlock>();
-    if (e == hipSuccess) e = hipMalloc(&p->d_block->ptr, p->d_block_bytes);
-    if (e != hipSuccess) {
-        delete p;
-        return hip_fail(e, "hipMalloc(plan tables)");
+    auto block1 = std::make_shared<DeviceBlock>();
+    MLORA_HIP_TRY(hipMalloc(&block1->ptr, o));
+    p->blocks.push_back(block1);
+    if (like) {      // every block the shared tables live in, whoever allocated it
+        p->shared_blocks = like->shared_blocks;
+        p->shared_blocks.insert(p->shared_blocks.end(), like->blocks.begin(), like->blocks.end());
     }
-    if (like) p->d_shared_block = like->d_block;      // keeps the shared tables alive
-    char* base = (char*)p->d_block->ptr;
+    char* base = (char*)block1->ptr;
     const PlanView* lv = like ? &like->view : nullptr;
     int32_t* d_off = own_seg ? (int32_t*)(base + o_off) : const_cast<int32_t*>(lv->off);
     int32_t* d_rank = own_seg ? (int32_t*)(base + o_rank) : const_cast<int32_t*>(lv->rank);
     float* d_scale = own_seg ? (float*)(base + o_scale) : const_cast<float*>(lv->scale);
     int64_t* d_soff = own_seg ? (int64_t*)(base + o_soff) : const_cast<int64_t*>(lv->soff);
     int32_t* d_rbs = own_seg ? (int32_t*)(base + o_rbs) : nullptr;
-    int32_t* d_wcs = own_wc ? (int32_t*)(base + o_wcs) : const_cast<int32_t*>(lv->wgrad_chunk_start);
+    int32_t* d_cbs = own_seg ? (int32_t*)(base + o_cbs) : nullptr;
+    int32_t* d_cbp = own_seg ? (int32_t*)(base + o_cbp) : nullptr;
+    int32_t* d_wcs = (int32_t*)(base + o_wcs);
+    int32_t* d_wcp = (int32_t*)(base + o_wcp);
+    int64_t* d_part = (int64_t*)(base + o_part);
+    p->d_reduce_list = (int32_t*)(base + o_red);
+    DevGeo* d_geo = (DevGeo*)(base + o_geo);
     p->d_ptrs = (AdapterPtrs*)(base + o_ptrs);
     Entry4* d_rb = own_seg ? (Entry4*)(base + o_rb) : const_cast<Entry4*>(lv->row_blocks);
+    Entry4* d_cb = own_seg ? (Entry4*)(base + o_cb) : const_cast<Entry4*>(lv->class_blocks);
     Entry4* d_gt = own_seg ? (Entry4*)(base + o_gt) : const_cast<Entry4*>(lv->gemm_tiles);
-    Entry4* d_wc = own_wc ? (Entry4*)(base + o_wc) : const_cast<Entry4*>(lv->wgrad_chunks);
+    Entry4* d_bo = own_seg ? (Entry4*)(base + o_bo) : const_cast<Entry4*>(lv->band_order);
     p->d_probs = base + o_probs;
-    p->d_part_off = (int64_t*)(base + o_part);
-    p->d_reduce_list = (int32_t*)(base + o_part + sizeof(int64_t) * (N + 1));
     p->d_adamw = base + o_adamw;
-    p->d_block_lists = own_seg ? (int32_t*)(base + o_lists) : like->d_block_lists;
 
-    hipStream_t st = p->build_stream;
-    std::vector<int32_t>& off32 = p->off32;
-    off32.resize(N + 1);
-    for (int32_t i = 0; i <= N; ++i) off32[i] = (int32_t)p->off[i];
-    auto fail = [&](hipError_t err, const char* what) {
-        delete p;
-        return hip_fail(err, what);
-    };
-    if (own_seg && (e = hipMemcpyAsync(d_off, off32.data(), sizeof(int32_t) * (N + 1), hipMemcpyHostToDevice, st)) != hipSuccess)
-        return fail(e, "hipMemcpyAsync(offsets)");
-    if (own_seg && N > 0) {
-        if ((e = hipMemcpyAsync(d_rank, p->ranks.data(), sizeof(int32_t) * N, hipMemcpyHostToDevice, st)) != hipSuccess)
-            return fail(e, "hipMemcpyAsync(ranks)");
-        if ((e = hipMemcpyAsync(d_scale, p->scales.data(), sizeof(float) * N, hipMemcpyHostToDevice, st)) != hipSuccess)
-            return fail(e, "hipMemcpyAsync(scales)");
-    }
-    if ((e = hipMemcpyAsync(p->d_part_off, part_off.data(), sizeof(int64_t) * (N + 1), hipMemcpyHostToDevice, st)) != hipSuccess)
-        return fail(e, "hipMemcpyAsync(partial offsets)");
-    if (!p->reduce_list.empty() &&
-        (e = hipMemcpyAsync(p->d_reduce_list, p->reduce_list.data(), sizeof(int32_t) * p->reduce_list.size(),
-                            hipMemcpyHostToDevice, st)) != hipSuccess)
-        return fail(e, "hipMemcpyAsync(reduce list)");
-    if (own_seg && !p->block_lists.empty() &&
-        (e = hipMemcpyAsync(p->d_block_lists, p->block_lists.data(), sizeof(int32_t) * p->block_lists.size(),
-                            hipMemcpyHostToDevice, st)) != hipSuccess)
-        return fail(e, "hipMemcpyAsync(row-block classes)");
-    // (a plan that shares the segmentation tables but chunks the tokens differently scans again for its chunk starts)
-    if (own_seg)
-        hipLaunchKernelGGL(plan_scan_kernel, dim3(1), dim3(64), 0, st, N, d_off, d_rank, d_soff, d_rbs, d_wcs,
-                           kBlockRows, p->wgrad_chunk_rows, p->wgrad_chunk_rows_wide);
-    else if (own_wc)
-        hipLaunchKernelGGL(plan_scan_kernel, dim3(1), dim3(64), 0, st, N, d_off, d_rank, (int64_t*)nullptr,
-                           (int32_t*)nullptr, d_wcs, kBlockRows, p->wgrad_chunk_rows, p->wgrad_chunk_rows_wide);
-    if (own_seg && p->n_row_blocks > 0)
-        hipLaunchKernelGGL(plan_fill_blocks_kernel, dim3((p->n_row_blocks + 255) / 256), dim3(256), 0, st, N,
-                           d_off, d_rbs, kBlockRows, d_rb, p->n_row_blocks, (const int32_t*)nullptr, 0);
-    if (own_wc && p->n_wgrad_chunks > 0) {
-        Entry4* d_wc_tmp = (Entry4*)(base + o_wc_tmp);
-        const unsigned blocks = (unsigned)((p->n_wgrad_chunks + 255) / 256);
-        if (p->n_wgrad_chunks <= kMaxSortedChunks) {   // canonical table, then reordered by cost
-            hipLaunchKernelGGL(plan_fill_blocks_kernel, dim3(blocks), dim3(256), 0, st, N, d_off, d_wcs,
-                               p->wgrad_chunk_rows, d_wc_tmp, p->n_wgrad_chunks, (const int32_t*)d_rank,
-                               p->wgrad_chunk_rows_wide);
-            hipLaunchKernelGGL(plan_sort_chunks_kernel, dim3(blocks), dim3(256), 0, st, d_wc_tmp, d_rank, d_wc,
-                               p->n_wgrad_chunks);
-        } else {
-            hipLaunchKernelGGL(plan_fill_blocks_kernel, dim3(blocks), dim3(256), 0, st, N, d_off, d_wcs,
-                               p->wgrad_chunk_rows, d_wc, p->n_wgrad_chunks, (const int32_t*)d_rank,
-                               p->wgrad_chunk_rows_wide);
+    // scheduler set-up on the library's own stream; the host waits for that stream alone
+    {
+        std::lock_guard<std::mutex> lock(g_sched_mutex);
+        hipStream_t ss = nullptr;
+        const int src = scheduler_stream(&ss);
+        if (src != MLORA_OK) return src;
+        if (own_seg) {
+            p->off32.resize(N + 1);
+            for (int32_t i = 0; i <= N; ++i) p->off32[i] = (int32_t)p->off[i];
+            MLORA_HIP_TRY(hipMemcpyAsync(d_off, p->off32.data(), nI, hipMemcpyHostToDevice, ss));
+            if (N > 0) {
+                MLORA_HIP_TRY(hipMemcpyAsync(d_rank, p->ranks.data(), sizeof(int32_t) * N, hipMemcpyHostToDevice, ss));
+                MLORA_HIP_TRY(hipMemcpyAsync(d_scale, p->scales.data(), sizeof(float) * N, hipMemcpyHostToDevice, ss));
+            }
         }
+        const int64_t panels = ceil_div(k, kWgradPanelCols) + ceil_div(n, kWgradPanelCols);
+        hipLaunchKernelGGL(plan_scan_kernel, dim3(1), dim3(kScanThreads), 0, ss, N, d_off, d_rank, panels, k + n,
+                           (int32_t)p->num_cus, kBlockRows, kBlockRowsWide, kWgradMinChunkRows, own_seg ? d_soff : nullptr,
+                           d_rbs, d_cbs, d_cbp, d_wcs, d_wcp, d_part, p->d_reduce_list, d_geo);
+        MLORA_HIP_TRY(hipGetLastError());
+        MLORA_HIP_TRY(hipMemcpyAsync(&p->geo, d_geo, sizeof(DevGeo), hipMemcpyDeviceToHost, ss));
+        MLORA_HIP_TRY(hipStreamSynchronize(ss));
     }
-    if (own_seg && p->n_gemm_tiles > 0)
-        hipLaunchKernelGGL(plan_fill_gemm_tiles_kernel, dim3((p->n_gemm_tiles + 255) / 256), dim3(256), 0, st, N,
-                           d_off, (int32_t)T, kGemmTileRows, d_gt, p->n_gemm_tiles);
-    if ((e = hipGetLastError()) != hipSuccess) return fail(e, "plan build kernels");
+    const DevGeo& geo = p->geo;
+    if (geo.R1 != p->R1 || geo.n_row_blocks != p->n_row_blocks || geo.n_blocks_wide != p->n_blocks_wide) {
+        set_error("device-side scheduler disagrees with the host about the segmentation");
+        return MLORA_ERR_HIP;
+    }
+    const size_t esz = dtype == MLORA_BF16 ? 2 : 4;
+    p->ws_ds_bytes = up256((size_t)p->R1 * esz);
+    p->ws_partial_bytes = up256((size_t)geo.partial_floats * sizeof(float));
+
+    // second allocation: the chunk table, sized by what the device chose
+    Entry4 *d_wc = nullptr, *d_wc_tmp = nullptr;
+    {
+        const size_t tab = up256(sizeof(Entry4) * (size_t)(geo.n_chunks + 1));
+        auto block2 = std::make_shared<DeviceBlock>();
+        MLORA_HIP_TRY(hipMalloc(&block2->ptr, 2 * tab));
+        p->blocks.push_back(block2);
+        d_wc = (Entry4*)block2->ptr;
+        d_wc_tmp = (Entry4*)((char*)block2->ptr + tab);
+    }
+
+    // table builds on the plan's stream (their inputs were complete when the wait above returned)
+    hipStream_t st = p->build_stream;
+    auto grid_for = [](int32_t cnt) { return dim3((unsigned)((cnt + 255) / 256)); };
+    if (own_seg && p->n_row_blocks > 0) {
+        hipLaunchKernelGGL(plan_fill_blocks_kernel, grid_for(p->n_row_blocks), dim3(256), 0, st, N, d_off, d_rank, d_rbs, d_rbs,
+                           kBlockRows, kBlockRows, d_rb, p->n_row_blocks);
+        hipLaunchKernelGGL(plan_fill_blocks_kernel, grid_for(p->n_row_blocks), dim3(256), 0, st, N, d_off, d_rank, d_cbs, d_cbp,
+                           kBlockRows, kBlockRowsWide, d_cb, p->n_row_blocks);
+    }
+    if (geo.n_chunks > 0) {
+        // class-ordered canonical table, then reordered by cost inside each class (very large tables keep the first)
+        const bool sorted = geo.n_chunks <= kMaxSortedChunks;
+        hipLaunchKernelGGL(plan_fill_blocks_kernel, grid_for(geo.n_chunks), dim3(256), 0, st, N, d_off, d_rank, d_wcs, d_wcp,
+                           geo.chunk_rows, geo.chunk_rows_wide, sorted ? d_wc_tmp : d_wc, geo.n_chunks);
+        if (sorted)
+            hipLaunchKernelGGL(plan_sort_chunks_kernel, grid_for(geo.n_chunks), dim3(256), 0, st, d_wc_tmp, d_rank, d_wc,
+                               geo.n_chunks, geo.n_chunks_wide);
+    }
+    if (own_seg && p->n_gemm_tiles > 0) {
+        hipLaunchKernelGGL(plan_fill_gemm_tiles_kernel, grid_for(p->n_gemm_tiles), dim3(256), 0, st, N, d_off, (int32_t)T,
+                           kGemmTileRows, d_gt, p->n_gemm_tiles);
+        Entry4* d_bo_tmp = (Entry4*)(base + o_bo_tmp);
+        const bool sorted = p->n_bands <= kMaxSortedChunks;
+        hipLaunchKernelGGL(plan_band_cost_kernel, grid_for(p->n_bands), dim3(256), 0, st, N, d_off, d_rank, d_gt,
+                           p->n_gemm_tiles, kGemmBandTiles, sorted ? d_bo_tmp : d_bo, p->n_bands);
+        if (sorted)
+            hipLaunchKernelGGL(plan_sort_bands_kernel, grid_for(p->n_bands), dim3(256), 0, st, d_bo_tmp, d_bo, p->n_bands,
+                               kGemmBandTiles);
+    }
+    MLORA_HIP_TRY(hipGetLastError());
     prepare_static_workspace();
 
     PlanView& v = p->view;
     v.N = N; v.T = T; v.k = k; v.n = n;
     v.off = d_off; v.rank = d_rank; v.scale = d_scale; v.soff = d_soff; v.ptrs = p->d_ptrs;
     v.row_blocks = d_rb; v.n_row_blocks = p->n_row_blocks;
+    v.class_blocks = d_cb; v.n_class_blocks = p->n_row_blocks;
     v.gemm_tiles = d_gt; v.n_gemm_tiles = p->n_gemm_tiles;
-    v.wgrad_chunks = d_wc; v.n_wgrad_chunks = p->n_wgrad_chunks;
+    v.band_order = d_bo; v.n_bands = p->n_bands;
+    v.wgrad_chunks = d_wc; v.n_wgrad_chunks = geo.n_chunks;
     v.wgrad_chunk_start = d_wcs;
-    *out = p;
+    v.part_off = d_part;
+    *out = holder.release();
     return MLORA_OK;
 }
 
@@ -592,8 +680,13 @@ extern "C" int multi_lora_plan_geometry(const mlora_plan* plan, int32_t* out) {
     out[MLORA_GEO_BLOCK_ROWS] = kBlockRows;
     out[MLORA_GEO_GEMM_TILE_ROWS] = kGemmTileRows;
     out[MLORA_GEO_GEMM_TILE_COLS] = kGemmTileCols;
-    out[MLORA_GEO_WGRAD_CHUNK_ROWS] = plan->wgrad_chunk_rows;
-    out[MLORA_GEO_WGRAD_CHUNK_ROWS_WIDE] = plan->wgrad_chunk_rows_wide;
+    out[MLORA_GEO_WGRAD_CHUNK_ROWS] = plan->geo.chunk_rows;
+    out[MLORA_GEO_WGRAD_CHUNK_ROWS_WIDE] = plan->geo.chunk_rows_wide;
+    out[MLORA_GEO_BLOCK_ROWS_WIDE] = kBlockRowsWide;
+    out[MLORA_GEO_GEMM_BAND_TILES] = kGemmBandTiles;
+    out[MLORA_GEO_NUM_CUS] = plan->num_cus;
+    out[MLORA_GEO_WGRAD_PANEL_COLS] = kWgradPanelCols;
+    out[MLORA_GEO_WGRAD_MIN_CHUNK_ROWS] = kWgradMinChunkRows;
     out[MLORA_GEO_R1_LO] = (int32_t)(plan->R1 & 0x7fffffff);
     out[MLORA_GEO_R1_HI] = (int32_t)(plan->R1 >> 31);
     out[MLORA_GEO_USES_MFMA] = plan->use_mfma ? 1 : 0;
@@ -611,7 +704,9 @@ extern "C" int multi_lora_plan_dump(const mlora_plan* plan, int which, int32_t* 
     switch (which) {
         case MLORA_TABLE_ROW_BLOCKS: src = plan->view.row_blocks; cnt = plan->n_row_blocks; break;
         case MLORA_TABLE_GEMM_ROW_TILES: src = plan->view.gemm_tiles; cnt = plan->n_gemm_tiles; break;
-        case MLORA_TABLE_WGRAD_CHUNKS: src = plan->view.wgrad_chunks; cnt = plan->n_wgrad_chunks; break;
+        case MLORA_TABLE_WGRAD_CHUNKS: src = plan->view.wgrad_chunks; cnt = plan->geo.n_chunks; break;
+        case MLORA_TABLE_CLASS_BLOCKS: src = plan->view.class_blocks; cnt = plan->n_row_blocks; break;
+        case MLORA_TABLE_GEMM_BAND_ORDER: src = plan->view.band_order; cnt = plan->n_bands; break;
         default:
             set_error("unknown table id");
             return MLORA_ERR_FLAGS;

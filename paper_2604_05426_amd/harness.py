@@ -25,11 +25,19 @@ def to_host(t: torch.Tensor) -> np.ndarray:
     return t.detach().to(torch.float32).cpu().numpy().astype(np.float64)
 
 
+GUARD_ELEMS = 4096          # guard region either side of every output (elements of the output's dtype)
+GUARD_VALUE = -7.0          # exact in bf16 and fp32; 0xA5 for the byte-typed workspace
+
+
 class DeviceLayer:
-    """One multi-LoRA layer resident on the GPU: inputs, outputs, plan and workspace."""
+    """One multi-LoRA layer resident on the GPU: inputs, outputs, plan and workspace.
+
+    With ``guards`` (the default) every output the library writes -- Y, dX, S, dA_i, dB_i and the workspace -- sits
+    inside a larger allocation between two guard regions filled with a known value; ``check_guards`` (called by
+    ``sync``) asserts that no kernel wrote outside the tensor it was given."""
 
     def __init__(self, w: Workload, device: str = "cuda:0", canary: Optional[float] = None,
-                 like: Optional["ml.Plan"] = None):
+                 like: Optional["ml.Plan"] = None, guards: bool = True):
         if not torch.cuda.is_available():
             raise RuntimeError("DeviceLayer needs a GPU; there is no CPU fallback")
         self.w = w
@@ -41,21 +49,43 @@ class DeviceLayer:
         self.A = [to_device(a, dt, dev) for a in w.A]
         self.B = [to_device(b, dt, dev) for b in w.B]
         fill = float("nan") if canary is None else canary
+        self._guarded = []
 
-        def out(*shape):
-            return torch.full(shape, fill, dtype=self.tdtype, device=dev)
+        def out(name, *shape):
+            if not guards:
+                return torch.full(shape, fill, dtype=self.tdtype, device=dev)
+            numel = int(np.prod(shape))
+            buf = torch.full((numel + 2 * GUARD_ELEMS,), GUARD_VALUE, dtype=self.tdtype, device=dev)
+            view = buf[GUARD_ELEMS:GUARD_ELEMS + numel].view(*shape)
+            view.fill_(fill)
+            self._guarded.append((name, buf, numel, GUARD_VALUE))
+            return view
 
-        self.Y, self.dX = out(w.T, w.n), out(w.T, w.k)
-        self.S = out(max(w.R1, 1))
-        self.dA = [out(w.k, r) for r in w.ranks]
-        self.dB = [out(r, w.n) for r in w.ranks]
+        self.Y, self.dX = out("Y", w.T, w.n), out("dX", w.T, w.k)
+        self.S = out("S", max(w.R1, 1))
+        self.dA = [out(f"dA{i}", w.k, r) for i, r in enumerate(w.ranks)]
+        self.dB = [out(f"dB{i}", r, w.n) for i, r in enumerate(w.ranks)]
         self.stream = torch.cuda.current_stream(dev).cuda_stream
         if like is None:
             self.plan = ml.Plan(self.mdtype, w.T, w.k, w.n, w.ranks, w.scales, w.offsets, stream=self.stream)
         else:      # another layer shape over the segmentation tables of an existing plan
             self.plan = ml.Plan.like(like, w.k, w.n, stream=self.stream)
         self.ws_bytes = self.plan.workspace_bytes()
-        self.workspace = torch.zeros(max(self.ws_bytes, 256), dtype=torch.uint8, device=dev)
+        ws_len = max(self.ws_bytes, 256)
+        if guards:
+            buf = torch.full((ws_len + 2 * GUARD_ELEMS,), 0xA5, dtype=torch.uint8, device=dev)
+            self.workspace = buf[GUARD_ELEMS:GUARD_ELEMS + ws_len]
+            self.workspace.zero_()
+            self._guarded.append(("workspace", buf, ws_len, 0xA5))
+        else:
+            self.workspace = torch.zeros(ws_len, dtype=torch.uint8, device=dev)
+
+    def check_guards(self) -> None:
+        """No kernel may have written outside the outputs it was handed."""
+        for name, buf, numel, value in self._guarded:
+            head, tail = buf[:GUARD_ELEMS], buf[GUARD_ELEMS + numel:]
+            if not (bool(torch.all(head == value)) and bool(torch.all(tail == value))):
+                raise AssertionError(f"guard region around {name} was overwritten")
 
     @classmethod
     def synthetic(cls, name: str, dtype: str, k: int, n: int, ranks, seg_lens, scales, seed: int,
@@ -65,6 +95,7 @@ class DeviceLayer:
         if not torch.cuda.is_available():
             raise RuntimeError("DeviceLayer needs a GPU; there is no CPU fallback")
         self = cls.__new__(cls)
+        self._guarded = []
         off = [0]
         for t in seg_lens:
             off.append(off[-1] + int(t))
@@ -106,6 +137,7 @@ class DeviceLayer:
 
     def sync(self) -> None:
         torch.cuda.synchronize(self.device)
+        self.check_guards()
 
     # ---- results as float64 numpy ------------------------------------------------------
     def S_list(self) -> List[np.ndarray]:

@@ -10,7 +10,7 @@ from oracle import tile_tables as tt
 from paper_2604_05426_amd import binding as ml
 from paper_2604_05426_amd import workloads as wl
 from paper_2604_05426_amd.harness import DeviceLayer, to_device, to_host
-from util import rel_fro, sample_cols, sample_rows
+from util import elem_excess, rel_fro, row_rel_max, sample_cols, sample_rows
 
 pytestmark = pytest.mark.gpu
 
@@ -27,16 +27,23 @@ def check_full(w, tol=None, label=""):
     dl.sync()
     fw = orc.forward(w.X, w.W, w.A, w.B, w.scales, w.offsets)
     bw = orc.backward(w.dY, w.X, w.W, w.A, w.B, w.scales, w.offsets)
-    errs = {"Y": rel_fro(to_host(dl.Y), fw.Y), "dX": rel_fro(to_host(dl.dX), bw.dX)}
+    Yg, dXg = to_host(dl.Y), to_host(dl.dX)
+    errs = {"Y": rel_fro(Yg, fw.Y), "dX": rel_fro(dXg, bw.dX)}
+    # every row by itself as well (the norm over the whole tensor hides a single wrong row)
+    errs["Y_row_max"], errs["dX_row_max"] = row_rel_max(Yg, fw.Y), row_rel_max(dXg, bw.dX)
     S, dS = dl.S_list(), dl.dS_list()
+    elem = {}
     for i in range(w.N):
-        errs[f"S{i}"] = rel_fro(S[i], fw.S[i])
-        errs[f"dS{i}"] = rel_fro(dS[i], bw.dS[i])
-        errs[f"dA{i}"] = rel_fro(to_host(dl.dA[i]), bw.dA[i])
-        errs[f"dB{i}"] = rel_fro(to_host(dl.dB[i]), bw.dB[i])
+        got = {"S": S[i], "dS": dS[i], "dA": to_host(dl.dA[i]), "dB": to_host(dl.dB[i])}
+        want = {"S": fw.S[i], "dS": bw.dS[i], "dA": bw.dA[i], "dB": bw.dB[i]}
+        for name in got:
+            errs[f"{name}{i}"] = rel_fro(got[name], want[name])
+            elem[f"{name}{i}"] = elem_excess(got[name], want[name], w.dtype)     # and every element by itself
     worst = max(errs.items(), key=lambda kv: kv[1])
-    print(f"        worst {worst[0]} = {worst[1]:.3e}", flush=True)
+    worst_e = max(elem.items(), key=lambda kv: kv[1]) if elem else ("-", 0.0)
+    print(f"        worst {worst[0]} = {worst[1]:.3e}; worst element {worst_e[0]} at {worst_e[1]:.2f} of its bound", flush=True)
     bad = {k: v for k, v in errs.items() if not v <= tol}
+    bad.update({k + "_elem": v for k, v in elem.items() if not v <= 1.0})
     assert not bad, bad
     return dl, fw, bw
 
@@ -44,27 +51,29 @@ def check_full(w, tol=None, label=""):
 # ---- bookkeeping ------------------------------------------------------------------------
 def test_plan_tables_bit_exact():
     rng = np.random.default_rng(0)
-    cases = [([0, 5, 5, 12], [8, 8, 16]), ([0, 0], [4]), ([0, 300], [0])]
+    cases = [([0, 5, 5, 12], [8, 8, 16]), ([0, 0], [4]), ([0, 300], [0]),
+             ([0, 3000, 7000, 7100, 30000], [128, 8, 100, 64])]      # many row bands with unequal rank-extension work
     for _ in range(12):
         N = int(rng.integers(1, 40))
         lens = [int(x) for x in rng.integers(0, 3000, size=N)]
         ranks = [int(x) for x in rng.choice([0, 1, 4, 8, 33, 64, 128], size=N)]
         cases.append(([0] + [int(x) for x in np.cumsum(lens)], ranks))
-    for off, ranks in cases:
+    shapes = [(64, 64), (4096, 4096), (1024, 14336), (256, 128)]
+    for c, (off, ranks) in enumerate(cases):
         T = off[-1]
-        plan = ml.Plan(ml.BF16, T, 64, 64, ranks, [1.0] * len(ranks), off)
+        k, n = shapes[c % len(shapes)]            # the layer shape enters the token chunk through the panel count
+        plan = ml.Plan(ml.BF16, T, k, n, ranks, [1.0] * len(ranks), off)
         geo = plan.geometry()
         assert plan.dump(ml.TABLE_ROW_BLOCKS) == tt.row_blocks(off, ranks, geo[ml.GEO_BLOCK_ROWS])
-        # same entries as the canonical chunk table, reordered by decreasing cost (ties keep canonical order)
-        # (adapters with a rank above 64 are chunked by a value of their own when the plan also holds narrower ones)
+        assert plan.dump(ml.TABLE_CLASS_BLOCKS) == tt.class_blocks(off, ranks, geo[ml.GEO_BLOCK_ROWS], geo[ml.GEO_BLOCK_ROWS_WIDE])
+        # the token chunks the device-side scheduler chose, and the item table it built and ordered from them
         cn, cw = geo[ml.GEO_WGRAD_CHUNK_ROWS], geo[ml.GEO_WGRAD_CHUNK_ROWS_WIDE]
-        live = [r for r, a, b in zip(ranks, off[:-1], off[1:]) if r > 0 and b > a]
-        assert cn == cw or (min(live) <= 64 < max(live))
-        canon = sorted([en for en in tt.row_blocks(off, ranks, cn) if ranks[en[0]] <= 64] +
-                       [en for en in tt.row_blocks(off, ranks, cw) if ranks[en[0]] > 64])
-        cost = lambda en: en[3] * (64 + ranks[en[0]])
-        assert plan.dump(ml.TABLE_WGRAD_CHUNKS) == sorted(canon, key=lambda en: -cost(en))
+        assert (cn, cw) == tt.wgrad_chunk_rows(off, ranks, k, n, geo[ml.GEO_NUM_CUS], geo[ml.GEO_WGRAD_PANEL_COLS],
+                                               geo[ml.GEO_WGRAD_MIN_CHUNK_ROWS])
+        assert plan.dump(ml.TABLE_WGRAD_CHUNKS) == tt.wgrad_chunks(off, ranks, cn, cw)
         assert plan.dump(ml.TABLE_GEMM_ROW_TILES) == tt.gemm_row_tiles(off, geo[ml.GEO_GEMM_TILE_ROWS])
+        assert plan.dump(ml.TABLE_GEMM_BAND_ORDER) == tt.gemm_band_order(off, ranks, geo[ml.GEO_GEMM_TILE_ROWS],
+                                                                         geo[ml.GEO_GEMM_BAND_TILES])
         lens = [off[i + 1] - off[i] for i in range(len(ranks))]
         assert plan.R1 == sum(t * r for t, r in zip(lens, ranks))
         plan.destroy()
@@ -264,6 +273,16 @@ def test_rank_padded_stacked_adapters_equal_true_rank_adapters():
     for i, r in enumerate(ranks):
         assert torch.equal(dA_stack[i, :, :r], ref.dA[i]) and torch.equal(dB_stack[i, :r, :], ref.dB[i])
         assert torch.all(dA_stack[i, :, r:] == 0)                        # dA = X^T (dY B^T): zero rows of B give zero columns
+    # and against the oracle run on the stacked (padded) matrices themselves
+    Ap = [np.pad(w.A[i], ((0, 0), (0, rmax - r))) for i, r in enumerate(ranks)]
+    Bp = [np.pad(w.B[i], ((0, rmax - r), (0, 0))) for i, r in enumerate(ranks)]
+    fw = orc.forward(w.X, w.W, Ap, Bp, scales, w.offsets)
+    bw = orc.backward(w.dY, w.X, w.W, Ap, Bp, scales, w.offsets)
+    assert rel_fro(to_host(Y), fw.Y) <= 1e-2 and row_rel_max(to_host(Y), fw.Y) <= 1e-2
+    assert rel_fro(to_host(dX), bw.dX) <= 1e-2 and row_rel_max(to_host(dX), bw.dX) <= 1e-2
+    for i in range(3):
+        assert elem_excess(to_host(dA_stack[i]), bw.dA[i], "bf16") <= 1.0 and elem_excess(to_host(dB_stack[i]), bw.dB[i], "bf16") <= 1.0
+        assert rel_fro(to_host(dB_stack[i]), bw.dB[i]) <= 1e-2           # the padding rows of dB are S_pad^T dY = 0 too
     plan.destroy()
 
 
@@ -320,12 +339,12 @@ def test_equal_length_batch_matches_same_data_run_as_ragged_neighbours():
     # its grouped_mm path must agree): results for an adapter do not depend on its neighbours' lengths
     base = wl.small_case(seed=62, dtype="bf16", k=256, n=256, ranks=(16, 16, 16), seg_lens=(128, 128, 128),
                          scales=(1.0, 1.0, 1.0), b_sigma=0.3)
-    dl = DeviceLayer(base); dl.forward(); dl.backward(); dl.sync()
+    dl, _, _ = check_full(base, label="equal lengths")          # the equal-length batch itself against the oracle
     # same middle adapter, neighbours shortened -> ragged offsets
     keep = np.r_[0:50, 128:256, 256:300]
     rag = wl.Workload(name="rag", dtype="bf16", T=len(keep), k=256, n=256, ranks=base.ranks, scales=base.scales,
                       offsets=[0, 50, 178, 222], X=base.X[keep], W=base.W, A=base.A, B=base.B, dY=base.dY[keep])
-    dr = DeviceLayer(rag); dr.forward(); dr.backward(); dr.sync()
+    dr, _, _ = check_full(rag, label="same adapter between ragged neighbours")
     assert rel_fro(to_host(dr.Y[50:178]), to_host(dl.Y[128:256])) <= 1e-6
     assert rel_fro(to_host(dr.dA[1]), to_host(dl.dA[1])) <= 1e-2
     assert rel_fro(to_host(dr.dX[50:178]), to_host(dl.dX[128:256])) <= 1e-6
