@@ -133,6 +133,35 @@ def check_schedule(starts, gpus, d, g, G: int, release: Optional[Sequence[float]
     return max([now] + [starts[i] + float(d[i]) for i in range(n)])
 
 
+def check_big_m(starts, gpus, d, g, G: int, c_max: float) -> bool:
+    """The paper's program (Sec. 6.2) evaluated as printed, for given start times s_i and GPU sets (x_ig = 1 iff q in
+    gpus[i]):  sum_g x_ig = g_i and s_i + d_i <= C_max for every task, and for every pair i < j some y_ij in {0, 1} with,
+    for EVERY GPU q,
+        s_i + d_i <= s_j + M (3 - x_iq - x_jq - y_ij)       and       s_j + d_j <= s_i + M (2 - x_iq - x_jq + y_ij),
+    M = sum_i d_i.  (One y_ij per pair serves all GPUs, as the paper notes.)  M = sum d is large enough to switch a
+    constraint off only for schedules whose tasks all end by M -- which every schedule worth considering does, since
+    running the tasks one after another already ends at M; a schedule that ends later is rejected here although it may
+    satisfy the plain no-overlap statement.  True iff all constraints hold."""
+    n = len(starts)
+    M = float(sum(float(x) for x in d))
+    x = [[1 if q in gpus[i] else 0 for q in range(G)] for i in range(n)]
+    for i in range(n):
+        if sum(x[i]) != int(g[i]) or len(set(gpus[i])) != len(gpus[i]):
+            return False
+        if starts[i] < 0.0 or starts[i] + float(d[i]) > c_max + EPS:
+            return False
+    for i in range(n):
+        for j in range(i + 1, n):
+            ok_pair = False
+            for y in (0, 1):
+                if all(starts[i] + float(d[i]) <= starts[j] + M * (3 - x[i][q] - x[j][q] - y) + EPS and
+                       starts[j] + float(d[j]) <= starts[i] + M * (2 - x[i][q] - x[j][q] + y) + EPS for q in range(G)):
+                    ok_pair = True
+            if not ok_pair:
+                return False
+    return True
+
+
 def time_indexed_optimum(d: Sequence[int], g: Sequence[int], G: int, horizon: int) -> int:
     """Minimum makespan over all integer start vectors in [0, horizon), demand checked at every integer instant."""
     n = len(d)

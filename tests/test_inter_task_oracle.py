@@ -125,3 +125,107 @@ def test_cluster_event_loop():
     assert c.poll(13.5) == [(f, [0, 1])]
     with pytest.raises(KeyError):
         c.complete(14.0, a)
+
+
+# ---- the paper's program as printed, and the canonical choice pinned without the oracle's own enumeration ----------
+
+def _subsets(G, size):
+    return [list(c) for c in itertools.combinations(range(G), size)]
+
+
+def test_big_m_program_agrees_with_the_plain_checker():
+    rng = np.random.default_rng(8)
+    seen_bad = 0
+    for _ in range(80):
+        n, G = int(rng.integers(1, 5)), int(rng.integers(1, 5))
+        d = [int(x) for x in rng.integers(1, 6, size=n)]
+        g = [int(x) for x in rng.integers(1, G + 1, size=n)]
+        starts, mk = its.optimal_schedule(d, g, G)
+        gpus = its.assign_gpus(starts, d, g, G)
+        assert its.check_big_m(starts, gpus, d, g, G, mk)
+        assert not its.check_big_m(starts, gpus, d, g, G, mk - 0.5)          # C_max below a completion time
+        # a random schedule (random starts, random GPU sets): both statements of the constraints agree on it
+        # (all tasks end by M = sum d, the range in which M is big enough to switch a constraint off)
+        rs = [int(rng.integers(0, sum(d) - d[i] + 1)) for i in range(n)]
+        rg = [[int(q) for q in rng.choice(G, size=g[i], replace=False)] for i in range(n)]
+        try:
+            its.check_schedule(rs, rg, d, g, G)
+            plain_ok = True
+        except AssertionError:
+            plain_ok = False
+            seen_bad += 1
+        assert its.check_big_m(rs, rg, d, g, G, max(s + di for s, di in zip(rs, d))) == plain_ok
+    assert seen_bad > 10
+
+
+def test_optimum_of_the_big_m_program_by_brute_force():
+    # tiny integer instances: every start vector x every GPU assignment through the program as printed
+    rng = np.random.default_rng(9)
+    for _ in range(25):
+        n, G = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+        d = [int(x) for x in rng.integers(1, 4, size=n)]
+        g = [int(x) for x in rng.integers(1, G + 1, size=n)]
+        best = None
+        for starts in itertools.product(range(sum(d)), repeat=n):
+            mk = max(s + di for s, di in zip(starts, d))
+            if best is not None and mk >= best:
+                continue
+            for sets in itertools.product(*[_subsets(G, gi) for gi in g]):
+                if its.check_big_m(list(starts), list(sets), d, g, G, mk):
+                    best = mk
+                    break
+        _, mk_opt = its.optimal_schedule(d, g, G)
+        assert mk_opt == best, (d, g, G)
+
+
+def _canonical_by_brute_force(d, g, G, release, now):
+    """The canonical optimal schedule (reading 2) stated on schedules and found by brute force over integer start vectors:
+    among the start vectors that (a) respect the capacity at every instant (GPUs count from their release time on),
+    (b) reach the minimum makespan and (c) are tight -- going through the tasks in order of (start, candidate position),
+    every task starts at the earliest instant, not before the task before it, at which enough GPUs are idle -- the one
+    whose order (by start, then candidate position) comes first when orders are compared position by position in the
+    candidate order (more GPUs first, then longer, then lower index)."""
+    n = len(d)
+    cand = sorted(range(n), key=lambda i: (-g[i], -d[i], i))
+    cpos = {i: p for p, i in enumerate(cand)}
+    horizon = int(max([now] + list(release))) + sum(d) + 1
+    avail = lambda t: sum(1 for r in release if max(r, now) <= t)
+    best_mk, best = None, None
+    for starts in itertools.product(range(int(now), horizon), repeat=n):
+        mk = max([now] + [s + di for s, di in zip(starts, d)])
+        if best_mk is not None and mk > best_mk:
+            continue
+        if any(sum(g[i] for i in range(n) if starts[i] <= t < starts[i] + d[i]) > avail(t) for t in range(int(now), mk)):
+            continue
+        order = sorted(range(n), key=lambda i: (starts[i], cpos[i]))
+        tight, prev = True, int(now)
+        for p, i in enumerate(order):
+            t = prev
+            while avail(t) - sum(g[j] for j in order[:p] if starts[j] <= t < starts[j] + d[j]) < g[i]:
+                t += 1
+            if t != starts[i]:
+                tight = False
+                break
+            prev = starts[i]
+        if not tight:
+            continue
+        key = [cpos[i] for i in order]
+        if best_mk is None or mk < best_mk or key < best[0]:
+            best_mk, best = mk, (key, list(starts))
+    return best[1], best_mk
+
+
+def test_canonical_choice_equals_the_rule_stated_on_schedules():
+    rng = np.random.default_rng(10)
+    ties = 0
+    for trial in range(60):
+        n, G = int(rng.integers(1, 5)), int(rng.integers(1, 4))
+        d = [int(x) for x in rng.integers(1, 5, size=n)]
+        g = [int(x) for x in rng.integers(1, G + 1, size=n)]
+        release = [0] * G if trial % 3 else [int(x) for x in rng.integers(0, 4, size=G)]
+        now = 0 if trial % 4 else 1
+        want, mk_want = _canonical_by_brute_force(d, g, G, release, now)
+        got, mk = its.optimal_schedule(d, g, G, release, now)
+        assert mk == mk_want and [float(x) for x in want] == [float(x) for x in got], (d, g, G, release, now)
+        ties += len(set(zip(d, g))) < n
+    assert ties > 5         # instances with twin tasks, where only the order by index separates two optimal schedules
