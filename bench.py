@@ -109,11 +109,15 @@ def bench_block(args, np, torch, ml, wl) -> int:
 
 def bench_kernel_table(args, np, torch, ml, wl) -> int:
     """Grouped execution against launching the same kernels once per adapter, on the shape of the paper's kernel
-    microbenchmark.  Three ways to run one fwd+bwd of a 2048 x 2048 projection for 32 co-resident adapters:
+    microbenchmark.  Ways to run one fwd+bwd of a 2048 x 2048 projection for 32 co-resident adapters:
       grouped      one plan over all adapters, fused step (this library's default);
-      back_to_back the frozen-weight GEMMs once over the whole batch (MLORA_FLAG_BASE_ONLY), then every adapter's LoRA
-                   terms on its own rows through its own single-adapter plan (MLORA_FLAG_LORA_ONLY), one after another;
-      sequential   every adapter alone: its own fused step on its own rows, frozen-weight GEMM included."""
+      decoupled    one plan over all adapters, the paper's three-launch form: frozen-weight GEMMs (MLORA_FLAG_BASE_ONLY),
+                   then grouped shrink and fused GEMM-add (MLORA_FLAG_LORA_ONLY);
+      back_to_back the frozen-weight GEMMs once over the whole batch, then every adapter's LoRA terms on its own rows
+                   through its own single-adapter plan, one after another;
+      sequential   every adapter alone: its own fused step on its own rows, frozen-weight GEMM included.
+    Every way is captured into a HIP graph once and the graph is replayed, so that what is compared is launches on the
+    GPU and not the host's cost of issuing them (the eager, host-issued time of the grouped step is reported next to it)."""
     from paper_2604_05426_amd.harness import DeviceLayer
     k = n = 2048
     N, seq = 32, 256
@@ -152,6 +156,10 @@ def bench_kernel_table(args, np, torch, ml, wl) -> int:
         def grouped():
             dl.forward(); dl.backward()
 
+        def decoupled():
+            dl.forward(ml.FLAG_BASE_ONLY); dl.forward(ml.FLAG_LORA_ONLY)
+            dl.backward(ml.FLAG_BASE_ONLY); dl.backward(ml.FLAG_LORA_ONLY)
+
         def per_adapter(flags):
             for i, (pl, ws, Si, sl) in enumerate(singles):
                 ml.multi_lora_fwd(pl, dl.X[sl], dl.W, [dl.A[i]], [dl.B[i]], dl.Y[sl], Si, ws, flags, dl.stream)
@@ -162,9 +170,29 @@ def bench_kernel_table(args, np, torch, ml, wl) -> int:
             dl.forward(ml.FLAG_BASE_ONLY); dl.backward(ml.FLAG_BASE_ONLY)
             per_adapter(ml.FLAG_LORA_ONLY)
 
-        t_g, t_b, t_s = timed(grouped), timed(back_to_back), timed(lambda: per_adapter(0))
-        rows.append({"per_adapter_batch": bs, "tokens": sum(lens), "grouped_ms": t_g, "back_to_back_ms": t_b, "sequential_ms": t_s,
-                     "grouped_over_back_to_back": t_b / t_g, "grouped_over_sequential": t_s / t_g})
+        def sequential():
+            per_adapter(0)
+
+        def graphed(fn):
+            fn()                                   # once eagerly: nothing is initialised inside the capture
+            torch.cuda.synchronize()
+            graph, side, eager_stream = torch.cuda.CUDAGraph(), torch.cuda.Stream(), dl.stream
+            with torch.cuda.graph(graph, stream=side):
+                dl.stream = torch.cuda.current_stream().cuda_stream
+                fn()
+            dl.stream = eager_stream
+            return graph
+
+        t_eager = timed(grouped)
+        graphs = {name: graphed(fn) for name, fn in (("grouped", grouped), ("decoupled", decoupled),
+                                                     ("back_to_back", back_to_back), ("sequential", sequential))}
+        t = {name: timed(g.replay) for name, g in graphs.items()}
+        rows.append({"per_adapter_batch": bs, "tokens": sum(lens), "grouped_eager_ms": t_eager, "grouped_ms": t["grouped"],
+                     "decoupled_ms": t["decoupled"], "back_to_back_ms": t["back_to_back"], "sequential_ms": t["sequential"],
+                     "decoupled_over_fused": t["decoupled"] / t["grouped"],
+                     "grouped_over_back_to_back": t["back_to_back"] / t["grouped"],
+                     "grouped_over_sequential": t["sequential"] / t["grouped"]})
+        del graphs
         for pl, _, _, _ in singles:
             pl.destroy()
         dl.plan.destroy()
@@ -172,7 +200,101 @@ def bench_kernel_table(args, np, torch, ml, wl) -> int:
            "unit": "x", "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": rows[0]["grouped_ms"], "higher_is_better": True,
            "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
            "config": {"workload": "kernel_table: 32 adapters, ranks 16/32/64 mixed, k = n = 2048, 256-token sequences", "adapters": N,
-                      "ranks": ranks}, "table": rows}
+                      "ranks": ranks, "mode": "every variant replayed from a captured HIP graph"}, "table": rows}
+    print(json.dumps(out))
+    return 0
+
+
+def bench_power_clock(args, np, torch, ml, wl) -> int:
+    """Evidence for what bounds the frozen-weight GEMM: socket power and shader clock (sampled with amd-smi from a
+    side thread) while, one after the other, the GPU idles, runs the register-only MFMA loop on zeros and on random
+    operands, and runs the fused GEMMs of a config back to back; next to them the rates reached in the same run."""
+    import re
+    import subprocess
+    import threading
+    from paper_2604_05426_amd.harness import DeviceLayer
+    cfg = args.config if args.config is not None else HEADLINE_CONFIG
+    dtype, k, n, ranks, lens, scales, seed, _ = wl.config_shape(cfg - 1)
+    dl = DeviceLayer.synthetic(f"config{cfg}", dtype, k, n, ranks, lens, scales, seed)
+    T = dl.w.T
+    scratch = torch.zeros(4096, dtype=torch.uint8, device=dl.device)
+
+    def run_tool(cmd):
+        try:
+            return subprocess.run(cmd, capture_output=True, text=True, timeout=20).stdout
+        except Exception:             # the tools are not part of the measurement: without them the fields stay empty
+            return ""
+
+    m = re.search(r"Max Graphics Package Power \(W\): ([0-9.]+)", run_tool(["rocm-smi", "--showmaxpower"]))
+    power_limit = float(m.group(1)) if m else None
+
+    def smi_sample():
+        txt = run_tool(["amd-smi", "metric", "-p", "-c"])
+        out = {}
+        m = re.search(r"SOCKET_POWER: ([0-9.]+) W", txt)
+        if m:
+            out["power_w"] = float(m.group(1))
+        clks = [float(x) for x in re.findall(r"GFX_\d+:\s+CLK: ([0-9.]+) MHz", txt)]     # one shader clock per XCD
+        if clks:
+            out["sclk_mhz"] = float(np.mean(clks))
+        return out
+
+    def phase(label, work, seconds):
+        """Run `work` repeatedly for `seconds` while a side thread samples power and clock."""
+        samples, stop = [], threading.Event()
+
+        def sampler():
+            time.sleep(0.3)           # let the phase reach its steady state
+            while not stop.is_set():
+                samples.append(smi_sample())
+
+        th = threading.Thread(target=sampler)
+        th.start()
+        t0, reps = time.perf_counter(), 0
+        start, end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        start.record()
+        while time.perf_counter() - t0 < seconds:
+            if work is None:
+                time.sleep(0.05)
+            else:
+                for _ in range(4):
+                    work()
+                    reps += 1
+                torch.cuda.synchronize()
+        end.record()
+        torch.cuda.synchronize()
+        stop.set()
+        th.join()
+        pw = [x["power_w"] for x in samples if "power_w" in x]
+        ck = [x["sclk_mhz"] for x in samples if "sclk_mhz" in x]
+        return {"phase": label, "samples": len(samples), "power_w_mean": float(np.mean(pw)) if pw else None,
+                "power_w_max": float(np.max(pw)) if pw else None, "sclk_mhz_mean": float(np.mean(ck)) if ck else None,
+                "sclk_mhz_min": float(np.min(ck)) if ck else None, "power_limit_w": power_limit,
+                "ms_per_call": start.elapsed_time(end) / max(reps, 1), "calls": reps}
+
+    rows = [phase("idle", None, 2.0)]
+    zeros = {}
+    rows.append(phase("mfma loop, zero operands", lambda: zeros.update(t=ml.multi_lora_calib_mfma(False, scratch, dl.stream)), 3.0))
+    rows[-1]["tflops"] = zeros["t"]
+    rnd = {}
+    rows.append(phase("mfma loop, random operands", lambda: rnd.update(t=ml.multi_lora_calib_mfma(True, scratch, dl.stream)), 3.0))
+    rows[-1]["tflops"] = rnd["t"]
+    flop = 2.0 * T * k * n
+    for label, fn in (("fused GEMM forward (frozen weight only), back to back", lambda: dl.forward(ml.FLAG_BASE_ONLY)),
+                      ("fused GEMM backward (frozen weight only), back to back", lambda: dl.backward(ml.FLAG_BASE_ONLY)),
+                      ("whole fused step", lambda: (dl.forward(), dl.backward()))):
+        dl.forward(); dl.backward()
+        rows.append(phase(label, fn, 4.0))
+        if "step" not in label:
+            rows[-1]["tflops"] = flop / (rows[-1]["ms_per_call"] * 1e-3) / 1e12
+            rows[-1]["frac_bf16_mfma_peak"] = rows[-1]["tflops"] / PEAK_BF16_MFMA_TFLOPS
+            rows[-1]["frac_of_mfma_loop_random"] = rows[-1]["tflops"] / rnd["t"]
+    out = {"metric": "socket power and shader clock under the fused GEMM", "value": rows[3].get("tflops"), "unit": "TFLOP/s",
+           "n_gpus": 1, "steps": rows[3]["calls"], "warmup": 0, "ms_per_step": rows[3]["ms_per_call"], "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": f"config{cfg}:{wl.CONFIG_NAMES[cfg - 1]}", "T": T, "k": k, "n": n,
+                      "mode": "socket power and the mean shader clock of the 8 XCDs, sampled with amd-smi while the kernels run"},
+           "nominal_clock_mhz_of_published_peak": 2400, "phases": rows}
     print(json.dumps(out))
     return 0
 
@@ -434,6 +556,9 @@ def main() -> int:
                     help="the paper's kernel microbenchmark shape (Sec. 8.3 ablation, kernel table): 32 adapters, ranks "
                          "16/32/64 equally mixed, Llama-3.2-1B width, per-adapter batch 1/2/4 x 256 tokens; grouped launch "
                          "against per-adapter launches of the same kernels")
+    ap.add_argument("--power-clock", action="store_true",
+                    help="sample socket power and shader clock (amd-smi) while the MFMA calibration loops and the fused GEMMs "
+                         "of --config (default: the headline config) run: the evidence for what bounds the GEMM")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 1 GiB device copy 3 times (calibrates FETCH_SIZE / WRITE_SIZE under rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -457,6 +582,8 @@ def main() -> int:
         return bench_block(args, np, torch, ml, wl)
     if args.kernel_table:
         return bench_kernel_table(args, np, torch, ml, wl)
+    if args.power_clock:
+        return bench_power_clock(args, np, torch, ml, wl)
 
     mods = (np, torch, ml, wl, DeviceLayer)
     head_cfg = args.config if args.config is not None else HEADLINE_CONFIG

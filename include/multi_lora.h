@@ -89,9 +89,10 @@ typedef enum {
                                    first, then the others; inside a class by decreasing cost rows x (64 + rank), ties in
                                    canonical order (the device-side balancing of heterogeneous segments);
                                    tables above 16384 entries keep the canonical order inside each class. */
-    MLORA_TABLE_CLASS_BLOCKS = 3, /* the entries of MLORA_TABLE_ROW_BLOCKS in the order the grouped kernels walk them:
-                                   adapters with a rank above 64 first (their blocks run longest and take a kernel
-                                   build of their own), then the others, canonical order inside a class. */
+    MLORA_TABLE_CLASS_BLOCKS = 3, /* the LoRA blocks in the order the grouped kernels walk them, same entry format as
+                                   MLORA_TABLE_ROW_BLOCKS: adapters with a rank above 64 first (their blocks run longest
+                                   and take a kernel build of their own), cut every MLORA_GEO_BLOCK_ROWS_WIDE rows, then
+                                   the others, cut every MLORA_GEO_BLOCK_ROWS rows; canonical order inside a class. */
     MLORA_TABLE_GEMM_BAND_ORDER = 4 /* launch order of the fused GEMMs' row bands (MLORA_GEO_GEMM_BAND_TILES consecutive
                                    row tiles x all column tiles are in flight together), 4 x int32: band, first row tile,
                                    row tiles, cost = rank-extension passes of its row tiles (per row tile, one per 64 ranks

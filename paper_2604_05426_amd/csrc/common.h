@@ -14,7 +14,7 @@ namespace mlora {
 
 // ---- tiling constants (reported through multi_lora_plan_geometry) ------------------
 constexpr int kBlockRows = 64;       // rows per LoRA block of the shrink kernels
-constexpr int kBlockRowsWide = 64;   // the same for adapters of the wide rank class
+constexpr int kBlockRowsWide = 128;  // the same for adapters of the wide rank class (their adapter tiles are the larger operand)
 constexpr int kGemmBandTiles = 8;    // row tiles per band of the fused GEMM's tile order
 constexpr int kGemmTileRows = 256;   // fused GEMM macro tile
 constexpr int kGemmTileCols = 256;

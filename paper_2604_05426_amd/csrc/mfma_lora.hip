@@ -215,7 +215,7 @@ __device__ __forceinline__ void shrink_body(const ShrinkArgs& g, const Entry4 e,
 template <bool FWD, bool WIDE>
 __global__ __launch_bounds__(64 * SNW) void shrink_kernel(ShrinkArgs g) {
     __shared__ __attribute__((aligned(16))) u16 lds[163840 / 2];
-    const Entry4 e = g.pv.class_blocks[blockIdx.x];
+    const Entry4 e = g.pv.row_blocks[blockIdx.x];      // the canonical 64-row blocks
     if (WIDE && g.pv.rank[e.a] > 64) shrink_body<FWD, 4, 32, 2, 1>(g, e, lds);
     else shrink_body<FWD, 2, 64, 2, 1>(g, e, lds);
 }
@@ -234,16 +234,20 @@ __global__ __launch_bounds__(64 * SNW) void shrink_kernel(ShrinkArgs g) {
 // at c ^ (t & 7); the A_i tile [k][ranks], read with the transposing load, keeps 32-byte unit u of row k at u ^ nn_swz(k)
 // (256-byte rows) or u ^ (((k >> 1) & 1) | (((k >> 3) & 1) << 1)) (128-byte rows).  Rows past the block and ranks past r_i
 // are clamped to valid addresses; they only feed outputs that are not stored.
-constexpr int ST_XT = 8192;     // X / dY tile bytes
-
-template <bool FWD, int RB16, bool DENSE = false>
+//   8 with ROWS = 128 (ranks 65..128, the wide rank class, whose row blocks are 128 rows): X / dY tile 16 KB, adapter tile 16 KB,
+//     five 32 KB stages; wavefront w owns row block w (of eight) and all eight rank blocks.  With 64-row blocks the adapter tile was
+//     twice the X tile and both go through the same load path of the CU; 128 rows halve that traffic per X byte.
+template <bool FWD, int RB16, bool DENSE = false, int ROWS = 64>
 __device__ __forceinline__ void shrink_tiled_body(const ShrinkArgs& g, const Entry4 e, unsigned char* lds) {
     static_assert(FWD || !DENSE, "the dense adapter tile is a layout of A_i");
+    static_assert(ROWS == 64 || (ROWS == 128 && RB16 == 8 && !DENSE), "128-row blocks: wide rank class, swizzled adapter tile");
+    constexpr int ST_XT = ROWS * 128;               // X / dY tile bytes
     constexpr int FT = RB16 * 2048;                 // adapter tile bytes
     constexpr int STAGE = ST_XT + FT;
-    constexpr int NST = RB16 == 8 ? 6 : 9;          // ring stages (144 KB either way)
+    constexpr int NST = ROWS == 128 ? 5 : RB16 == 8 ? 6 : 9;   // ring stages (144 KB; 160 KB with 128-row blocks)
+    constexpr int NX = ROWS / 64;                   // X-tile loads per wavefront per step
     constexpr int NF = RB16 / 4;                    // adapter-tile loads per wavefront per step
-    constexpr int NCB = RB16 / 2;                   // rank blocks per wavefront
+    constexpr int NCB = ROWS == 128 ? RB16 : RB16 / 2;   // rank blocks per wavefront
     constexpr int FROW = RB16 * 32;                 // FWD: bytes per contraction row of the A_i tile
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -256,10 +260,13 @@ __device__ __forceinline__ void shrink_tiled_body(const ShrinkArgs& g, const Ent
     auto fkey = [](int k) { return RB16 == 8 ? nn_swz(k) : (((k >> 1) & 1) | (((k >> 3) & 1) << 1)); };
 
     // per-lane byte offsets of the direct loads this wavefront issues per step
-    unsigned voffX, voffF[NF];
+    unsigned voffX[NX], voffF[NF];
     {
-        const int row = 8 * wave + (lane >> 3);
-        voffX = (unsigned)(((int64_t)min(row, rows - 1) * g.ld + (((lane & 7) ^ (lane >> 3)) << 3)) * 2);
+#pragma unroll
+        for (int j = 0; j < NX; ++j) {
+            const int row = 8 * (NX * wave + j) + (lane >> 3);
+            voffX[j] = (unsigned)(((int64_t)min(row, rows - 1) * g.ld + (((lane & 7) ^ (lane >> 3)) << 3)) * 2);
+        }
 #pragma unroll
         for (int j = 0; j < NF; ++j) {
             const int kb = NF * wave + j;        // 1 KB piece of the adapter tile
@@ -285,14 +292,15 @@ __device__ __forceinline__ void shrink_tiled_body(const ShrinkArgs& g, const Ent
     auto issue = [&]() {                  // past the last step the last one is loaded again (keeps the wait counts uniform)
         const int t = min(issued, steps - 1);
         const unsigned dst = lds0 + slot_in * STAGE;
-        dma16(voffX, baseX + (int64_t)t * 128, dst + wave * 1024);
+#pragma unroll
+        for (int j = 0; j < NX; ++j) dma16(voffX[j], baseX + (int64_t)t * 128, dst + (NX * wave + j) * 1024);
 #pragma unroll
         for (int j = 0; j < NF; ++j) dma16(voffF[j], baseF + t * stepF, dst + ST_XT + (NF * wave + j) * 1024);
         ++issued;
         slot_in = slot_in == NST - 1 ? 0 : slot_in + 1;
     };
 
-    const int rb = wave & 3, ch = wave >> 2;
+    const int rb = ROWS == 128 ? wave : (wave & 3), ch = ROWS == 128 ? 0 : (wave >> 2);
     f32x4 acc[NCB];
 #pragma unroll
     for (int j = 0; j < NCB; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -332,7 +340,7 @@ __device__ __forceinline__ void shrink_tiled_body(const ShrinkArgs& g, const Ent
         // step t-1, whose slot the next load overwrites
         if (RB16 == 8) asm volatile("s_waitcnt vmcnt(12)\n\ts_barrier" ::: "memory");
         else           asm volatile("s_waitcnt vmcnt(14)\n\ts_barrier" ::: "memory");
-        static_assert((1 + NF) * (NST - 2) == (RB16 == 8 ? 12 : 14), "wait count = loads of the steps that may still be in flight");
+        static_assert((NX + NF) * (NST - 2) == (RB16 == 8 ? 12 : 14), "wait count = loads of the steps that may still be in flight");
         issue();
         compute(slot);
         slot = slot == NST - 1 ? 0 : slot + 1;
@@ -359,20 +367,27 @@ __device__ __forceinline__ void shrink_tiled_body(const ShrinkArgs& g, const Ent
 // not a multiple of 8 (forward form only): a rank that is a multiple of 4 takes the tiled body with the adapter tile kept
 // dense in LDS (rows of 2 r bytes: 8-byte granules, which is what one lane of the transposing load reads), any other rank
 // the register-staged body.  Uniform branches per work group.
+// Row blocks of the wide class have 128 rows (kBlockRowsWide); the bodies built for 64 rows take such a block as two halves.
 template <bool FWD, bool WIDE, bool MIXED>
 __global__ __launch_bounds__(64 * SNW) void shrink_tiled_kernel(ShrinkArgs g) {
-    __shared__ __attribute__((aligned(1024))) unsigned char lds[MIXED ? 163840 : 147456];
+    __shared__ __attribute__((aligned(1024))) unsigned char lds[(MIXED || WIDE) ? 163840 : 147456];
     const Entry4 e = g.pv.class_blocks[blockIdx.x];
     const int r = g.pv.rank[e.a];
-    if (MIXED && FWD && (r & 7) == 4) {
-        if (WIDE && r > 64) shrink_tiled_body<FWD, 8, FWD>(g, e, lds);
-        else shrink_tiled_body<FWD, 4, FWD>(g, e, lds);
+    if (WIDE && r > 64) {
+        if (!MIXED || (r & 7) == 0) {
+            shrink_tiled_body<FWD, 8, false, kBlockRowsWide>(g, e, lds);
+        } else {
+            for (int h = 0; h < e.d; h += SR) {       // (uniform)
+                const Entry4 half{e.a, e.b, e.c + h, min(SR, e.d - h)};
+                if (h) __syncthreads();               // every wavefront is done with the first half's tiles
+                if (FWD && (r & 7) == 4) shrink_tiled_body<FWD, 8, FWD>(g, half, lds);
+                else shrink_body<FWD, 4, 32, 2, 1>(g, half, reinterpret_cast<u16*>(lds));
+            }
+        }
+    } else if (MIXED && FWD && (r & 7) == 4) {
+        shrink_tiled_body<FWD, 4, FWD>(g, e, lds);
     } else if (MIXED && (r & 7) != 0) {
-        u16* l16p = reinterpret_cast<u16*>(lds);
-        if (WIDE && r > 64) shrink_body<FWD, 4, 32, 2, 1>(g, e, l16p);
-        else shrink_body<FWD, 2, 64, 2, 1>(g, e, l16p);
-    } else if (WIDE && r > 64) {
-        shrink_tiled_body<FWD, 8>(g, e, lds);
+        shrink_body<FWD, 2, 64, 2, 1>(g, e, reinterpret_cast<u16*>(lds));
     } else {
         shrink_tiled_body<FWD, 4>(g, e, lds);
     }
@@ -380,13 +395,15 @@ __global__ __launch_bounds__(64 * SNW) void shrink_tiled_kernel(ShrinkArgs g) {
 
 template <bool FWD>
 static void launch_shrink(mlora_plan* p, ShrinkArgs a, hipStream_t st) {
-    const dim3 grid(p->n_row_blocks), block(64 * SNW);
+    const dim3 block(64 * SNW);
     // the tiled kernels address rows with 32-bit lane offsets: rows of at most 2^22 elements
     const bool tiled = a.Kdim >= 64 && a.Kdim % 64 == 0 && a.ld <= ((int64_t)1 << 22);
     const bool wide = p->n_blocks_wide != 0;
     // (the forward form reads A_i in 16-byte chunks of a rank row: row blocks of adapters whose rank is not a multiple of 8
     // keep the register-staged body; B_i is read along its rows, any rank will do)
     const bool mixed = FWD && !p->ranks_mult8;
+    // the tiled kernels walk the class table (wide class first, 128-row blocks); the register-staged ones the canonical 64-row blocks
+    const dim3 grid(tiled ? p->n_blocks_wide + p->n_blocks_narrow : p->n_row_blocks);
     if (tiled && !mixed) {
         if (!wide) hipLaunchKernelGGL((shrink_tiled_kernel<FWD, false, false>), grid, block, 0, st, a);
         else       hipLaunchKernelGGL((shrink_tiled_kernel<FWD, true, false>), grid, block, 0, st, a);
@@ -693,7 +710,7 @@ struct ExpandArgs {
     int32_t Ncols, col_tiles;
     int32_t stream_out;      // streaming stores for the output
     int32_t stream_in;       // non-temporal loads for the old output tile
-    const Entry4* blocks;    // the row blocks this launch covers (one rank class of pv.class_blocks, or all of them)
+    const Entry4* blocks;    // the row blocks this launch covers: one rank class of pv.class_blocks
     PlanView pv;
 };
 
@@ -710,10 +727,13 @@ __global__ __launch_bounds__(256) void expand_add_kernel(ExpandArgs g) {
     const int wr = wave >> 1, wc = wave & 1;
     const int l16 = lane & 15, g4 = lane >> 4;
     // row-block-major: consecutive workgroups cover adjacent column tiles of the same 64 rows
+    constexpr int PARTS = (MAXKS == 4 ? kBlockRowsWide : kBlockRows) / 64;   // 64-row work items per block of this class's table
     const int bsel = blockIdx.x / g.col_tiles;
-    const Entry4 e = g.blocks[bsel];
+    const Entry4 e = g.blocks[bsel / PARTS];
     const int ct = blockIdx.x % g.col_tiles;
-    const int i = e.a, row0 = e.c, rows = e.d;
+    const int part = bsel % PARTS;
+    const int i = e.a, row0 = e.c + 64 * part, rows = min(64, e.d - 64 * part);
+    if (PARTS > 1 && rows <= 0) return;          // a last block of at most 64 rows has no second part (uniform)
     const int r = g.pv.rank[i];
     const int ksteps = (r + 31) / 32;
     const int64_t so = g.pv.soff[i];
@@ -881,7 +901,8 @@ static int launch_expand(mlora_plan* p, bool fwd, void* C, const void* E, hipStr
     auto go = [&](bool narrow, int32_t nblocks, const Entry4* blocks) {
         if (nblocks <= 0) return;
         a.blocks = blocks;
-        const dim3 grid((unsigned)((int64_t)nblocks * a.col_tiles));
+        const int parts = (narrow ? kBlockRows : kBlockRowsWide) / 64;     // 64-row work items per block of the class table
+        const dim3 grid((unsigned)((int64_t)nblocks * parts * a.col_tiles));
         if (fwd && narrow)      hipLaunchKernelGGL((expand_add_kernel<true, 2>), grid, dim3(256), 0, st, a);
         else if (fwd)           hipLaunchKernelGGL((expand_add_kernel<true, 4>), grid, dim3(256), 0, st, a);
         else if (narrow)        hipLaunchKernelGGL((expand_add_kernel<false, 2>), grid, dim3(256), 0, st, a);

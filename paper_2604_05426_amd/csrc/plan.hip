@@ -410,7 +410,7 @@ static int plan_create_impl(mlora_plan** out, int dtype, int64_t T, int64_t k, i
 
     // Host side: sizes that follow from the adapters alone (one pass over the adapters, none over blocks or chunks).
     // The tables themselves, the token chunks and everything that depends on them come from the device.
-    int64_t R1 = 0, rb = 0, rb_wide = 0;
+    int64_t R1 = 0, rb = 0, rb_wide = 0, rb_narrow = 0;
     for (int32_t i = 0; i < N; ++i) {
         const int64_t Ti = p->off[i + 1] - p->off[i];
         R1 += Ti * ranks[i];
@@ -419,14 +419,17 @@ static int plan_create_impl(mlora_plan** out, int dtype, int64_t T, int64_t k, i
         if (Ti <= 0 || ranks[i] <= 0) continue;
         rb += ceil_div(Ti, kBlockRows);
         if (ranks[i] % 8) p->ranks_mult8 = false;
-        if (ranks[i] > kNarrowMaxRank) rb_wide += ceil_div(Ti, kBlockRowsWide);
-        else if (ranks[i] > p->max_rank_narrow) p->max_rank_narrow = ranks[i];
+        if (ranks[i] > kNarrowMaxRank) {
+            rb_wide += ceil_div(Ti, kBlockRowsWide);
+        } else {
+            rb_narrow += ceil_div(Ti, kBlockRows);
+            if (ranks[i] > p->max_rank_narrow) p->max_rank_narrow = ranks[i];
+        }
     }
-    static_assert(kBlockRows == kBlockRowsWide, "the class table holds the same blocks as the canonical one");
     p->R1 = R1;
     p->n_row_blocks = (int32_t)rb;
     p->n_blocks_wide = (int32_t)rb_wide;
-    p->n_blocks_narrow = (int32_t)(rb - rb_wide);
+    p->n_blocks_narrow = (int32_t)rb_narrow;
     p->n_gemm_tiles = (int32_t)ceil_div(T, kGemmTileRows);
     p->n_bands = (int32_t)ceil_div(p->n_gemm_tiles, kGemmBandTiles);
     p->shares_tables = like != nullptr;
@@ -520,14 +523,15 @@ static int plan_create_impl(mlora_plan** out, int dtype, int64_t T, int64_t k, i
         d_wc_tmp = (Entry4*)((char*)block2->ptr + tab);
     }
 
+    const int32_t n_class_blocks = p->n_blocks_wide + p->n_blocks_narrow;
     // table builds on the plan's stream (their inputs were complete when the wait above returned)
     hipStream_t st = p->build_stream;
     auto grid_for = [](int32_t cnt) { return dim3((unsigned)((cnt + 255) / 256)); };
     if (own_seg && p->n_row_blocks > 0) {
         hipLaunchKernelGGL(plan_fill_blocks_kernel, grid_for(p->n_row_blocks), dim3(256), 0, st, N, d_off, d_rank, d_rbs, d_rbs,
                            kBlockRows, kBlockRows, d_rb, p->n_row_blocks);
-        hipLaunchKernelGGL(plan_fill_blocks_kernel, grid_for(p->n_row_blocks), dim3(256), 0, st, N, d_off, d_rank, d_cbs, d_cbp,
-                           kBlockRows, kBlockRowsWide, d_cb, p->n_row_blocks);
+        hipLaunchKernelGGL(plan_fill_blocks_kernel, grid_for(n_class_blocks), dim3(256), 0, st, N, d_off, d_rank, d_cbs, d_cbp,
+                           kBlockRows, kBlockRowsWide, d_cb, n_class_blocks);
     }
     if (geo.n_chunks > 0) {
         // class-ordered canonical table, then reordered by cost inside each class (very large tables keep the first)
@@ -556,7 +560,7 @@ static int plan_create_impl(mlora_plan** out, int dtype, int64_t T, int64_t k, i
     v.N = N; v.T = T; v.k = k; v.n = n;
     v.off = d_off; v.rank = d_rank; v.scale = d_scale; v.soff = d_soff; v.ptrs = p->d_ptrs;
     v.row_blocks = d_rb; v.n_row_blocks = p->n_row_blocks;
-    v.class_blocks = d_cb; v.n_class_blocks = p->n_row_blocks;
+    v.class_blocks = d_cb; v.n_class_blocks = n_class_blocks;
     v.gemm_tiles = d_gt; v.n_gemm_tiles = p->n_gemm_tiles;
     v.band_order = d_bo; v.n_bands = p->n_bands;
     v.wgrad_chunks = d_wc; v.n_wgrad_chunks = geo.n_chunks;
@@ -705,7 +709,7 @@ extern "C" int multi_lora_plan_dump(const mlora_plan* plan, int which, int32_t* 
         case MLORA_TABLE_ROW_BLOCKS: src = plan->view.row_blocks; cnt = plan->n_row_blocks; break;
         case MLORA_TABLE_GEMM_ROW_TILES: src = plan->view.gemm_tiles; cnt = plan->n_gemm_tiles; break;
         case MLORA_TABLE_WGRAD_CHUNKS: src = plan->view.wgrad_chunks; cnt = plan->geo.n_chunks; break;
-        case MLORA_TABLE_CLASS_BLOCKS: src = plan->view.class_blocks; cnt = plan->n_row_blocks; break;
+        case MLORA_TABLE_CLASS_BLOCKS: src = plan->view.class_blocks; cnt = plan->view.n_class_blocks; break;
         case MLORA_TABLE_GEMM_BAND_ORDER: src = plan->view.band_order; cnt = plan->n_bands; break;
         default:
             set_error("unknown table id");
