@@ -325,8 +325,11 @@ def committed_traffic(config: int):
     traffic, sha = {}, None
     for line in open(prof):
         parts = line.split()
-        if len(parts) == 3 and parts[0] == "traffic_bytes" and parts[1] in names:
-            traffic[names[parts[1]]] = traffic.get(names[parts[1]], 0.0) + float(parts[2])
+        if len(parts) == 3 and parts[0] == "traffic_bytes":
+            for key, short in names.items():        # (the launches of one step's rank classes add up)
+                if parts[1].startswith(key):
+                    traffic[short] = traffic.get(short, 0.0) + float(parts[2])
+                    break
         if len(parts) == 2 and parts[0] == "kernel_sources_sha256":
             sha = parts[1]
     if sha != kernel_sources_sha256():
@@ -356,7 +359,17 @@ def cpu_oracle_baseline(w, np, budget_s: float):
     per_token = 4.0 * w.k * w.n
     cal_per_adapter = int(max(1, min(max(w.seg_lens), 4e9 / per_token / max(1, w.N))))
     cal_tokens, cal_dt = sample(cal_per_adapter)
-    per_adapter = int(max(1, min(max(w.seg_lens), (budget_s / max(cal_dt, 1e-3)) * cal_tokens / max(1, w.N))))
+    # A call has a fixed cost (thread start, widening W to fp64) next to the cost per token: two small runs give both,
+    # and the final sample is sized so that the whole call takes about budget_s.
+    cap = max(w.seg_lens)
+    mid_per_adapter = min(cap, max(cal_per_adapter + 1, 3 * cal_per_adapter))
+    mid_tokens, mid_dt = sample(mid_per_adapter)
+    if mid_tokens > cal_tokens and mid_dt > cal_dt:
+        per_token = (mid_dt - cal_dt) / (mid_tokens - cal_tokens)
+        fixed = max(0.0, cal_dt - per_token * cal_tokens)
+    else:
+        per_token, fixed = mid_dt / max(mid_tokens, 1), 0.0
+    per_adapter = int(max(1, min(cap, (budget_s - fixed) / max(per_token, 1e-9) / max(1, w.N))))
     ntok, dt = sample(per_adapter)
     return {"value": ntok / dt, "unit": "tokens/s", "cores": orc.num_threads(), "kind": "oracle", "seconds": dt,
             "sample": f"first {per_adapter} tokens of each of the {w.N} adapters ({ntok} of {w.T} tokens), "
@@ -478,8 +491,24 @@ def measure_layer(config: int, args, mods, extras: bool, lora_and_base: bool, ce
         small = (2 * sum_r * (k + n) + 2 * R1) * e
         bytes_f = (T * k + 2 * T * n) * e + (sum_r * (k + n) + 2 * R1) * e
         bytes_b = (2 * T * n + T * k + 2 * T * k) * e + small + 3 * R1 * e
+        # per-kernel times of the same path (expand-add launches report under the ids of the GEMMs they stand in for)
+        dl.plan.profile_begin(K * 16)
+        for _ in range(K):
+            step(ml.FLAG_LORA_ONLY)
+        per_lo = {}
+        for kid, ms in dl.plan.profile_end(K * 16):
+            per_lo.setdefault({"gemm_fwd": "expand_add_fwd", "gemm_bwd": "expand_add_bwd"}.get(ml.KERNEL_NAMES[kid], ml.KERNEL_NAMES[kid]), []).append(ms)
+        alg_lo = {"shrink": (T * k + sum_r * k + R1) * e, "dshrink": (T * n + sum_r * n + R1) * e,
+                  "wgrad": (T * k + T * n + 2 * R1 + sum_r * (k + n)) * e,
+                  "expand_add_fwd": (2 * T * n + R1 + sum_r * n) * e, "expand_add_bwd": (2 * T * k + R1 + sum_r * k) * e}
+        kern_lo = {}
+        for name, v in per_lo.items():
+            t = float(np.sum(v)) / K * 1e-3
+            kern_lo[name] = {"ms_per_step": t * 1e3}
+            if name in alg_lo:
+                kern_lo[name].update(algorithmic_bytes=alg_lo[name], achieved_gbs=alg_lo[name] / t / 1e9, frac_hbm=alg_lo[name] / t / 1e9 / PEAK_HBM_GBS)
         out["lora_path"] = {
-            "mode": "MLORA_FLAG_LORA_ONLY", "fwd_ms": ms_lf, "bwd_ms": ms_lb,
+            "mode": "MLORA_FLAG_LORA_ONLY", "fwd_ms": ms_lf, "bwd_ms": ms_lb, "kernels": kern_lo,
             "fwd_gbs": bytes_f / (ms_lf * 1e-3) / 1e9, "bwd_gbs": bytes_b / (ms_lb * 1e-3) / 1e9,
             "frac_hbm": (bytes_f + bytes_b) / ((ms_lf + ms_lb) * 1e-3) / 1e9 / PEAK_HBM_GBS,
             "algorithmic_bytes_fwd": bytes_f, "algorithmic_bytes_bwd": bytes_b,
@@ -590,7 +619,7 @@ def main() -> int:
     extras = not args.no_extra
     full = extras and not args.fused_only
     h = measure_layer(head_cfg, args, mods, extras=extras, lora_and_base=full, ceilings=full,
-                      cpu_budget_s=0.0 if args.no_cpu else 15.0)
+                      cpu_budget_s=0.0 if args.no_cpu else 12.0)
     out = {
         "metric": "multi-LoRA layer fwd+bwd tokens/s", "value": h["value"], "unit": "tokens/s",
         "n_gpus": 1, "steps": h["steps"], "warmup": h["warmup"], "warmup_clock_settle_steps": h["warmup_clock_settle_steps"],
@@ -606,7 +635,7 @@ def main() -> int:
     if args.config is None and not args.no_configs:
         # the other bf16 configs, same fields, a shorter CPU leg each
         out["configs"] = [measure_layer(c, args, mods, extras=extras, lora_and_base=full, ceilings=False,
-                                        cpu_budget_s=0.0 if args.no_cpu else 4.0) for c in OTHER_CONFIGS]
+                                        cpu_budget_s=0.0 if args.no_cpu else 3.0) for c in OTHER_CONFIGS]
     print(json.dumps(out))
     return 0
 
