@@ -12,12 +12,21 @@ from . import binding as ml
 from .workloads import Workload, bf16_bits
 
 
-def to_device(a: np.ndarray, dtype: str, device) -> torch.Tensor:
-    """float32 host array (holding values exact in `dtype`) -> device tensor of that dtype."""
+def to_device(a: np.ndarray, dtype: str, device, nan_guard: bool = False) -> torch.Tensor:
+    """float32 host array (holding values exact in `dtype`) -> device tensor of that dtype.  With `nan_guard` the tensor
+    is a view into a larger allocation whose head and tail are NaN: a kernel that reads past either end of an input and
+    lets the value reach an output poisons that output, which the parity checks then catch."""
     if dtype == "bf16":
         bits = bf16_bits(a).view(np.int16)
-        return torch.from_numpy(bits).to(device).view(torch.bfloat16)
-    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device)
+        t = torch.from_numpy(bits).to(device).view(torch.bfloat16)
+    else:
+        t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device)
+    if not nan_guard:
+        return t
+    buf = torch.full((t.numel() + 2 * GUARD_ELEMS,), float("nan"), dtype=t.dtype, device=device)
+    view = buf[GUARD_ELEMS:GUARD_ELEMS + t.numel()].view(t.shape)
+    view.copy_(t)
+    return view
 
 
 def to_host(t: torch.Tensor) -> np.ndarray:
@@ -34,7 +43,8 @@ class DeviceLayer:
 
     With ``guards`` (the default) every output the library writes -- Y, dX, S, dA_i, dB_i and the workspace -- sits
     inside a larger allocation between two guard regions filled with a known value; ``check_guards`` (called by
-    ``sync``) asserts that no kernel wrote outside the tensor it was given."""
+    ``sync``) asserts that no kernel wrote outside the tensor it was given.  The inputs (X, W, dY, A_i, B_i) sit between
+    NaN regions, so that a value read from outside an input cannot reach an output unnoticed."""
 
     def __init__(self, w: Workload, device: str = "cuda:0", canary: Optional[float] = None,
                  like: Optional["ml.Plan"] = None, guards: bool = True):
@@ -45,9 +55,10 @@ class DeviceLayer:
         self.tdtype = torch.bfloat16 if w.dtype == "bf16" else torch.float32
         self.mdtype = ml.BF16 if w.dtype == "bf16" else ml.F32
         dev, dt = self.device, w.dtype
-        self.X, self.W, self.dY = to_device(w.X, dt, dev), to_device(w.W, dt, dev), to_device(w.dY, dt, dev)
-        self.A = [to_device(a, dt, dev) for a in w.A]
-        self.B = [to_device(b, dt, dev) for b in w.B]
+        ng = guards        # inputs sit between NaN regions, outputs between regions of a known value
+        self.X, self.W, self.dY = to_device(w.X, dt, dev, ng), to_device(w.W, dt, dev, ng), to_device(w.dY, dt, dev, ng)
+        self.A = [to_device(a, dt, dev, ng) for a in w.A]
+        self.B = [to_device(b, dt, dev, ng) for b in w.B]
         fill = float("nan") if canary is None else canary
         self._guarded = []
 
