@@ -312,6 +312,26 @@ def test_single_token_segments():
     check_full(w)
 
 
+def test_error_does_not_grow_with_the_contraction_length():
+    """fp32 accumulation and one rounding per output: the relative error of Y and dX is set by the bf16 rounding of the
+    result (about 2^-9 / sqrt(3) = 1.1e-3, plus the rounded S / dS inside the LoRA term), whatever the contraction
+    length; an accumulator narrower than fp32, or partial sums rounded on the way, would show as growth with k."""
+    errs = {}
+    for kk in (256, 1024, 4096, 16384):
+        w = wl.make_workload(f"k{kk}", "bf16", kk, 256, [16, 64], [200, 120], [1.0, 0.25], seed=66, b_sigma=0.3)
+        dl = DeviceLayer(w); dl.forward(); dl.backward(); dl.sync()
+        fw = orc.forward(w.X, w.W, w.A, w.B, w.scales, w.offsets)
+        errs[kk] = rel_fro(to_host(dl.Y), fw.Y)
+        w2 = wl.make_workload(f"n{kk}", "bf16", 256, kk, [16, 64], [200, 120], [1.0, 0.25], seed=67, b_sigma=0.3)
+        d2 = DeviceLayer(w2); d2.forward(); d2.backward(); d2.sync()
+        bw = orc.backward(w2.dY, w2.X, w2.W, w2.A, w2.B, w2.scales, w2.offsets)
+        errs[-kk] = rel_fro(to_host(d2.dX), bw.dX)
+        dl.plan.destroy(); d2.plan.destroy()
+    print("        relative error of Y by k and of dX by n:", {k: f"{v:.2e}" for k, v in errs.items()}, flush=True)
+    assert all(v <= 4e-3 for v in errs.values()), errs
+    assert errs[16384] <= 1.5 * errs[256] and errs[-16384] <= 1.5 * errs[-256], errs
+
+
 # ---- determinism and isolation ----------------------------------------------------------------------
 def test_repeat_runs_are_bit_identical_and_adapters_are_isolated():
     w = wl.small_case(seed=61, dtype="bf16", k=512, n=512, ranks=(8, 64, 16), seg_lens=(300, 1200, 77),

@@ -66,3 +66,30 @@ def test_static_workspace_backward_rejects_oversized_plans_and_bad_arguments():
     assert e.value.status == -7 and "static workspace" in str(e.value)
     plan.destroy()
     assert ml.lib().multi_lora_bwd_static(None, None, None, None, None, None, None, None, None, None, 0, None) == -1
+
+
+def test_static_workspace_backward_inside_a_captured_graph():
+    """The callers this entry point is for: a step captured into a HIP graph (no allocation, no workspace to carry).  The
+    replays must reproduce the eager result bit for bit, with eager work of the same plan in between."""
+    w = wl.small_case(seed=93, dtype="bf16", k=256, n=320, ranks=(8, 64, 100, 16), seg_lens=(300, 700, 77, 0),
+                      scales=(2.0, 0.25, 1.0, 3.0), b_sigma=0.3)
+    dl = DeviceLayer(w)
+    outs = lambda: [dl.Y, dl.dX, dl.S] + [t for t in dl.dA + dl.dB if t.numel()]
+    dl.forward(); dl.backward(); dl.sync()
+    ref = [t.clone() for t in outs()]
+    eager_stream = dl.stream
+    graph, side = torch.cuda.CUDAGraph(), torch.cuda.Stream()
+    with torch.cuda.graph(graph, stream=side):
+        st = torch.cuda.current_stream().cuda_stream
+        ml.multi_lora_fwd(dl.plan, dl.X, dl.W, dl.A, dl.B, dl.Y, dl.S, None, 0, st)
+        ml.multi_lora_bwd_static(dl.plan, dl.dY, dl.X, dl.W, dl.A, dl.B, dl.S, dl.dX, dl.dA, dl.dB, 0, st)
+    for rep in range(3):
+        for t in outs():
+            t.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, want in zip(outs(), ref):
+            assert torch.equal(got.view(torch.uint8), want.view(torch.uint8)), rep
+        dl.forward(ml.FLAG_BASE_ONLY); dl.backward(); dl.sync()      # eager work between the replays, caller's workspace
+    dl.plan.destroy()
