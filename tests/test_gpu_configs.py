@@ -100,3 +100,24 @@ def test_config_full_size_sampled(index):
     bad = {k: v for k, v in e2.items() if not v <= (2e-2 if k.startswith(("Y", "dX")) else 1e-2)}
     assert not bad, bad
     assert not torch.isnan(dl.Y).any() and not torch.isnan(dl.dX).any()
+
+
+@pytest.mark.parametrize("index", [2, 4])
+def test_config_full_size_repeat_runs_are_bit_identical(index):
+    """A property that holds at any size and needs no oracle: every reduction has a fixed order (no atomics), so two
+    steps on the same inputs give the same bits - at full size, where the weight gradients of config 3 go through
+    chunk partials and the fixed-order sum, and config 5 runs tens of thousands of work groups.  Any data race shows here."""
+    import torch
+    dtype, k, n, ranks, lens, scales, seed, _ = wl.config_shape(index)
+    print(f"[case] config {index + 1}: repeat-run determinism at full size", flush=True)
+    dl = DeviceLayer.synthetic(f"config{index + 1}", dtype, k, n, ranks, lens, scales, seed)
+    outs = lambda: [dl.Y, dl.dX, dl.S] + dl.dA + dl.dB
+    dl.forward(); dl.backward(); dl.sync()
+    first = [t.clone() for t in outs()]
+    for t in outs():
+        t.fill_(float("nan"))
+    dl.forward(); dl.backward(); dl.sync()
+    for a, b in zip(first, outs()):
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+    assert not any(bool(torch.isnan(t).any()) for t in outs())
+    dl.plan.destroy()

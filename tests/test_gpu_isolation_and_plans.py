@@ -120,3 +120,27 @@ def test_launches_per_step_do_not_depend_on_the_number_of_adapters(dtype):
         dl.plan.destroy()
     assert seen[8] == seen[32] == seen[100]
     assert len(seen[1]) <= len(seen[8])          # a single rank class launches one weight-gradient kernel fewer
+
+
+def test_adapter_permutation_moves_rows_and_leaves_every_bit_alone():
+    """Permuting the adapters (segments, ranks, scales, matrices together) permutes the rows of Y and dX and leaves every
+    dA_i, dB_i unchanged - bit for bit: a row's result does not depend on where in the flat buffer, in which tile or next
+    to which neighbours it sits.  (The oracle has the same property exactly; here it is the kernels' tiling that is on trial:
+    segments that are not multiples of any tile, three rank classes.)"""
+    ranks, lens, scales = [8, 100, 0, 33, 64], [300, 210, 70, 129, 515], [2.0, 0.25, 1.0, 0.5, 0.125]
+    w = wl.make_workload("perm_base", "bf16", 320, 264, ranks, lens, scales, seed=75, b_sigma=0.3)
+    perm = [3, 0, 4, 2, 1]
+    rows = np.concatenate([np.arange(w.offsets[i], w.offsets[i + 1]) for i in perm])
+    off = [0]
+    for i in perm:
+        off.append(off[-1] + lens[i])
+    wp = wl.Workload(name="perm", dtype="bf16", T=w.T, k=w.k, n=w.n, ranks=[ranks[i] for i in perm], scales=[scales[i] for i in perm],
+                     offsets=off, X=w.X[rows], W=w.W, A=[w.A[i] for i in perm], B=[w.B[i] for i in perm], dY=w.dY[rows])
+    a, b = DeviceLayer(w), DeviceLayer(wp)
+    for d in (a, b):
+        d.forward(); d.backward(); d.sync()
+    idx = torch.tensor(rows, device=a.Y.device)
+    assert torch.equal(_bits(a.Y[idx]), _bits(b.Y)) and torch.equal(_bits(a.dX[idx]), _bits(b.dX))
+    for j, i in enumerate(perm):
+        assert torch.equal(_bits(a.dA[i]), _bits(b.dA[j])) and torch.equal(_bits(a.dB[i]), _bits(b.dB[j])), (i, j)
+    a.plan.destroy(); b.plan.destroy()
