@@ -376,7 +376,46 @@ def cpu_oracle_baseline(w, np, budget_s: float):
                       f"whole fwd+bwd (Y, S, dS, dX, dA_i, dB_i), naive fp64 loops"}
 
 
-def measure_layer(config: int, args, mods, extras: bool, lora_and_base: bool, ceilings: bool, cpu_budget_s: float) -> dict:
+class PowerClockSampler:
+    """Samples socket power and the mean shader clock of the XCDs with amd-smi from a side thread (about ten samples a
+    second) while the main thread keeps the GPU busy.  Missing tool or unparsable output: no samples, fields stay None."""
+
+    def __init__(self, np):
+        import threading
+        self.np, self.samples, self._stop = np, [], threading.Event()
+        self._thread = threading.Thread(target=self._run, daemon=True)
+
+    def _run(self):
+        import re
+        import subprocess
+        while not self._stop.is_set():
+            try:
+                txt = subprocess.run(["amd-smi", "metric", "-p", "-c"], capture_output=True, text=True, timeout=20).stdout
+            except Exception:
+                return
+            m = re.search(r"SOCKET_POWER: ([0-9.]+) W", txt)
+            clks = [float(x) for x in re.findall(r"GFX_\d+:\s+CLK: ([0-9.]+) MHz", txt)]
+            if m and clks:
+                self.samples.append((float(m.group(1)), float(self.np.mean(clks))))
+
+    def __enter__(self):
+        self._thread.start()
+        return self
+
+    def __exit__(self, *exc):
+        self._stop.set()
+        self._thread.join()
+
+    def summary(self):
+        if not self.samples:
+            return {"samples": 0, "socket_power_w_mean": None, "shader_clock_mhz_mean": None}
+        pw, ck = [x[0] for x in self.samples], [x[1] for x in self.samples]
+        return {"samples": len(pw), "socket_power_w_mean": float(self.np.mean(pw)), "socket_power_w_max": float(max(pw)),
+                "shader_clock_mhz_mean": float(self.np.mean(ck)), "shader_clock_over_nominal_2400": float(self.np.mean(ck)) / 2400.0}
+
+
+def measure_layer(config: int, args, mods, extras: bool, lora_and_base: bool, ceilings: bool, cpu_budget_s: float,
+                  power: bool = False) -> dict:
     """Everything bench.py reports for one benchmark config (1-based): the timed fused step, per-kernel times and
     roofline fractions, the LoRA-only path against the HBM roofline, the frozen-weight GEMMs alone, the CPU oracle."""
     np, torch, ml, wl, DeviceLayer = mods
@@ -481,6 +520,17 @@ def measure_layer(config: int, args, mods, extras: bool, lora_and_base: bool, ce
                                "avg_kernel_ms": kern[dom]["avg_ms"]}
         if traffic:
             out["traffic_per_launch_bytes"] = traffic
+
+    if power:
+        # socket power and shader clock while the fused step runs back to back for about two seconds (the published MFMA
+        # peak assumes 2400 MHz; under this step the board sits at its power limit and clocks lower)
+        with PowerClockSampler(np) as smp:
+            t_end = time.perf_counter() + 2.0
+            while time.perf_counter() < t_end:
+                for _ in range(4):
+                    step()
+                torch.cuda.synchronize()
+        out["power_clock_under_fused_step"] = smp.summary()
 
     if extras and lora_and_base:
         # LoRA grouped path alone (W skipped; Y and dX updated in place) against the HBM roofline
@@ -619,7 +669,7 @@ def main() -> int:
     extras = not args.no_extra
     full = extras and not args.fused_only
     h = measure_layer(head_cfg, args, mods, extras=extras, lora_and_base=full, ceilings=full,
-                      cpu_budget_s=0.0 if args.no_cpu else 12.0)
+                      cpu_budget_s=0.0 if args.no_cpu else 12.0, power=full)
     out = {
         "metric": "multi-LoRA layer fwd+bwd tokens/s", "value": h["value"], "unit": "tokens/s",
         "n_gpus": 1, "steps": h["steps"], "warmup": h["warmup"], "warmup_clock_settle_steps": h["warmup_clock_settle_steps"],
@@ -629,7 +679,8 @@ def main() -> int:
                    "ranks": h["ranks"], "tokens_per_adapter": h["tokens_per_adapter"], "mode": h["mode"]},
     }
     for key in ("tflops", "frac_bf16_mfma_peak_whole_step", "kernels", "roofline", "traffic_per_launch_bytes", "lora_path",
-                "decoupled", "base_only", "measured_ceilings", "calib_copy_bytes", "cpu_baseline", "host_input_generation_s"):
+                "decoupled", "base_only", "measured_ceilings", "power_clock_under_fused_step", "calib_copy_bytes", "cpu_baseline",
+                "host_input_generation_s"):
         if key in h:
             out[key] = h[key]
     if args.config is None and not args.no_configs:
