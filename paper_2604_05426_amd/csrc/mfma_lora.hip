@@ -691,7 +691,7 @@ __global__ void wgrad_zero_empty_kernel(PlanView pv) {
 // Expand-add (MLORA_FLAG_LORA_ONLY; the paper's decoupled "fused GEMM-add", Sec. 5.1 / App. A.1):
 //   fwd  Y_i  += s_i S_i B_i        bwd  dX_i += dS_i A_i^T        in place, one rounding.
 // A pure read-modify-write stream of the output with a small contraction on top.  Work item = (64-row block of
-// one adapter, 128 columns); 4 wavefronts (2 x 2), each 32 rows x 64 columns = 2 x 4 blocks of 16x16x32 MFMAs.
+// one adapter, 128 or 256 columns); 4 or 8 wavefronts (2 x 2 / 2 x 4), each 32 rows x 64 columns = 2 x 4 blocks of 16x16x32 MFMAs.
 // The old output tile is not added after the fact: it is loaded in 16-byte row chunks, which is exactly the MFMA
 // operand layout of a [row][32 columns] fragment, and multiplied by a constant identity operand into the fp32
 // accumulators (bf16 x 1.0 is exact), so the accumulators start as the old tile and the rank steps add on top.
@@ -701,7 +701,6 @@ __global__ void wgrad_zero_empty_kernel(PlanView pv) {
 // (256-byte rows, 16-byte chunk c of row k at c ^ (nn_swz(k) << 1)) and reads it with the transposing load;
 // bwd: A_i is [k][r], contraction contiguous: the work group stages its 128 rows in LDS (padded pitch) and reads plain fragments.
 // =========================================================================================
-constexpr int XC = 128;               // output columns per work item
 constexpr int XE_LD = 64 + 8;         // epilogue staging row of one wavefront (elements)
 
 struct ExpandArgs {
@@ -717,14 +716,21 @@ struct ExpandArgs {
 // MAXKS: 32-wide rank steps the kernel is built for (2: every rank <= 64, 4: ranks up to 128).
 // All loads of a work item (old output tile, S fragments, B_i / A_i^T operands) are issued before the
 // first MFMA, so a wavefront pays the memory latency once; many small work items per CU overlap each other.
-template <bool FWD, int MAXKS>
-__global__ __launch_bounds__(256) void expand_add_kernel(ExpandArgs g) {
+// XCW: 64-column wavefront columns of a work item (2: 128 output columns, 4 wavefronts; 4: 256 columns, 8 wavefronts - every
+// work item fetches its 64 rows of S_i / dS_i again, so a strip twice as wide halves that traffic; used for the narrow rank class,
+// whose adapter tile stays small enough for two work groups per CU: expand-add of configs 3-5 4-6 % faster; the wide class with
+// 256 columns fits one work group per CU and is 10-20 % slower).
+template <bool FWD, int MAXKS, int XCW>
+__global__ __launch_bounds__(128 * XCW) void expand_add_kernel(ExpandArgs g) {
+    constexpr int XC = 64 * XCW;                                 // output columns per work item
+    constexpr int NTH = 128 * XCW;                               // threads
+    constexpr int BROW = XC * 2;                                 // fwd: bytes per rank row of the staged B_i tile
     constexpr int AT_PITCH = MAXKS * 64 + 16;                    // bwd: bytes per column of the staged A_i rows (padded: bank spread)
-    constexpr int BT_BYTES = FWD ? MAXKS * 32 * 256 : XC * AT_PITCH;   // staged B_i tile / A_i rows
+    constexpr int BT_BYTES = FWD ? MAXKS * 32 * BROW : XC * AT_PITCH;   // staged B_i tile / A_i rows
     constexpr int EP_WAVE = 32 * XE_LD * 2;                      // bytes of epilogue staging per wavefront
-    __shared__ __attribute__((aligned(16))) unsigned char lds[BT_BYTES + 4 * EP_WAVE];
+    __shared__ __attribute__((aligned(16))) unsigned char lds[BT_BYTES + 2 * XCW * EP_WAVE];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wr = wave >> 1, wc = wave & 1;
+    const int wr = wave / XCW, wc = wave % XCW;
     const int l16 = lane & 15, g4 = lane >> 4;
     // row-block-major: consecutive workgroups cover adjacent column tiles of the same 64 rows
     constexpr int PARTS = (MAXKS == 4 ? kBlockRowsWide : kBlockRows) / 64;   // 64-row work items per block of this class's table
@@ -772,14 +778,14 @@ __global__ __launch_bounds__(256) void expand_add_kernel(ExpandArgs g) {
         uint4 st[2 * MAXKS];
 #pragma unroll
         for (int jj = 0; jj < 2 * MAXKS; ++jj) {
-            const int idx = tid + 256 * jj, kr = idx >> 4, c = idx & 15;
+            const int idx = tid + NTH * jj, kr = idx / (XC / 8), c = idx % (XC / 8);
             const int col = ct * XC + c * 8;
             st[jj] = (kr < r && col < g.Ncols) ? *reinterpret_cast<const uint4*>(F + (int64_t)kr * g.Ncols + col) : zero4();
         }
 #pragma unroll
         for (int jj = 0; jj < 2 * MAXKS; ++jj) {
-            const int idx = tid + 256 * jj, kr = idx >> 4, c = idx & 15;
-            if (kr < ksteps * 32) *reinterpret_cast<uint4*>(lds + kr * 256 + ((c ^ (nn_swz(kr) << 1)) << 4)) = st[jj];
+            const int idx = tid + NTH * jj, kr = idx / (XC / 8), c = idx % (XC / 8);
+            if (kr < ksteps * 32) *reinterpret_cast<uint4*>(lds + kr * BROW + ((c ^ (nn_swz(kr) << 1)) << 4)) = st[jj];
         }
         __syncthreads();
         const int vq = ((l16 >> 2) & 3) | ((g4 & 1) << 2);   // nn_swz of the rows this lane reads
@@ -789,9 +795,9 @@ __global__ __launch_bounds__(256) void expand_add_kernel(ExpandArgs g) {
             for (int cb = 0; cb < 4; ++cb) {
                 fv[cb][ks] = zero4();
                 if (ks < ksteps) {
-                    const unsigned char* p = lds + (ks * 32 + 8 * g4 + (l16 >> 2)) * 256 + (((wc * 4 + cb) ^ vq) << 5) + (l16 & 3) * 8;
+                    const unsigned char* p = lds + (ks * 32 + 8 * g4 + (l16 >> 2)) * BROW + (((wc * 4 + cb) ^ vq) << 5) + (l16 & 3) * 8;
                     fv[cb][ks] = __builtin_bit_cast(uint4, lds_read_frag_tr(reinterpret_cast<const u16*>(p),
-                                                                            reinterpret_cast<const u16*>(p + 4 * 256)));
+                                                                            reinterpret_cast<const u16*>(p + 4 * BROW)));
                 }
             }
     } else {
@@ -803,14 +809,14 @@ __global__ __launch_bounds__(256) void expand_add_kernel(ExpandArgs g) {
         uint4 st[2 * MAXKS];
 #pragma unroll
         for (int jj = 0; jj < 2 * MAXKS; ++jj) {
-            const int idx = tid + 256 * jj, c = idx / CPR, cc = idx % CPR;
+            const int idx = tid + NTH * jj, c = idx / CPR, cc = idx % CPR;
             const int col = ct * XC + c;
             st[jj] = zero4();
             if (col < g.Ncols && cc * 8 < r) st[jj] = load_chunk_a8(F + (int64_t)col * r + cc * 8, min(8, r - cc * 8), f_vec);
         }
 #pragma unroll
         for (int jj = 0; jj < 2 * MAXKS; ++jj) {
-            const int idx = tid + 256 * jj, c = idx / CPR, cc = idx % CPR;
+            const int idx = tid + NTH * jj, c = idx / CPR, cc = idx % CPR;
             if (cc < ksteps * 4) *reinterpret_cast<uint4*>(lds + c * AT_PITCH + cc * 16) = st[jj];
         }
         __syncthreads();
@@ -890,7 +896,6 @@ static int launch_expand(mlora_plan* p, bool fwd, void* C, const void* E, hipStr
     a.C = (u16*)C; a.E = (const u16*)E; a.pv = p->view;
     a.Ncols = (int32_t)(fwd ? p->n : p->k);
     a.ldc = a.Ncols;
-    a.col_tiles = (a.Ncols + XC - 1) / XC;
     a.stream_out = 1;
     // An output that is larger than the Infinity Cache (256 MB) cannot stay there until anybody reads it again: its old
     // tile is then loaded with the non-temporal hint as well, so that it does not evict X / dY, which the next kernels
@@ -902,11 +907,13 @@ static int launch_expand(mlora_plan* p, bool fwd, void* C, const void* E, hipStr
         if (nblocks <= 0) return;
         a.blocks = blocks;
         const int parts = (narrow ? kBlockRows : kBlockRowsWide) / 64;     // 64-row work items per block of the class table
-        const dim3 grid((unsigned)((int64_t)nblocks * parts * a.col_tiles));
-        if (fwd && narrow)      hipLaunchKernelGGL((expand_add_kernel<true, 2>), grid, dim3(256), 0, st, a);
-        else if (fwd)           hipLaunchKernelGGL((expand_add_kernel<true, 4>), grid, dim3(256), 0, st, a);
-        else if (narrow)        hipLaunchKernelGGL((expand_add_kernel<false, 2>), grid, dim3(256), 0, st, a);
-        else                    hipLaunchKernelGGL((expand_add_kernel<false, 4>), grid, dim3(256), 0, st, a);
+        const int xcw = narrow ? 4 : 2;                                    // narrow class: 256-column strips, 8 wavefronts
+        a.col_tiles = (a.Ncols + 64 * xcw - 1) / (64 * xcw);
+        const dim3 grid((unsigned)((int64_t)nblocks * parts * a.col_tiles)), block(128 * xcw);
+        if (fwd && narrow)      hipLaunchKernelGGL((expand_add_kernel<true, 2, 4>), grid, block, 0, st, a);
+        else if (fwd)           hipLaunchKernelGGL((expand_add_kernel<true, 4, 2>), grid, block, 0, st, a);
+        else if (narrow)        hipLaunchKernelGGL((expand_add_kernel<false, 2, 4>), grid, block, 0, st, a);
+        else                    hipLaunchKernelGGL((expand_add_kernel<false, 4, 2>), grid, block, 0, st, a);
     };
     // each rank class through the build made for it (the class table holds the wide class first)
     go(false, p->n_blocks_wide, p->view.class_blocks);
