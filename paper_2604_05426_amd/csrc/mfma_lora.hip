@@ -728,7 +728,12 @@ __global__ __launch_bounds__(128 * XCW) void expand_add_kernel(ExpandArgs g) {
     constexpr int AT_PITCH = MAXKS * 64 + 16;                    // bwd: bytes per column of the staged A_i rows (padded: bank spread)
     constexpr int BT_BYTES = FWD ? MAXKS * 32 * BROW : XC * AT_PITCH;   // staged B_i tile / A_i rows
     constexpr int EP_WAVE = 32 * XE_LD * 2;                      // bytes of epilogue staging per wavefront
-    __shared__ __attribute__((aligned(16))) unsigned char lds[BT_BYTES + 2 * XCW * EP_WAVE];
+    // 256-column forward strips stage the work item's 64 rows of S_i in LDS once (one 16-byte load per thread) instead of every
+    // wavefront fetching the fragments of its rows itself (four wavefronts share each row)
+    constexpr bool SLDS = FWD && XCW == 4;
+    constexpr int ST_PITCH = MAXKS * 64 + 16;                    // bytes per staged row of S_i (padded: bank spread)
+    constexpr int ST_BYTES = SLDS ? 64 * ST_PITCH : 0;
+    __shared__ __attribute__((aligned(16))) unsigned char lds[BT_BYTES + ST_BYTES + 2 * XCW * EP_WAVE];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wr = wave / XCW, wc = wave % XCW;
     const int l16 = lane & 15, g4 = lane >> 4;
@@ -762,15 +767,27 @@ __global__ __launch_bounds__(128 * XCW) void expand_add_kernel(ExpandArgs g) {
     // 2. S / dS fragments: [16 rows][32 ranks]
     const bool e_vec = ((r & 7) == 0) && ((so & 7) == 0);
     uint4 sv[2][MAXKS];
+    constexpr int SCH = (64 * MAXKS * 4) / NTH;          // staged S chunks per thread
+    uint4 sst[SCH > 0 ? SCH : 1];
+    if (SLDS) {
 #pragma unroll
-    for (int ks = 0; ks < MAXKS; ++ks)
-#pragma unroll
-        for (int rb = 0; rb < 2; ++rb) {
-            const int row = wr * 32 + rb * 16 + l16, rho = ks * 32 + g4 * 8;
-            sv[rb][ks] = zero4();
-            if (ks < ksteps && row < rows && rho < r)
-                sv[rb][ks] = load_chunk_a8(g.E + so + (int64_t)(row0 + row - seg0) * r + rho, min(8, r - rho), e_vec);
+        for (int jj = 0; jj < SCH; ++jj) {
+            const int idx = tid + NTH * jj, row = idx / (MAXKS * 4), cc = idx % (MAXKS * 4);
+            sst[jj] = zero4();
+            if (row < rows && cc * 8 < r)
+                sst[jj] = load_chunk_a8(g.E + so + (int64_t)(row0 + row - seg0) * r + cc * 8, min(8, r - cc * 8), e_vec);
         }
+    } else {
+#pragma unroll
+        for (int ks = 0; ks < MAXKS; ++ks)
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb) {
+                const int row = wr * 32 + rb * 16 + l16, rho = ks * 32 + g4 * 8;
+                sv[rb][ks] = zero4();
+                if (ks < ksteps && row < rows && rho < r)
+                    sv[rb][ks] = load_chunk_a8(g.E + so + (int64_t)(row0 + row - seg0) * r + rho, min(8, r - rho), e_vec);
+            }
+    }
     // 3. the adapter matrix: fragments [16 columns][32 ranks], lane = (column l16, 8 ranks at 8 g4)
     uint4 fv[4][MAXKS];
     if (FWD) {
@@ -787,7 +804,24 @@ __global__ __launch_bounds__(128 * XCW) void expand_add_kernel(ExpandArgs g) {
             const int idx = tid + NTH * jj, kr = idx / (XC / 8), c = idx % (XC / 8);
             if (kr < ksteps * 32) *reinterpret_cast<uint4*>(lds + kr * BROW + ((c ^ (nn_swz(kr) << 1)) << 4)) = st[jj];
         }
+        if (SLDS) {
+#pragma unroll
+            for (int jj = 0; jj < SCH; ++jj) {
+                const int idx = tid + NTH * jj, row = idx / (MAXKS * 4), cc = idx % (MAXKS * 4);
+                *reinterpret_cast<uint4*>(lds + BT_BYTES + row * ST_PITCH + cc * 16) = sst[jj];
+            }
+        }
         __syncthreads();
+        if (SLDS) {
+#pragma unroll
+            for (int ks = 0; ks < MAXKS; ++ks)
+#pragma unroll
+                for (int rb = 0; rb < 2; ++rb) {
+                    sv[rb][ks] = zero4();
+                    if (ks < ksteps)
+                        sv[rb][ks] = *reinterpret_cast<const uint4*>(lds + BT_BYTES + (wr * 32 + rb * 16 + l16) * ST_PITCH + (ks * 32 + g4 * 8) * 2);
+                }
+        }
         const int vq = ((l16 >> 2) & 3) | ((g4 & 1) << 2);   // nn_swz of the rows this lane reads
 #pragma unroll
         for (int ks = 0; ks < MAXKS; ++ks)
@@ -862,7 +896,7 @@ __global__ __launch_bounds__(128 * XCW) void expand_add_kernel(ExpandArgs g) {
     }
 
     // epilogue: one rounding, transpose through this wavefront's private LDS, 128-byte row segments
-    u16* Es = reinterpret_cast<u16*>(lds + BT_BYTES + wave * EP_WAVE);
+    u16* Es = reinterpret_cast<u16*>(lds + BT_BYTES + ST_BYTES + wave * EP_WAVE);
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
