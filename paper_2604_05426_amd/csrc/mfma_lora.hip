@@ -446,8 +446,13 @@ struct WgradArgs {
 
 // One work item; isA: a dA_i item (panel of X against dS_i), else a dB_i item (panel of dY against S_i).  The two forms
 // are separate instantiations (the kernel branches once, uniformly): they use the MFMA operands the other way round.
-template <int MAXNB, bool isA>
+// NW: wavefronts per work group: 4, or 8 for the wide build (64 columns x 32 ranks per wavefront: half the accumulators and half
+// the prefetch registers per wavefront, 128 registers instead of 240, so twice the wavefronts per CU hide the latency of the
+// same two work groups' loads; weight gradients of 4 x 2048 tokens at rank 128, 8192 + 28672 wide: 190 -> 173 us)
+template <int MAXNB, bool isA, int NW = 4>
 __device__ __forceinline__ void wgrad_body(const WgradArgs& g, u16* lds, const int ce, const int panel) {
+    constexpr int NTHW = 64 * NW;
+    static_assert(NW == 4 || (NW == 8 && MAXNB == 4), "8 wavefronts: wide build only");
     constexpr int SW = MAXNB * 32;                 // S / dS tile width (elements)
     constexpr int CPRS = SW / 8;                   // 16-byte chunks per S tile row
     constexpr int W_STAGE = WX_TILE + WT * SW;     // elements per stage
@@ -476,12 +481,13 @@ __device__ __forceinline__ void wgrad_body(const WgradArgs& g, u16* lds, const i
     const bool s_v8 = !s_vec && ((r & 3) == 0) && ((so & 3) == 0) && ((reinterpret_cast<uintptr_t>(isA ? g.dS : g.S) & 7) == 0);
 
     // Accumulator blocks of a wavefront: NCB 32-column blocks x NRB 32-rank blocks.  Up to 64 ranks every wavefront takes
-    // 32 panel columns against all ranks; the widest build splits the work group 2 x 2 (64 columns x 64 ranks per wavefront),
+    // 32 panel columns against all ranks; the widest build splits the work group 2 x 4 (64 columns x 32 ranks per wavefront;
+    // with four wavefronts it was 2 x 2 with 64 x 64 each),
     // which reads a fifth less from LDS for the same MFMAs - that build is bound by LDS bandwidth.
     constexpr int NCB = MAXNB == 4 ? 2 : 1;
-    constexpr int NRB = MAXNB == 4 ? 2 : MAXNB;
+    constexpr int NRB = MAXNB == 4 ? (NW == 8 ? 1 : 2) : MAXNB;
     const int cwave = MAXNB == 4 ? (wave & 1) * 64 : wave * 32;      // first panel column of this wavefront
-    const int rb0 = MAXNB == 4 ? (wave >> 1) * 2 : 0;                // its first rank block
+    const int rb0 = MAXNB == 4 ? (wave >> 1) * NRB : 0;              // its first rank block
     f32x16 acc[NCB * NRB];
 #pragma unroll
     for (int nb = 0; nb < NCB * NRB; ++nb)
@@ -489,19 +495,20 @@ __device__ __forceinline__ void wgrad_body(const WgradArgs& g, u16* lds, const i
         for (int q = 0; q < 16; ++q) acc[nb][q] = 0.f;
 
     const int nt = (rows + WT - 1) / WT;
-    uint4 ra[2][4], rb[2][MAXNB];   // two register sets: tiles of even / odd index, two steps of loads in flight
+    constexpr int NRA = 1024 / NTHW, NRS = MAXNB * 256 / NTHW;      // 16-byte chunks per thread: panel tile, S tile
+    uint4 ra[2][NRA], rb[2][NRS];   // two register sets: tiles of even / odd index, two steps of loads in flight
     auto gload = [&](int tt, int set) {
         const int t0 = tt * WT;
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
-            const int trow = (tid >> 4) + 16 * jj, cc = tid & 15;
+        for (int jj = 0; jj < NRA; ++jj) {
+            const int trow = (tid >> 4) + (NTHW / 16) * jj, cc = tid & 15;
             const int col = col0 + cc * 8;
             ra[set][jj] = (t0 + trow < rows && col < width)
                               ? load_streaming(big + (int64_t)(row0 + t0 + trow) * width + col) : zero4();
         }
 #pragma unroll
-        for (int jj = 0; jj < MAXNB; ++jj) {
-            const int idx = tid + 256 * jj, trow = idx / CPRS, cc = idx % CPRS;
+        for (int jj = 0; jj < NRS; ++jj) {
+            const int idx = tid + NTHW * jj, trow = idx / CPRS, cc = idx % CPRS;
             rb[set][jj] = zero4();
             if (t0 + trow < rows && cc * 8 < r) {
                 const u16* ps = small + (int64_t)(t0 + trow) * r + cc * 8;
@@ -522,13 +529,13 @@ __device__ __forceinline__ void wgrad_body(const WgradArgs& g, u16* lds, const i
         unsigned char* Xs = reinterpret_cast<unsigned char*>(lds + stage * W_STAGE);
         unsigned char* Ss = Xs + WX_TILE * 2;
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
-            const int trow = (tid >> 4) + 16 * jj, cc = tid & 15;
+        for (int jj = 0; jj < NRA; ++jj) {
+            const int trow = (tid >> 4) + (NTHW / 16) * jj, cc = tid & 15;
             *reinterpret_cast<uint4*>(Xs + x_off(trow, cc * 8)) = ra[set][jj];
         }
 #pragma unroll
-        for (int jj = 0; jj < MAXNB; ++jj) {
-            const int idx = tid + 256 * jj, trow = idx / CPRS, cc = idx % CPRS;
+        for (int jj = 0; jj < NRS; ++jj) {
+            const int idx = tid + NTHW * jj, trow = idx / CPRS, cc = idx % CPRS;
             *reinterpret_cast<uint4*>(Ss + s_off(trow, cc * 8)) = rb[set][jj];
         }
     };
@@ -637,15 +644,15 @@ __device__ __forceinline__ void wgrad_body(const WgradArgs& g, u16* lds, const i
 }
 
 // (the register budget is stated per build: the work groups per CU that its LDS footprint allows, one wavefront of each per SIMD)
-template <int MAXNB>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(MAXNB == 4 ? 2 : MAXNB == 2 ? 3 : 4)))
+template <int MAXNB, int NW = 4>
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(NW == 8 ? 4 : MAXNB == 4 ? 2 : MAXNB == 2 ? 3 : 4)))
 void wgrad_kernel(WgradArgs g) {
     __shared__ __attribute__((aligned(16))) u16 lds[2 * (WX_TILE + WT * MAXNB * 32)];
     const int panels = g.panels_k + g.panels_n;
     const int ce = g.chunk_base + blockIdx.x / panels;
     const int panel = blockIdx.x % panels;
-    if (panel < g.panels_k) wgrad_body<MAXNB, true>(g, lds, ce, panel);
-    else wgrad_body<MAXNB, false>(g, lds, ce, panel - g.panels_k);
+    if (panel < g.panels_k) wgrad_body<MAXNB, true, NW>(g, lds, ce, panel);
+    else wgrad_body<MAXNB, false, NW>(g, lds, ce, panel - g.panels_k);
 }
 
 // Adds the chunk partials of one adapter in chunk order and rounds once.  blockIdx.y walks the adapters that have
@@ -1001,7 +1008,7 @@ int mfma_backward(mlora_plan* p, const void* dY, const void* X, const void* W, c
                 const int32_t n_wide = geo.n_chunks_wide, n_narrow = geo.n_chunks - geo.n_chunks_wide;
                 if (n_wide > 0) {
                     w.chunk_base = 0;
-                    hipLaunchKernelGGL(wgrad_kernel<4>, dim3((unsigned)(n_wide * panels)), dim3(256), 0, st, w);
+                    hipLaunchKernelGGL((wgrad_kernel<4, 8>), dim3((unsigned)(n_wide * panels)), dim3(512), 0, st, w);
                 }
                 if (n_narrow > 0) {
                     w.chunk_base = n_wide;
