@@ -70,6 +70,10 @@ typedef enum {
                                    overwritten (gradient accumulation over micro-batches; the paper's runs use 1
                                    accumulation step).  The sum is formed in fp32 from the stored value and the
                                    fp32 result and rounded once to the plan dtype.  dX is not affected. */
+#define MLORA_FLAG_GROUP_BANDS 8u /* bf16 tile order only, results unchanged bit for bit: sweep the frozen weight once
+                                   per group of four 2048-row bands instead of once per band.  The library does this by
+                                   itself when W is larger than half the Infinity Cache and the bands' rows fit the other
+                                   half; the flag forces it for any shape (tuning, tests).  Ignored by the fp32 path. */
 
 /* which table multi_lora_plan_dump copies out */
 typedef enum {

@@ -12,7 +12,7 @@ import os
 from typing import List, Optional, Sequence
 
 F32, BF16 = 0, 1
-FLAG_BASE_ONLY, FLAG_LORA_ONLY, FLAG_ACCUM_GRADS = 1, 2, 4
+FLAG_BASE_ONLY, FLAG_LORA_ONLY, FLAG_ACCUM_GRADS, FLAG_GROUP_BANDS = 1, 2, 4, 8
 TABLE_ROW_BLOCKS, TABLE_GEMM_ROW_TILES, TABLE_WGRAD_CHUNKS, TABLE_CLASS_BLOCKS, TABLE_GEMM_BAND_ORDER = 0, 1, 2, 3, 4
 GEO_BLOCK_ROWS, GEO_GEMM_TILE_ROWS, GEO_GEMM_TILE_COLS, GEO_WGRAD_CHUNK_ROWS = 0, 1, 2, 3
 GEO_R1_LO, GEO_R1_HI, GEO_USES_MFMA, GEO_WGRAD_CHUNK_ROWS_WIDE = 4, 5, 6, 7

@@ -50,7 +50,7 @@ void prepare_static_workspace() {
 static inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
 static int check_flags(uint32_t flags, bool backward) {
-    if (flags & ~(MLORA_FLAG_BASE_ONLY | MLORA_FLAG_LORA_ONLY | (backward ? MLORA_FLAG_ACCUM_GRADS : 0u))) {
+    if (flags & ~(MLORA_FLAG_BASE_ONLY | MLORA_FLAG_LORA_ONLY | MLORA_FLAG_GROUP_BANDS | (backward ? MLORA_FLAG_ACCUM_GRADS : 0u))) {
         set_error("unknown flag bits");
         return MLORA_ERR_FLAGS;
     }

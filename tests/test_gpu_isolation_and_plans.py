@@ -144,3 +144,31 @@ def test_adapter_permutation_moves_rows_and_leaves_every_bit_alone():
     for j, i in enumerate(perm):
         assert torch.equal(_bits(a.dA[i]), _bits(b.dA[j])) and torch.equal(_bits(a.dB[i]), _bits(b.dB[j])), (i, j)
     a.plan.destroy(); b.plan.destroy()
+
+
+@pytest.mark.parametrize("k,n,total", [(384, 1544, 10540), (1024, 520, 8192 + 77)])
+def test_grouped_row_bands_change_the_tile_order_and_no_bit(k, n, total):
+    """MLORA_FLAG_GROUP_BANDS (what the library does by itself for weights larger than half the Infinity Cache) interleaves
+    four 2048-row bands by groups of four column tiles.  The shapes put every branch of that numbering on trial: five full
+    bands and a short one (one group of four and a single band behind it), column counts that are not multiples of four tiles
+    (one whole group plus three tiles, one of them ragged; fewer than four tiles: no whole group at all), exactly four bands
+    and a 77-row one.  Every tile must be computed exactly once: same bits as the ungrouped order, which the parity tests
+    hold against the oracle, and the sampled rows are held against the oracle here as well."""
+    lens = [1500, 2300, 700, total - 1500 - 2300 - 700 - 1300, 1300]
+    ranks, scales = [16, 128, 0, 40, 64], [2.0, 0.25, 1.0, 0.5, 1.0]
+    w = wl.make_workload("bands", "bf16", k, n, ranks, lens, scales, seed=91, b_sigma=0.3)
+    print(f"[case] grouped bands k={k} n={n} T={w.T}", flush=True)
+    dl = DeviceLayer(w)
+    dl.forward(); dl.backward(); dl.sync()
+    plain = [t.clone() for t in (dl.Y, dl.dX, *dl.dA, *dl.dB)]
+    dl.Y.fill_(-3.0); dl.dX.fill_(-3.0)
+    dl.forward(ml.FLAG_GROUP_BANDS); dl.backward(ml.FLAG_GROUP_BANDS); dl.sync()
+    for a, b in zip(plain, (dl.Y, dl.dX, *dl.dA, *dl.dB)):
+        assert torch.equal(_bits(a), _bits(b))
+    rows = np.unique(np.concatenate([np.arange(0, w.T, 251), np.arange(w.T - 40, w.T), [2047, 2048, 8191, 8192]]))
+    rows = rows[rows < w.T]
+    fw = orc.forward(w.X, w.W, w.A, w.B, w.scales, w.offsets, rows=rows)
+    bw = orc.backward(w.dY, w.X, w.W, w.A, w.B, w.scales, w.offsets, S=fw.S, rows=rows)
+    assert rel_fro(to_host(dl.Y[rows.tolist()]), fw.Y) < 1e-2 and row_rel_max(to_host(dl.Y[rows.tolist()]), fw.Y) <= 1e-2
+    assert rel_fro(to_host(dl.dX[rows.tolist()]), bw.dX) < 1e-2 and row_rel_max(to_host(dl.dX[rows.tolist()]), bw.dX) <= 1e-2
+    dl.plan.destroy()
