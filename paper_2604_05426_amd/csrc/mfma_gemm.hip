@@ -329,6 +329,12 @@ __global__ __launch_bounds__(NTHR) void fused_gemm_kernel(GemmArgs g) {
             mma8(1, 1, 0, 2); __builtin_amdgcn_sched_barrier(0);
             dmaB(bp, 2);
             __builtin_amdgcn_sched_barrier(0);
+            // Last quarter before the barrier: this wavefront steps back behind the one it shares the SIMD with.  The two run
+            // the same instruction stream and the issue arbiter prefers the older one, so one of them used to reach the barrier
+            // half a tile early and the other finished alone, with nobody to fill the gaps behind its own LDS reads and load
+            // issue.  With the priority dropped here the one that is behind gets the matrix pipe first and both arrive
+            // together (backward GEMM 1.7-2 % faster, forward unchanged).
+            __builtin_amdgcn_s_setprio(0);
             rfa(cur, 1, 1, 1); mma8(0, 0, 1, 0); interleave(4);
             dmaB(bp, 3); baseB += (kt + 3 < nk) ? bstep : 0;
             __builtin_amdgcn_sched_barrier(0);
@@ -337,6 +343,7 @@ __global__ __launch_bounds__(NTHR) void fused_gemm_kernel(GemmArgs g) {
             // complete (this wavefront's share; the barrier covers the rest), and every wavefront has finished reading
             // row stage cur and weight slot bs, which the next loads overwrite.
             asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+            __builtin_amdgcn_s_setprio(3);
             dmaA(cur, 0);
             __builtin_amdgcn_sched_barrier(0);
             rfa(cur ^ 1, 0, 0, 0); rfb(bn, 0, 0); mma8(1, 1, 1, 0); interleave(4 + NDSB);
