@@ -2,9 +2,9 @@
 //
 // Forward (paper Sec. 5.1 / App. A.1, "fused base-output addition"): the paper runs the
 // base GEMM, then a second GEMM Y = S_i B_i + Y_base that reloads the base tile.  Here the
-// expand is folded into the base GEMM itself: after the contraction over k, the same
-// accumulators take a few more MFMA steps over the rank dimension with operands
-// s_i S_i (rows of the tile that belong to adapter i, zero elsewhere) and B_i, so Y is
+// expand is folded into the base GEMM itself: ahead of the contraction over k, the same
+// accumulators take a few MFMA steps over the rank dimension with operands S_i (rows of
+// the tile that belong to adapter i, zero elsewhere) and B_i, and are scaled by s_i, so Y is
 // written exactly once and Y_base never exists in memory.  Row tiles are not aligned to
 // segments; a tile that straddles several adapters runs one masked extension per adapter.
 // Backward input gradient is the mirror image: dX = dY W^T, extended with dS_i and A_i^T.
@@ -72,7 +72,6 @@ struct PassDesc {
     const u16* a_src; int64_t a_ld;   // element (row t, c) at a_src[(t - a_row_base) * a_ld + c]
     int a_row_base, a_row_lo, a_row_hi;
     bool a_vec;
-    float scale;
     const u16* b_src; int64_t b_ld;   // NN: (c, col) at b_src[c * b_ld + col];  NT: at b_src[col * b_ld + c]
     bool b_vec;
     int kc;                            // valid contraction length, 1..64
@@ -115,10 +114,7 @@ __device__ __forceinline__ void stage_pass(unsigned char* lds, const PassDesc& d
         const u16* src = d.a_src + (int64_t)(t - d.a_row_base) * d.a_ld;
         for (int cc = tid >> 8; cc < nch; cc += NTHR / BM) {
             uint4 v = zero4();
-            if (own) {
-                v = load_chunk(src + cc * 8, min(8, d.kc - cc * 8), d.a_vec);
-                if (d.scale != 1.0f) v = scale_chunk(v, d.scale);
-            }
+            if (own) v = load_chunk(src + cc * 8, min(8, d.kc - cc * 8), d.a_vec);
             *reinterpret_cast<uint4*>(lds + row * 128 + ((cc ^ (row & 7)) << 4)) = v;
         }
     }
@@ -267,42 +263,225 @@ __global__ __launch_bounds__(NTHR) void fused_gemm_kernel(GemmArgs g) {
         __builtin_amdgcn_sched_barrier(0);
     };
 
-    // ---- contraction over the frozen weight: whole 64-wide tiles -------------------------------
+    // Direct loads of the contraction over the frozen weight: 4 instructions per wave per operand, each fills 1 KB of LDS.
+    // Address = uniform base (advances one tile per step) + constant per-lane byte offset.  Rows / columns past the edge are
+    // clamped to valid memory (they only feed outputs that are never stored).
     const int nk = g.skip_base ? 0 : g.Kdim / BK;
-    if (nk > 0) {
-        // direct loads: 4 instructions per wave per operand, each fills 1 KB of LDS.  Address = uniform base (advances one
-        // tile per step) + constant per-lane byte offset.  Rows / columns past the edge are clamped to valid memory (they
-        // only feed outputs that are never stored).
-        unsigned oa[4], ob[4];
+    unsigned oa[4], ob[4];
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const int ii = wave * 4 + c;
-            const int row = ii * 8 + (lane >> 3), ch = (lane & 7) ^ (lane >> 3);
-            oa[c] = (unsigned)((int64_t)(min(m0 + row, g.M - 1) - m0) * g.lda + ch * 8) * 2u;
-            if (NN) {
-                const int k = ii * 2 + (lane >> 5);
-                const int chn = (lane & 31) ^ (nn_swz(k) << 1);
-                ob[c] = (unsigned)((int64_t)k * g.ldb + min(n0 + chn * 8, g.Ncols - 8)) * 2u;
-            } else {
-                ob[c] = (unsigned)((int64_t)(min(n0 + row, g.Ncols - 1) - n0) * g.ldb + ch * 8) * 2u;
+    for (int c = 0; c < 4; ++c) {
+        const int ii = wave * 4 + c;
+        const int row = ii * 8 + (lane >> 3), ch = (lane & 7) ^ (lane >> 3);
+        oa[c] = (unsigned)((int64_t)(min(m0 + row, g.M - 1) - m0) * g.lda + ch * 8) * 2u;
+        if (NN) {
+            const int k = ii * 2 + (lane >> 5);
+            const int chn = (lane & 31) ^ (nn_swz(k) << 1);
+            ob[c] = (unsigned)((int64_t)k * g.ldb + min(n0 + chn * 8, g.Ncols - 8)) * 2u;
+        } else {
+            ob[c] = (unsigned)((int64_t)(min(n0 + row, g.Ncols - 1) - n0) * g.ldb + ch * 8) * 2u;
+        }
+    }
+    const char* baseA = reinterpret_cast<const char*>(g.Aop + (int64_t)m0 * g.lda);
+    const char* baseB = NN ? reinterpret_cast<const char*>(g.Bop) : reinterpret_cast<const char*>(g.Bop + (int64_t)n0 * g.ldb);
+    const int64_t astep = (int64_t)BK * 2, bstep = NN ? (int64_t)BK * g.ldb * 2 : (int64_t)BK * 2;
+    const unsigned ldsw = (unsigned)(uintptr_t)lds + wave * 4096;
+    auto dmaA = [&](int stage, int c) { dma16(oa[c], baseA, ldsw + stage * TILE_BYTES + c * 1024); };
+    auto dmaB = [&](int slot, int c) { dma16(ob[c], baseB, ldsw + (B_SLOT0 + slot) * TILE_BYTES + c * 1024); };
+
+    // one masked pass: stage (through registers) into the first row stage and weight slot, then one or two 32-wide MFMA steps
+    auto run_pass = [&](const PassDesc& d) {
+        wait_all_and_barrier();          // outstanding direct loads have landed; nobody reads the buffers any more
+        if (d.isolate) {                 // (uniform) clear the column flags before anybody sets one
+            if (tid <= BN / 4) reinterpret_cast<uint32_t*>(lds + FLAG_OFF)[tid] = 0u;
+            __syncthreads();
+        }
+        stage_pass<NN>(lds, d, m0, n0, g.Ncols, tid);
+        __syncthreads();
+        const int ksteps = (d.kc + 31) / 32;
+        for (int ks = 0; ks < ksteps; ++ks) {
+            rfa(0, ks, 0, 0); rfa(0, ks, 1, 1); rfb(0, ks, 0);
+            mma(0, 0, 0); mma(1, 1, 0);
+        }
+        if (d.isolate && *reinterpret_cast<const uint32_t*>(lds + FLAG_ANY) != 0u) {
+            // the adapter's operand held Inf / NaN in some columns: its own rows of those columns are NaN
+            const float qnan = __uint_as_float(0x7fc00000u);
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const uint32_t f4 = *reinterpret_cast<const uint32_t*>(lds + FLAG_OFF + wn * TN + b * 16 + 4 * g4);
+                if (f4 == 0u) continue;
+#pragma unroll
+                for (int a = 0; a < 8; ++a) {
+                    const int row = m0 + wm * TM + a * 16 + l16;
+                    if (row < d.a_row_lo || row >= d.a_row_hi) continue;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if ((f4 >> (8 * i)) & 0xffu) acc[a][b][i] = qnan;
+                }
             }
         }
-        const char* baseA = reinterpret_cast<const char*>(g.Aop + (int64_t)m0 * g.lda);
-        const char* baseB = NN ? reinterpret_cast<const char*>(g.Bop) : reinterpret_cast<const char*>(g.Bop + (int64_t)n0 * g.ldb);
-        const int64_t astep = (int64_t)BK * 2, bstep = NN ? (int64_t)BK * g.ldb * 2 : (int64_t)BK * 2;
-        const unsigned ldsw = (unsigned)(uintptr_t)lds + wave * 4096;
-        auto dmaA = [&](int stage, int c) { dma16(oa[c], baseA, ldsw + stage * TILE_BYTES + c * 1024); };
-        auto dmaB = [&](int slot, int c) { dma16(ob[c], baseB, ldsw + (B_SLOT0 + slot) * TILE_BYTES + c * 1024); };
+    };
 
+    // ---- rank extension: the LoRA term goes into the accumulators first ------------------------------
+    // acc = s_i (S_i B_i) here, the contraction over the frozen weight is added afterwards: the scale is applied to the fp32
+    // accumulators (rows of S_i reach the MFMAs as stored, one rounding fewer than scaling them in bf16), and the operands of
+    // the passes can be fetched like any other operand tile:
+    //  * A tile whose rows all belong to one adapter with a rank that is a multiple of 8 (nearly every tile of a training
+    //    batch) takes its one or two 64-rank passes as extra K-steps of the main loop's own form: rows of S_i and the
+    //    64 x 256 piece of B_i (backward: dS_i, A_i) come by direct loads into tile buffers in the main loop's layouts -
+    //    no staging registers, no LDS stores - and, for ranks up to 64, together with tile 0 of the frozen weight's
+    //    contraction, so that their latency costs nothing.  Chunks past the rank are fetched from a valid address and
+    //    overwritten with zeros before any MFMA reads them.
+    //  * Any other tile (several adapters, a rank that is not a multiple of 8) stages each adapter's pass through registers
+    //    with the rows of other adapters zeroed, as before.
+    // Both forms feed the same values to the same MFMAs in the same order, so a row's bits do not depend on which one its
+    // tile took.
+    bool tile0_requested = false;
+    if (!g.skip_lora) {
+        const Entry4 tile = g.pv.gemm_tiles[tm];
+        const int row_end = min(g.M, m0 + BM);
+        int owners = 0, one = -1;
+        for (int i = tile.c; i < tile.d; ++i) {
+            if (g.pv.rank[i] == 0) continue;
+            if (max(g.pv.off[i], m0) >= min(g.pv.off[i + 1], m0 + BM)) continue;
+            ++owners; one = i;
+        }
+        bool direct = false;
+        if (owners == 1) {
+            const int r = g.pv.rank[one];
+            direct = g.pv.off[one] <= m0 && g.pv.off[one + 1] >= row_end && (r & 7) == 0 && (g.pv.soff[one] & 7) == 0;
+        }
+        if (direct) {
+            const int i = one;
+            const int r = g.pv.rank[i];
+            const int npass = (r + BK - 1) / BK;                       // 1 or 2
+            const char* sb = reinterpret_cast<const char*>(g.E + g.pv.soff[i] + (int64_t)(m0 - g.pv.off[i]) * r);
+            const u16* F = (const u16*)(NN ? g.pv.ptrs[i].B : g.pv.ptrs[i].A);
+            // pass 0 goes to row stage 1 / weight slot 2, pass 1 to row stage 0 / weight slot 0 (the buffers tile 0 of the main
+            // loop uses: with two passes it is requested after them)
+            if (npass == 1 && nk > 0) {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) dmaA(0, c);
+#pragma unroll
+                for (int c = 0; c < 4; ++c) dmaB(0, c);
+                tile0_requested = true;
+            }
+            for (int p = 0; p < npass; ++p) {
+                const int kc = min(BK, r - p * BK);
+                const int stage = p == 0 ? 1 : 0, slot = p == 0 ? 2 : 0;
+                const char* sbp = sb + p * BK * 2;
+                const char* fbp = NN ? reinterpret_cast<const char*>(F + (int64_t)p * BK * g.Ncols)
+                                     : reinterpret_cast<const char*>(F + (int64_t)n0 * r + p * BK);
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const int ii = wave * 4 + c;
+                    const int row = ii * 8 + (lane >> 3), ch = (lane & 7) ^ (lane >> 3);
+                    const int chv = ch * 8 < kc ? ch : 0;
+                    const unsigned va = (unsigned)((min(m0 + row, g.M - 1) - m0) * r + chv * 8) * 2u;
+                    dma16(va, sbp, ldsw + stage * TILE_BYTES + c * 1024);
+                    unsigned vb;
+                    if (NN) {
+                        const int k = ii * 2 + (lane >> 5);
+                        const int chn = (lane & 31) ^ (nn_swz(k) << 1);
+                        vb = (unsigned)((int64_t)(k < kc ? k : 0) * g.ldb + min(n0 + chn * 8, g.Ncols - 8)) * 2u;
+                    } else {
+                        vb = (unsigned)((min(n0 + row, g.Ncols - 1) - n0) * r + chv * 8) * 2u;
+                    }
+                    dma16(vb, fbp, ldsw + (B_SLOT0 + slot) * TILE_BYTES + c * 1024);
+                }
+            }
+            wait_all_and_barrier();
+            // ranks that are not multiples of 32: zeros over the chunks between the rank and the end of its 32-wide MFMA step
+            bool zeroed = false;
+            for (int p = 0; p < npass; ++p) {
+                const int kc = min(BK, r - p * BK), kpad = (kc + 31) & ~31;
+                if (kc == kpad) continue;
+                zeroed = true;
+                const int stage = p == 0 ? 1 : 0, slot = p == 0 ? 2 : 0;
+                unsigned char* As = lds + stage * TILE_BYTES;
+                unsigned char* Bs = lds + (B_SLOT0 + slot) * TILE_BYTES;
+                const int c0 = kc / 8, nc = (kpad - kc) / 8;
+                for (int idx = tid; idx < BM * nc; idx += NTHR) {
+                    const int row = idx & (BM - 1), cc = c0 + idx / BM;
+                    *reinterpret_cast<uint4*>(As + row * 128 + ((cc ^ (row & 7)) << 4)) = zero4();
+                    if (!NN) *reinterpret_cast<uint4*>(Bs + row * 128 + ((cc ^ (row & 7)) << 4)) = zero4();
+                }
+                if (NN)
+                    for (int idx = tid; idx < (kpad - kc) * 32; idx += NTHR)
+                        *reinterpret_cast<uint4*>(Bs + (kc + idx / 32) * 512 + ((idx & 31) << 4)) = zero4();
+            }
+            if (zeroed) __syncthreads();
+            for (int p = 0; p < npass; ++p) {
+                const int kc = min(BK, r - p * BK);
+                const int stage = p == 0 ? 1 : 0, slot = p == 0 ? 2 : 0;
+                const int ksteps = (kc + 31) / 32;
+                for (int ks = 0; ks < ksteps; ++ks) {
+                    rfa(stage, ks, 0, 0); rfa(stage, ks, 1, 1); rfb(slot, ks, 0);
+                    mma(0, 0, 0); mma(1, 1, 0);
+                }
+            }
+            if (NN) {
+                const float sc = g.pv.scale[i];
+                if (sc != 1.0f) {
+#pragma unroll
+                    for (int a = 0; a < 8; ++a)
+#pragma unroll
+                        for (int b = 0; b < 4; ++b)
+#pragma unroll
+                            for (int q = 0; q < 4; ++q) acc[a][b][q] *= sc;
+                }
+            }
+            wait_all_and_barrier();      // every wavefront is done with the pass buffers before the main loop's loads reuse them
+        } else if (owners > 0) {
+            for (int i = tile.c; i < tile.d; ++i) {
+                const int r = g.pv.rank[i];
+                if (r == 0) continue;
+                const int seg0 = g.pv.off[i], seg1 = g.pv.off[i + 1];
+                const int lo = max(seg0, m0), hi = min(seg1, m0 + BM);
+                if (lo >= hi) continue;
+                const int64_t so = g.pv.soff[i];
+                const u16* F = (const u16*)(NN ? g.pv.ptrs[i].B : g.pv.ptrs[i].A);
+                for (int r0 = 0; r0 < r; r0 += BK) {
+                    PassDesc d;
+                    d.a_src = g.E + so + r0; d.a_ld = r; d.a_row_base = seg0; d.a_row_lo = lo; d.a_row_hi = hi;
+                    d.a_vec = ((r & 7) == 0) && ((so & 7) == 0);
+                    if (NN) { d.b_src = F + (int64_t)r0 * g.Ncols; d.b_ld = g.Ncols; d.b_vec = true; }
+                    else    { d.b_src = F + r0; d.b_ld = r; d.b_vec = ((r & 7) == 0); }
+                    d.kc = min(BK, r - r0);
+                    d.isolate = lo > m0 || hi < row_end;
+                    run_pass(d);
+                }
+                if (NN) {   // this adapter's rows hold nothing but its own term so far: scale them
+                    const float sc = g.pv.scale[i];
+                    if (sc != 1.0f) {
+#pragma unroll
+                        for (int a = 0; a < 8; ++a) {
+                            const int row = m0 + wm * TM + a * 16 + l16;
+                            if (row < lo || row >= hi) continue;
+#pragma unroll
+                            for (int b = 0; b < 4; ++b)
+#pragma unroll
+                                for (int q = 0; q < 4; ++q) acc[a][b][q] *= sc;
+                        }
+                    }
+                }
+            }
+            wait_all_and_barrier();      // as above
+        }
+    }
+
+    // ---- contraction over the frozen weight: whole 64-wide tiles -------------------------------
+    if (nk > 0) {
         // tile 0 of both operands, then the weight tile 1 and the first half of the row tile 1: from here on the
         // order of this wavefront's loads is ... A(t+1) x4, B(t+2) x4, A(t+2) x4, B(t+3) x4 ...  Past the last tile the
         // base pointers stop advancing and the loads fetch the last tile again into buffers nobody reads.
+        if (!tile0_requested) {
 #pragma unroll
-        for (int c = 0; c < 4; ++c) dmaA(0, c);
+            for (int c = 0; c < 4; ++c) dmaA(0, c);
 #pragma unroll
-        for (int c = 0; c < 4; ++c) dmaB(0, c);
+            for (int c = 0; c < 4; ++c) dmaB(0, c);
+        }
         if (nk > 1) { baseA += astep; baseB += bstep; }
-        wait_all_and_barrier();
+        if (!tile0_requested) wait_all_and_barrier();
 #pragma unroll
         for (int c = 0; c < 4; ++c) dmaB(1, c);
         if (nk > 2) baseB += bstep;
@@ -361,74 +540,16 @@ __global__ __launch_bounds__(NTHR) void fused_gemm_kernel(GemmArgs g) {
         }
     }
 
-    // one masked pass: stage into the first row stage and weight slot, then one or two 32-wide MFMA steps
-    auto run_pass = [&](const PassDesc& d) {
-        wait_all_and_barrier();          // outstanding direct loads have landed; nobody reads the buffers any more
-        if (d.isolate) {                 // (uniform) clear the column flags before anybody sets one
-            if (tid <= BN / 4) reinterpret_cast<uint32_t*>(lds + FLAG_OFF)[tid] = 0u;
-            __syncthreads();
-        }
-        stage_pass<NN>(lds, d, m0, n0, g.Ncols, tid);
-        __syncthreads();
-        const int ksteps = (d.kc + 31) / 32;
-        for (int ks = 0; ks < ksteps; ++ks) {
-            rfa(0, ks, 0, 0); rfa(0, ks, 1, 1); rfb(0, ks, 0);
-            mma(0, 0, 0); mma(1, 1, 0);
-        }
-        if (d.isolate && *reinterpret_cast<const uint32_t*>(lds + FLAG_ANY) != 0u) {
-            // the adapter's operand held Inf / NaN in some columns: its own rows of those columns are NaN
-            const float qnan = __uint_as_float(0x7fc00000u);
-#pragma unroll
-            for (int b = 0; b < 4; ++b) {
-                const uint32_t f4 = *reinterpret_cast<const uint32_t*>(lds + FLAG_OFF + wn * TN + b * 16 + 4 * g4);
-                if (f4 == 0u) continue;
-#pragma unroll
-                for (int a = 0; a < 8; ++a) {
-                    const int row = m0 + wm * TM + a * 16 + l16;
-                    if (row < d.a_row_lo || row >= d.a_row_hi) continue;
-#pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        if ((f4 >> (8 * i)) & 0xffu) acc[a][b][i] = qnan;
-                }
-            }
-        }
-    };
-
     // ---- tail of a contraction that is not a multiple of 64 -------------------------------------
     if (!g.skip_base && (g.Kdim % BK) != 0) {
         const int k0 = (g.Kdim / BK) * BK;
         PassDesc d;
         d.a_src = g.Aop + k0; d.a_ld = g.lda; d.a_row_base = 0; d.a_row_lo = m0; d.a_row_hi = min(g.M, m0 + BM);
-        d.a_vec = true; d.scale = 1.0f;
+        d.a_vec = true;
         d.b_src = NN ? g.Bop + (int64_t)k0 * g.ldb : g.Bop + k0; d.b_ld = g.ldb; d.b_vec = true;
         d.kc = g.Kdim - k0;
         d.isolate = false;
         run_pass(d);
-    }
-
-    // ---- rank extension: one masked pass per adapter that owns rows of this tile -----------------
-    if (!g.skip_lora) {
-        const Entry4 tile = g.pv.gemm_tiles[tm];
-        for (int i = tile.c; i < tile.d; ++i) {
-            const int r = g.pv.rank[i];
-            if (r == 0) continue;
-            const int seg0 = g.pv.off[i], seg1 = g.pv.off[i + 1];
-            const int lo = max(seg0, m0), hi = min(seg1, m0 + BM);
-            if (lo >= hi) continue;
-            const int64_t so = g.pv.soff[i];
-            const u16* F = (const u16*)(NN ? g.pv.ptrs[i].B : g.pv.ptrs[i].A);
-            for (int r0 = 0; r0 < r; r0 += BK) {
-                PassDesc d;
-                d.a_src = g.E + so + r0; d.a_ld = r; d.a_row_base = seg0; d.a_row_lo = lo; d.a_row_hi = hi;
-                d.a_vec = ((r & 7) == 0) && ((so & 7) == 0);
-                d.scale = NN ? g.pv.scale[i] : 1.0f;
-                if (NN) { d.b_src = F + (int64_t)r0 * g.Ncols; d.b_ld = g.Ncols; d.b_vec = true; }
-                else    { d.b_src = F + r0; d.b_ld = r; d.b_vec = ((r & 7) == 0); }
-                d.kc = min(BK, r - r0);
-                d.isolate = lo > m0 || hi < min(g.M, m0 + BM);
-                run_pass(d);
-            }
-        }
     }
 
     // ---- epilogue: each wavefront transposes its own sub-tile through LDS; one rounding from fp32 ----
