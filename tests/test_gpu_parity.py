@@ -115,6 +115,20 @@ def test_bf16_contraction_lengths_around_the_two_stage_pipeline(k, n):
     check_full(w)
 
 
+@pytest.mark.parametrize("k,n", [(320, 264), (128, 576)])
+def test_tiles_owned_by_one_adapter_take_every_rank_through_the_direct_loads(k, n):
+    """Segments that are multiples of the 256-row GEMM tile: every tile belongs to one adapter, so its rank extension
+    fetches S_i / B_i (dS_i / A_i) by direct loads.  The ranks cover every case of that path: one and two 64-rank passes,
+    ranks that are multiples of 32 (nothing to zero), ranks that end 8, 16 or 24 short of a 32-wide MFMA step in the first
+    and in the second half of a pass, rank 0 (no pass), and a last segment that ends inside a tile (rows past T).  The
+    scales are not powers of two, so a rounding of s_i S_i to bf16 would show in the per-element bound."""
+    ranks = (8, 24, 40, 56, 72, 104, 120, 128, 64, 32, 0, 16)
+    lens = (256, 512, 256, 256, 512, 256, 256, 256, 256, 512, 256, 256 + 77)
+    scales = [16.0 / 33.0, 3.0, 0.3, 1.7, 16.0 / 72.0, 0.77, 1.0, 2.0, 0.9, 1.1, 5.0, 0.6]
+    w = wl.small_case(seed=81 + k % 3, dtype="bf16", k=k, n=n, ranks=ranks, seg_lens=lens, scales=scales, b_sigma=0.3)
+    check_full(w)
+
+
 def test_bf16_odd_widths_use_fma_kernels():
     w = wl.small_case(seed=35, dtype="bf16", k=100, n=52, ranks=(4, 7, 0, 16), seg_lens=(33, 64, 10, 70),
                       scales=(2.0, 0.5, 1.0, 1.5), b_sigma=0.3)
