@@ -281,8 +281,8 @@ __global__ __launch_bounds__(NTHR) void fused_gemm_kernel(GemmArgs g) {
             ob[c] = (unsigned)((int64_t)(min(n0 + row, g.Ncols - 1) - n0) * g.ldb + ch * 8) * 2u;
         }
     }
-    const char* baseA = reinterpret_cast<const char*>(g.Aop + (int64_t)m0 * g.lda);
-    const char* baseB = NN ? reinterpret_cast<const char*>(g.Bop) : reinterpret_cast<const char*>(g.Bop + (int64_t)n0 * g.ldb);
+    const char* baseA = uniform_ptr(g.Aop + (int64_t)m0 * g.lda);
+    const char* baseB = NN ? uniform_ptr(g.Bop) : uniform_ptr(g.Bop + (int64_t)n0 * g.ldb);
     const int64_t astep = (int64_t)BK * 2, bstep = NN ? (int64_t)BK * g.ldb * 2 : (int64_t)BK * 2;
     const unsigned ldsw = (unsigned)(uintptr_t)lds + wave * 4096;
     auto dmaA = [&](int stage, int c) { dma16(oa[c], baseA, ldsw + stage * TILE_BYTES + c * 1024); };
@@ -368,9 +368,8 @@ __global__ __launch_bounds__(NTHR) void fused_gemm_kernel(GemmArgs g) {
             for (int p = 0; p < npass; ++p) {
                 const int kc = min(BK, r - p * BK);
                 const int stage = p == 0 ? 1 : 0, slot = p == 0 ? 2 : 0;
-                const char* sbp = sb + p * BK * 2;
-                const char* fbp = NN ? reinterpret_cast<const char*>(F + (int64_t)p * BK * g.Ncols)
-                                     : reinterpret_cast<const char*>(F + (int64_t)n0 * r + p * BK);
+                const char* sbp = uniform_ptr(sb + p * BK * 2);
+                const char* fbp = uniform_ptr(NN ? F + (int64_t)p * BK * g.Ncols : F + (int64_t)n0 * r + p * BK);
 #pragma unroll
                 for (int c = 0; c < 4; ++c) {
                     const int ii = wave * 4 + c;
