@@ -498,6 +498,11 @@ def measure_layer(config: int, args, mods, extras: bool, lora_and_base: bool, ce
                 else:
                     kern[name].update(bound="hbm", achieved_gbs=work / t / 1e9, frac=work / t / 1e9 / PEAK_HBM_GBS)
         out["kernels"] = kern
+        # forward and backward by themselves: the sum of their launches' own durations (HIP events around every launch)
+        fwd_names, tot = ("shrink", "gemm_fwd"), lambda nm: kern[nm]["avg_ms"] * kern[nm]["launches_per_step"]
+        if all(nm in kern for nm in fwd_names):
+            out["fwd_ms_kernels"] = float(sum(tot(nm) for nm in fwd_names))
+            out["bwd_ms_kernels"] = float(sum(tot(nm) for nm in kern if nm not in fwd_names))
         traffic, traffic_source = committed_traffic(config)
         named = [nm for nm in kern if nm in alg]
         if not named:
@@ -678,7 +683,7 @@ def main() -> int:
         "config": {"workload": h["workload"], "T": h["T"], "k": h["k"], "n": h["n"], "adapters": h["adapters"],
                    "ranks": h["ranks"], "tokens_per_adapter": h["tokens_per_adapter"], "mode": h["mode"]},
     }
-    for key in ("tflops", "frac_bf16_mfma_peak_whole_step", "kernels", "roofline", "traffic_per_launch_bytes", "lora_path",
+    for key in ("tflops", "frac_bf16_mfma_peak_whole_step", "fwd_ms_kernels", "bwd_ms_kernels", "kernels", "roofline", "traffic_per_launch_bytes", "lora_path",
                 "decoupled", "base_only", "measured_ceilings", "power_clock_under_fused_step", "calib_copy_bytes", "cpu_baseline",
                 "host_input_generation_s"):
         if key in h:
