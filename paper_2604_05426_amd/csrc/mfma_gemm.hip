@@ -180,7 +180,7 @@ __global__ __launch_bounds__(NTHR) void fused_gemm_kernel(GemmArgs g) {
     // bands of that order run interleaved by 32-tile groups (band 0 columns 0-3, band 1 columns 0-3, ..., band 0 columns
     // 4-7, ...): the eight XCDs then cover H bands x 8/H column groups at a time, and one sweep over the weight's column
     // panels serves H bands.  What is left over (a short last band, fewer than H bands, the columns past the last whole
-    // group of four) is numbered band by band as before.
+    // group of four) is numbered band by band.
     constexpr int GM = kGemmBandTiles;
     const int per_band = GM * g.tiles_n;
     const int H = g.band_group;
@@ -332,7 +332,7 @@ __global__ __launch_bounds__(NTHR) void fused_gemm_kernel(GemmArgs g) {
     //    contraction, so that their latency costs nothing.  Chunks past the rank are fetched from a valid address and
     //    overwritten with zeros before any MFMA reads them.
     //  * Any other tile (several adapters, a rank that is not a multiple of 8) stages each adapter's pass through registers
-    //    with the rows of other adapters zeroed, as before.
+    //    with the rows of other adapters zeroed (run_pass).
     // Both forms feed the same values to the same MFMAs in the same order, so a row's bits do not depend on which one its
     // tile took.
     bool tile0_requested = false;
@@ -508,8 +508,8 @@ __global__ __launch_bounds__(NTHR) void fused_gemm_kernel(GemmArgs g) {
             dmaB(bp, 2);
             __builtin_amdgcn_sched_barrier(0);
             // Last quarter before the barrier: this wavefront steps back behind the one it shares the SIMD with.  The two run
-            // the same instruction stream and the issue arbiter prefers the older one, so one of them used to reach the barrier
-            // half a tile early and the other finished alone, with nobody to fill the gaps behind its own LDS reads and load
+            // the same instruction stream and the issue arbiter prefers the older one, so without this one of them reaches the barrier
+            // half a tile early and the other finishes alone, with nobody to fill the gaps behind its own LDS reads and load
             // issue.  With the priority dropped here the one that is behind gets the matrix pipe first and both arrive
             // together (backward GEMM 1.7-2 % faster, forward unchanged).
             __builtin_amdgcn_s_setprio(0);

@@ -14,7 +14,7 @@ namespace mlora {
 // dShrink:  dS_i = s_i dY_i B_i^T     (!FWD: B_i is [r][n], contraction contiguous)
 // One workgroup per row block (64 rows of one adapter), 8 wavefronts.  Two bodies: the GEMM-tiled one further down
 // (shrink_tiled_body) serves contractions that are multiples of 64 and, in the forward form, ranks that are multiples
-// of 4; the register-staged one below is the first design and remains for everything else.  Register-staged body: the
+// of 4; the register-staged one below takes everything else.  Register-staged body: the
 // work is a pure stream of X (or dY), so it is built for bytes in flight: every wavefront owns a
 // contiguous slice of the contraction and runs its own register-prefetch -> private LDS tile
 // -> MFMA pipeline with no workgroup barrier in the loop, so eight independent streams per
