@@ -172,3 +172,14 @@ def test_grouped_row_bands_change_the_tile_order_and_no_bit(k, n, total):
     assert rel_fro(to_host(dl.Y[rows.tolist()]), fw.Y) < 1e-2 and row_rel_max(to_host(dl.Y[rows.tolist()]), fw.Y) <= 1e-2
     assert rel_fro(to_host(dl.dX[rows.tolist()]), bw.dX) < 1e-2 and row_rel_max(to_host(dl.dX[rows.tolist()]), bw.dX) <= 1e-2
     dl.plan.destroy()
+
+
+def test_grouped_row_bands_flag_is_accepted_and_ignored_by_the_fp32_path():
+    w = wl.small_case(seed=93, dtype="f32", k=96, n=72, ranks=(4, 16), seg_lens=(150, 300), scales=(2.0, 0.5), b_sigma=0.3)
+    dl = DeviceLayer(w)
+    dl.forward(); dl.backward(); dl.sync()
+    plain = [t.clone() for t in (dl.Y, dl.dX, *dl.dA, *dl.dB)]
+    dl.forward(ml.FLAG_GROUP_BANDS); dl.backward(ml.FLAG_GROUP_BANDS); dl.sync()
+    for a, b in zip(plain, (dl.Y, dl.dX, *dl.dA, *dl.dB)):
+        assert torch.equal(a.contiguous().view(torch.int32), b.contiguous().view(torch.int32))
+    dl.plan.destroy()
