@@ -17,8 +17,8 @@ A_i ~ N(0, 1/k).  For bf16 workloads each array is then rounded once to bf16
 """
 from __future__ import annotations
 
-from dataclasses import dataclass, field
-from typing import Dict, List, Optional, Sequence
+from dataclasses import dataclass
+from typing import List, Optional, Sequence
 
 import numpy as np
 
