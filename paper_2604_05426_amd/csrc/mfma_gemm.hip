@@ -59,7 +59,7 @@ struct GemmArgs {
     const u16* E;                  // ragged S (fwd) or dS (bwd)
     int32_t M, Ncols, Kdim;
     int32_t tiles_m, tiles_n;
-    int32_t skip_base, skip_lora, accumulate;
+    int32_t skip_lora;             // MLORA_FLAG_BASE_ONLY, or a plan without adapters (the LoRA-only mode has a kernel of its own)
     int32_t stream_out;            // write the output with streaming stores (see launch_gemm)
     int32_t band_group;            // bands whose column groups are interleaved (see the tile order)
     PlanView pv;
@@ -266,7 +266,7 @@ __global__ __launch_bounds__(NTHR) void fused_gemm_kernel(GemmArgs g) {
     // Direct loads of the contraction over the frozen weight: 4 instructions per wave per operand, each fills 1 KB of LDS.
     // Address = uniform base (advances one tile per step) + constant per-lane byte offset.  Rows / columns past the edge are
     // clamped to valid memory (they only feed outputs that are never stored).
-    const int nk = g.skip_base ? 0 : g.Kdim / BK;
+    const int nk = g.Kdim / BK;
     unsigned oa[4], ob[4];
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
@@ -540,7 +540,7 @@ __global__ __launch_bounds__(NTHR) void fused_gemm_kernel(GemmArgs g) {
     }
 
     // ---- tail of a contraction that is not a multiple of 64 -------------------------------------
-    if (!g.skip_base && (g.Kdim % BK) != 0) {
+    if ((g.Kdim % BK) != 0) {
         const int k0 = (g.Kdim / BK) * BK;
         PassDesc d;
         d.a_src = g.Aop + k0; d.a_ld = g.lda; d.a_row_base = 0; d.a_row_lo = m0; d.a_row_hi = min(g.M, m0 + BM);
@@ -573,18 +573,8 @@ __global__ __launch_bounds__(NTHR) void fused_gemm_kernel(GemmArgs g) {
             const int rr = it * RPI + lane / CPR, c = lane % CPR;
             const int row = m0 + wm * TM + rr, col = n0 + wn * TN + c * 8;
             if (row >= g.M || col >= g.Ncols) continue;   // Ncols is a multiple of 8: chunks are all-in or all-out
-            uint4 v = *reinterpret_cast<const uint4*>(Es + rr * E_LD + c * 8);
+            const uint4 v = *reinterpret_cast<const uint4*>(Es + rr * E_LD + c * 8);
             u16* dst = g.C + (int64_t)row * g.ldc + col;
-            if (g.accumulate) {   // in-place LoRA-only mode: add what the output already holds, round once more
-                const uint4 old = *reinterpret_cast<const uint4*>(dst);
-                const uint32_t nv[4] = {v.x, v.y, v.z, v.w}, ov[4] = {old.x, old.y, old.z, old.w};
-                uint32_t res[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    res[e] = pack2(__uint_as_float(nv[e] << 16) + __uint_as_float(ov[e] << 16),
-                                   __uint_as_float(nv[e] & 0xffff0000u) + __uint_as_float(ov[e] & 0xffff0000u));
-                v = make_uint4(res[0], res[1], res[2], res[3]);
-            }
             if (g.stream_out) store_streaming(dst, v);
             else *reinterpret_cast<uint4*>(dst) = v;
         }
@@ -610,9 +600,7 @@ static int launch_gemm(mlora_plan* p, bool fwd, const void* Aop, const void* W, 
     else     { g.lda = p->n; g.ldc = p->k; g.Ncols = (int32_t)p->k; g.Kdim = (int32_t)p->n; }
     g.tiles_m = (g.M + BM - 1) / BM;
     g.tiles_n = (g.Ncols + BN - 1) / BN;
-    g.skip_base = (flags & MLORA_FLAG_LORA_ONLY) ? 1 : 0;
     g.skip_lora = ((flags & MLORA_FLAG_BASE_ONLY) || p->N == 0) ? 1 : 0;
-    g.accumulate = g.skip_base;
     // Streaming stores: an output written with ordinary stores sits dirty in the caches when the kernel ends and is
     // written back underneath the next kernel, which is always a memory-bound one (dShrink after the forward and the
     // weight gradients after the backward ran up to a third slower).

@@ -45,7 +45,6 @@ __global__ __launch_bounds__(kScanThreads) void plan_scan_kernel(
         int64_t* soff, int32_t* rb_start, int32_t* cb_start, int32_t* cb_pos,
         int32_t* wc_start, int32_t* wc_pos, int64_t* part_off, int32_t* reduce_list, DevGeo* geo) {
     __shared__ int64_t red[kScanThreads];
-    __shared__ int32_t chosen[2];
     const int tid = threadIdx.x;
     // items of one launch if the tokens of class `cls` (0: every adapter, 1: narrow ranks, 2: wide ranks) are cut every `chunk`
     auto count_items = [&](int64_t chunk, int cls) -> int64_t {
