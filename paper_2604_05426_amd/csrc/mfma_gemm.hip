@@ -241,6 +241,18 @@ __global__ __launch_bounds__(NTHR) void fused_gemm_kernel(GemmArgs g) {
             }
         }
     };
+    auto rfbh = [&](int slot, int k32, int buf, int h) {     // half of rfb: column blocks 2 h, 2 h + 1
+        const unsigned char* bbase = lds + (B_SLOT0 + slot) * TILE_BYTES;
+#pragma unroll
+        for (int b = 2 * h; b < 2 * h + 2; ++b) {
+            if (NN) {
+                const unsigned char* p = bbase + bnn_off + k32 * 32 * 512 + (((wn * 4 + b) ^ vq) << 5);
+                fb[buf][b] = lds_read_frag_tr(reinterpret_cast<const u16*>(p), reinterpret_cast<const u16*>(p + 4 * 512));
+            } else {
+                fb[buf][b] = lds_read_frag(reinterpret_cast<const u16*>(bbase + (k32 ? bnt_off1 : bnt_off0) + b * 16 * 128));
+            }
+        }
+    };
     // operands swapped: each accumulator block holds the transposed 16x16 block (lane = output row, 4 consecutive columns)
     auto mma = [&](int half, int abuf, int bbuf) {
 #pragma unroll
@@ -501,10 +513,10 @@ __global__ __launch_bounds__(NTHR) void fused_gemm_kernel(GemmArgs g) {
             mma8(0, 0, 0, 2); __builtin_amdgcn_sched_barrier(0);
             dmaB(bp, 0);
             __builtin_amdgcn_sched_barrier(0);
-            rfa(cur, 1, 0, 0); rfb(bs, 1, 1); mma8(1, 1, 0, 0); interleave(4 + NDSB);
+            rfa(cur, 1, 0, 0); rfbh(bs, 1, 1, 0); mma8(1, 1, 0, 0); interleave(4 + NDSB / 2);
             dmaB(bp, 1);
             __builtin_amdgcn_sched_barrier(0);
-            mma8(1, 1, 0, 2); __builtin_amdgcn_sched_barrier(0);
+            rfbh(bs, 1, 1, 1); mma8(1, 1, 0, 2); interleave(NDSB / 2);
             dmaB(bp, 2);
             __builtin_amdgcn_sched_barrier(0);
             // Last quarter before the barrier: this wavefront steps back behind the one it shares the SIMD with.  The two run
@@ -524,10 +536,12 @@ __global__ __launch_bounds__(NTHR) void fused_gemm_kernel(GemmArgs g) {
             __builtin_amdgcn_s_setprio(3);
             dmaA(cur, 0);
             __builtin_amdgcn_sched_barrier(0);
-            rfa(cur ^ 1, 0, 0, 0); rfb(bn, 0, 0); mma8(1, 1, 1, 0); interleave(4 + NDSB);
+            // (the fragments of the weight operand are read in two halves, one with each group of 8 MFMAs: the forward's
+            // transposing reads are two instructions per fragment, and sixteen of them in one group held the MFMAs up)
+            rfa(cur ^ 1, 0, 0, 0); rfbh(bn, 0, 0, 0); mma8(1, 1, 1, 0); interleave(4 + NDSB / 2);
             dmaA(cur, 1);
             __builtin_amdgcn_sched_barrier(0);
-            mma8(1, 1, 1, 2); __builtin_amdgcn_sched_barrier(0);
+            rfbh(bn, 0, 0, 1); mma8(1, 1, 1, 2); interleave(NDSB / 2);
             bs = bn;
         }
         {
